@@ -1,0 +1,533 @@
+"""Pins for the CPU oracle: finite differences, closed forms, invariants,
+brute force and library routines.  None of these call the HIP path.
+
+Paper passages: Sec. 3.1 (which attention gradients stay sparse; Eq. 3-4),
+Sec. 3.2 (row-sparse G, the two GEMM types), Sec. 2.1 Eq. 2 (mask = 1 for a
+selected token)."""
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import layer_oracle as O
+from paper_2502_00340_amd import workloads as WL
+
+TINY = dict(B=2, S=6, H=16, Hq=4, Hkv=2, d=8, F=24)
+
+
+def _tiny_problem(seed=0, dtype=np.float64, **over):
+    c = dict(TINY, **over)
+    rng = np.random.default_rng(seed)
+    T = c["B"] * c["S"]
+    Nq, Nkv = c["Hq"] * c["d"], c["Hkv"] * c["d"]
+    W = {
+        "wq": rng.standard_normal((c["H"], Nq)) * 0.3, "wk": rng.standard_normal((c["H"], Nkv)) * 0.3,
+        "wv": rng.standard_normal((c["H"], Nkv)) * 0.3, "wo": rng.standard_normal((Nq, c["H"])) * 0.3,
+        "wg": rng.standard_normal((c["H"], c["F"])) * 0.3, "wu": rng.standard_normal((c["H"], c["F"])) * 0.3,
+        "wd": rng.standard_normal((c["F"], c["H"])) * 0.3,
+        "g1": 1.0 + 0.1 * rng.standard_normal(c["H"]), "g2": 1.0 + 0.1 * rng.standard_normal(c["H"]),
+    }
+    W = {k: v.astype(dtype) for k, v in W.items()}
+    x = rng.standard_normal((T, c["H"])).astype(dtype)
+    dy = rng.standard_normal((T, c["H"])).astype(dtype)
+    mask = (rng.random((c["B"], c["S"])) < 0.5).astype(np.uint8)
+    mask[0, -1] = 1
+    mask[0, 0] = 0
+    return c, W, x, dy, mask
+
+
+def _kw(c):
+    return dict(B=c["B"], S=c["S"], Hq=c["Hq"], Hkv=c["Hkv"], d=c["d"])
+
+
+def _fd(fun, arr, eps=1e-6):
+    """Central finite differences of the scalar fun() wrt every entry of arr."""
+    g = np.zeros_like(arr)
+    it = np.nditer(arr, flags=["multi_index"])
+    for _ in it:
+        i = it.multi_index
+        old = arr[i]
+        arr[i] = old + eps
+        fp = fun()
+        arr[i] = old - eps
+        fm = fun()
+        arr[i] = old
+        g[i] = (fp - fm) / (2 * eps)
+    return g
+
+
+def _relerr(a, b):
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+# ---------------------------------------------------------------------------
+# dense mode == gradient of the forward (finite differences, float64)
+# ---------------------------------------------------------------------------
+
+def test_dense_backward_matches_finite_differences():
+    c, W, x, dy, _ = _tiny_problem(1)
+    kw = _kw(c)
+    y, saved = O.layer_fwd(x, W, **kw)
+    got = O.layer_bwd(saved, W, dy, None, **kw)
+
+    def loss():
+        yy, _ = O.layer_fwd(x, W, **kw)
+        return float(np.sum(yy * dy))
+
+    assert _relerr(got["dx"], _fd(loss, x)) < 1e-6
+    for name in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g1", "g2"):
+        fd = _fd(loss, W[name])
+        assert _relerr(got["d" + name], fd) < 1e-6, name
+
+
+def test_float32_oracle_agrees_with_float64():
+    c, W, x, dy, mask = _tiny_problem(2)
+    kw = _kw(c)
+    _, saved = O.layer_fwd(x, W, **kw)
+    ref = O.layer_bwd(saved, W, dy, mask, **kw)
+    W32 = {k: v.astype(np.float32) for k, v in W.items()}
+    saved32 = {k: v.astype(np.float32) for k, v in saved.items()}
+    got = O.layer_bwd(saved32, W32, dy.astype(np.float32), mask, **kw)
+    for k in ref:
+        assert got[k].dtype == np.float32
+        assert _relerr(got[k].astype(np.float64), ref[k]) < 1e-5, k
+
+
+# ---------------------------------------------------------------------------
+# filtered mode == gradient of a forward in which (1) only kept rows of y
+# enter the loss and (2) keys/values of filtered tokens are constants
+# ---------------------------------------------------------------------------
+
+def _fwd_frozen_kv(x, W, x0, W0, mask, c, eps=1e-5):
+    """Layer forward whose key/value rows of filtered tokens come from the
+    frozen copies (x0, W0): differentiating it wrt (x, W) cuts exactly the
+    paths that masking point (2) cuts."""
+    kw = _kw(c)
+    M = mask.reshape(-1, 1).astype(x.dtype)
+    h1, _ = O.rmsnorm_fwd(x, W["g1"], eps)
+    h10, _ = O.rmsnorm_fwd(x0, W0["g1"], eps)
+    q = h1 @ W["wq"]
+    k = M * (h1 @ W["wk"]) + (1 - M) * (h10 @ W0["wk"])
+    v = M * (h1 @ W["wv"]) + (1 - M) * (h10 @ W0["wv"])
+    a, _ = O.attn_fwd(q, k, v, scale=1.0 / math.sqrt(c["d"]), **kw)
+    r = x + a @ W["wo"]
+    h2, _ = O.rmsnorm_fwd(r, W["g2"], eps)
+    return r + (O.silu(h2 @ W["wg"]) * (h2 @ W["wu"])) @ W["wd"]
+
+
+@pytest.mark.parametrize("seed", [3, 4])
+def test_filtered_backward_matches_finite_differences_of_frozen_kv_forward(seed):
+    c, W, x, dy, mask = _tiny_problem(seed)
+    kw = _kw(c)
+    _, saved = O.layer_fwd(x, W, **kw)
+    got = O.layer_bwd(saved, W, dy, mask, **kw)
+    x0 = x.copy()
+    W0 = {k: v.copy() for k, v in W.items()}
+    M = mask.reshape(-1, 1).astype(np.float64)
+
+    def loss():
+        return float(np.sum(_fwd_frozen_kv(x, W, x0, W0, mask, c) * dy * M))
+
+    assert _relerr(got["dx"], _fd(loss, x)) < 1e-6
+    for name in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g1", "g2"):
+        assert _relerr(got["d" + name], _fd(loss, W[name])) < 1e-6, name
+
+
+# ---------------------------------------------------------------------------
+# invariants the method states
+# ---------------------------------------------------------------------------
+
+def test_keep_ratio_one_is_bit_identical_to_dense():
+    c, W, x, dy, _ = _tiny_problem(5)
+    kw = _kw(c)
+    _, saved = O.layer_fwd(x, W, **kw)
+    ones = np.ones((c["B"], c["S"]), dtype=np.uint8)
+    a = O.layer_bwd(saved, W, dy, ones, **kw)
+    b = O.layer_bwd(saved, W, dy, None, **kw)
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+
+
+def test_dx_rows_of_filtered_tokens_are_exactly_zero():
+    c, W, x, dy, mask = _tiny_problem(6)
+    kw = _kw(c)
+    _, saved = O.layer_fwd(x, W, **kw)
+    out = O.layer_bwd(saved, W, dy, mask, **kw)
+    dead = mask.reshape(-1) == 0
+    assert dead.any() and (~dead).any()
+    for k in ("dx", "_dr", "_da", "_dq", "_dk", "_dv"):
+        assert np.all(out[k][dead] == 0.0), k
+        assert np.all(np.abs(out[k][~dead]).sum(axis=1) > 0), k
+
+
+def test_single_linear_dw_equals_dense_dw_with_filtered_dy_rows_zeroed():
+    rng = np.random.default_rng(7)
+    T, I, Oo = 20, 5, 7
+    x = rng.standard_normal((T, I))
+    dy = rng.standard_normal((T, Oo))
+    w = rng.standard_normal((I, Oo))
+    keep = (rng.random(T) < 0.5).astype(np.uint8)
+    dx, dw = O.linear_bwd(x, dy, w, keep)
+    dyz = dy.copy()
+    dyz[keep == 0] = 0
+    # brute force triple loops
+    dw_ref = np.zeros((I, Oo))
+    dx_ref = np.zeros((T, I))
+    for t in range(T):
+        for i in range(I):
+            for o in range(Oo):
+                dw_ref[i, o] += x[t, i] * dyz[t, o]
+                dx_ref[t, i] += dyz[t, o] * w[i, o]
+    assert np.allclose(dw, dw_ref, rtol=1e-12, atol=1e-12)
+    assert np.allclose(dx, dx_ref, rtol=1e-12, atol=1e-12)
+    assert np.all(dx[keep == 0] == 0)
+    # compact form: the same sums over the kept rows only
+    kept = np.flatnonzero(keep)
+    assert np.allclose(dw, x[kept].T @ dy[kept], rtol=1e-12, atol=1e-12)
+
+
+def test_layer_level_which_outputs_depend_on_masking_point_two():
+    """dWd, dWg, dWu, dWo, dWq, dg2 follow from masking the upstream gradient
+    alone; dWk, dWv, dg1, dx also need the dK/dV row drop, and must differ
+    from the one-mask result (otherwise that drop would be dead code)."""
+    c, W, x, dy, mask = _tiny_problem(8)
+    kw = _kw(c)
+    _, saved = O.layer_fwd(x, W, **kw)
+    two = O.layer_bwd(saved, W, dy, mask, **kw)
+    M = mask.reshape(-1, 1).astype(np.float64)
+    one = O.layer_bwd(saved, W, dy * M, None, **kw)       # dense backward of the masked gradient
+    for k in ("dwd", "dwg", "dwu", "dwo", "dwq", "dg2"):
+        assert _relerr(two[k], one[k]) < 1e-12, k
+    for k in ("dwk", "dwv", "dg1", "dx"):
+        assert _relerr(two[k], one[k]) > 1e-3, k
+    # one-mask dx is dense: filtered rows receive gradient through K and V
+    assert np.abs(one["dx"][mask.reshape(-1) == 0]).sum() > 0
+
+
+# ---------------------------------------------------------------------------
+# attention: closed forms, identities, Eq. 3 + Eq. 4 written out, strawman
+# ---------------------------------------------------------------------------
+
+def _attn_problem(seed, B=2, S=9, Hq=4, Hkv=2, d=8):
+    rng = np.random.default_rng(seed)
+    T = B * S
+    q = rng.standard_normal((T, Hq * d))
+    k = rng.standard_normal((T, Hkv * d))
+    v = rng.standard_normal((T, Hkv * d))
+    da = rng.standard_normal((T, Hq * d))
+    mask = (rng.random((B, S)) < 0.5).astype(np.uint8)
+    mask[:, -1] = 1
+    mask[:, 0] = 0
+    kw = dict(B=B, S=S, Hq=Hq, Hkv=Hkv, d=d)
+    return q, k, v, da, mask, kw
+
+
+def test_attention_forward_closed_form_zero_queries():
+    q, k, v, _, _, kw = _attn_problem(10)
+    a, lse = O.attn_fwd(np.zeros_like(q), k, v, scale=0.7, **kw)
+    B, S, Hq, Hkv, d = kw["B"], kw["S"], kw["Hq"], kw["Hkv"], kw["d"]
+    for b in range(B):
+        for s in range(S):
+            assert np.allclose(lse[b, :, s], math.log(s + 1))
+            for h in range(Hq):
+                g = h // (Hq // Hkv)
+                mean_v = v[b * S:b * S + s + 1, g * d:(g + 1) * d].mean(axis=0)
+                assert np.allclose(a[b * S + s, h * d:(h + 1) * d], mean_v)
+
+
+def test_attention_forward_and_dense_backward_match_torch_autograd():
+    q, k, v, da, _, kw = _attn_problem(11)
+    B, S, Hq, Hkv, d = kw["B"], kw["S"], kw["Hq"], kw["Hkv"], kw["d"]
+    scale = 1.0 / math.sqrt(d)
+    a, lse = O.attn_fwd(q, k, v, scale=scale, **kw)
+    dq, dk, dv = O.attn_bwd(q, k, v, a, lse, da, scale=scale, **kw)
+    tq = torch.tensor(q.reshape(B, S, Hq, d).transpose(0, 2, 1, 3).copy(), requires_grad=True)
+    tk = torch.tensor(k.reshape(B, S, Hkv, d).transpose(0, 2, 1, 3).copy(), requires_grad=True)
+    tv = torch.tensor(v.reshape(B, S, Hkv, d).transpose(0, 2, 1, 3).copy(), requires_grad=True)
+    G = Hq // Hkv
+    out = torch.nn.functional.scaled_dot_product_attention(
+        tq, tk.repeat_interleave(G, dim=1), tv.repeat_interleave(G, dim=1), is_causal=True)
+    tda = torch.tensor(da.reshape(B, S, Hq, d).transpose(0, 2, 1, 3).copy())
+    out.backward(tda)
+    back = lambda t, Hh: t.detach().numpy().transpose(0, 2, 1, 3).reshape(B * S, Hh * d)
+    assert _relerr(a, back(out, Hq)) < 1e-12
+    assert _relerr(dq, back(tq.grad, Hq)) < 1e-12
+    assert _relerr(dk, back(tk.grad, Hkv)) < 1e-12
+    assert _relerr(dv, back(tv.grad, Hkv)) < 1e-12
+    # lse against a library logsumexp
+    sc = torch.einsum("bhid,bhjd->bhij", tq.detach(), tk.detach().repeat_interleave(G, dim=1)) * scale
+    sc = sc.masked_fill(torch.triu(torch.ones(S, S, dtype=torch.bool), 1), float("-inf"))
+    assert np.allclose(lse, torch.logsumexp(sc, dim=-1).numpy(), rtol=1e-12, atol=1e-12)
+
+
+def test_attention_row_identities():
+    q, k, v, da, _, kw = _attn_problem(12)
+    B, S, Hq, Hkv, d = kw["B"], kw["S"], kw["Hq"], kw["Hkv"], kw["d"]
+    scale = 1.0 / math.sqrt(d)
+    a, lse = O.attn_fwd(q, k, v, scale=scale, **kw)
+    for b in range(B):
+        for h in range(Hq):
+            g = h // (Hq // Hkv)
+            rows = slice(b * S, (b + 1) * S)
+            Q, K, V = q[rows, h * d:(h + 1) * d], k[rows, g * d:(g + 1) * d], v[rows, g * d:(g + 1) * d]
+            P = np.tril(np.exp(Q @ K.T * scale - lse[b, h][:, None]))
+            assert np.allclose(P.sum(axis=1), 1.0)
+            dO = da[rows, h * d:(h + 1) * d]
+            dP = dO @ V.T
+            D_def = np.sum(P * dP, axis=1)                      # sum_j P_ij dP_ij
+            D_used = np.sum(dO * a[rows, h * d:(h + 1) * d], axis=1)   # rowsum(dO * O)
+            assert np.allclose(D_def, D_used)
+            dS = P * (dP - D_used[:, None])
+            assert np.allclose(dS.sum(axis=1), 0.0, atol=1e-12)
+
+
+def _eq3_eq4_literal(q, k, v, a, lse, da, mask, B, S, Hq, Hkv, d, scale):
+    """Eq. 3 and Eq. 4 evaluated as printed, on explicitly partitioned tensors:
+    hat = remaining tokens, check = filtered tokens.  Causality is applied on
+    original positions.  Returns compact (dq, dk, dv) per sequence, stacked."""
+    G = Hq // Hkv
+    dq_all, dk_all, dv_all = [], [], []
+    for b in range(B):
+        kept = np.flatnonzero(mask[b])
+        filt = np.flatnonzero(mask[b] == 0)
+        base = b * S
+        dqb = np.zeros((len(kept), Hq * d))
+        dkb = np.zeros((len(kept), Hkv * d))
+        dvb = np.zeros((len(kept), Hkv * d))
+        for h in range(Hq):
+            g = h // G
+            cq, ck = slice(h * d, (h + 1) * d), slice(g * d, (g + 1) * d)
+            Qh = q[base + kept, cq]
+            dOh = da[base + kept, cq]
+            Oh = a[base + kept, cq]
+            LSEh = lse[b, h, kept][:, None]
+            Dh = np.sum(dOh * Oh, axis=1, keepdims=True)
+            # part 1 (Eq. 3): remaining queries x remaining keys
+            Kh, Vh = k[base + kept, ck], v[base + kept, ck]
+            allow = kept[None, :] <= kept[:, None]
+            Ph = np.where(allow, np.exp(Qh @ Kh.T * scale - LSEh), 0.0)
+            dSh = Ph * (dOh @ Vh.T - Dh)
+            dkb[:, ck] += dSh.T @ Qh * scale
+            dvb[:, ck] += Ph.T @ dOh
+            part1 = dSh @ Kh
+            # part 2 (Eq. 4): remaining queries x filtered keys
+            Kc, Vc = k[base + filt, ck], v[base + filt, ck]
+            allow = filt[None, :] <= kept[:, None]
+            Pc = np.where(allow, np.exp(Qh @ Kc.T * scale - LSEh), 0.0)
+            dSc = Pc * (dOh @ Vc.T - Dh)
+            dqb[:, cq] = (part1 + dSc @ Kc) * scale
+        dq_all.append(dqb), dk_all.append(dkb), dv_all.append(dvb)
+    return np.concatenate(dq_all), np.concatenate(dk_all), np.concatenate(dv_all)
+
+
+@pytest.mark.parametrize("seed", [13, 14])
+def test_single_pass_equals_eq3_plus_eq4_written_out(seed):
+    q, k, v, da, mask, kw = _attn_problem(seed)
+    scale = 1.0 / math.sqrt(kw["d"])
+    a, lse = O.attn_fwd(q, k, v, scale=scale, **kw)
+    dq, dk, dv = O.attn_bwd_filtered(q, k, v, a, lse, da, mask, **kw)
+    cq, ck, cv = _eq3_eq4_literal(q, k, v, a, lse, da, mask, scale=scale, **kw)
+    idx = np.flatnonzero(mask.reshape(-1))
+    assert _relerr(dq[idx], cq) < 1e-12
+    assert _relerr(dk[idx], ck) < 1e-12
+    assert _relerr(dv[idx], cv) < 1e-12
+    dead = mask.reshape(-1) == 0
+    assert np.all(dq[dead] == 0) and np.all(dk[dead] == 0) and np.all(dv[dead] == 0)
+    # kept rows agree with the dense attention backward fed the masked gradient
+    M = mask.reshape(-1, 1).astype(np.float64)
+    dq_d, dk_d, dv_d = O.attn_bwd(q, k, v, a, lse, da * M, scale=scale, **kw)
+    assert _relerr(dq[idx], dq_d[idx]) < 1e-14
+    assert _relerr(dk[idx], dk_d[idx]) < 1e-14
+    assert np.abs(dk_d[dead]).sum() > 0        # the dense one is not row-sparse
+
+
+def test_strawman_prefiltered_kv_corrupts_dq():
+    """Negative control (Sec. 2.2 / 3.1): dropping the filtered tokens' K and V
+    before the backward changes dQ by O(1), so the parity tests can see the
+    failure the paper is about."""
+    q, k, v, da, mask, kw = _attn_problem(15)
+    scale = 1.0 / math.sqrt(kw["d"])
+    a, lse = O.attn_fwd(q, k, v, scale=scale, **kw)
+    dq, _, _ = O.attn_bwd_filtered(q, k, v, a, lse, da, mask, **kw)
+    cq, _, _ = _eq3_only_dq(q, k, v, a, lse, da, mask, scale=scale, **kw)
+    idx = np.flatnonzero(mask.reshape(-1))
+    assert _relerr(cq, dq[idx]) > 0.1
+
+
+def _eq3_only_dq(q, k, v, a, lse, da, mask, B, S, Hq, Hkv, d, scale):
+    """Strawman: only the remaining keys/values are visible to the backward."""
+    G = Hq // Hkv
+    outs = []
+    for b in range(B):
+        kept = np.flatnonzero(mask[b])
+        base = b * S
+        dqb = np.zeros((len(kept), Hq * d))
+        for h in range(Hq):
+            g = h // G
+            cq, ck = slice(h * d, (h + 1) * d), slice(g * d, (g + 1) * d)
+            Qh, dOh, Oh = q[base + kept, cq], da[base + kept, cq], a[base + kept, cq]
+            Kh, Vh = k[base + kept, ck], v[base + kept, ck]
+            allow = kept[None, :] <= kept[:, None]
+            Ph = np.where(allow, np.exp(Qh @ Kh.T * scale - lse[b, h, kept][:, None]), 0.0)
+            dSh = Ph * (dOh @ Vh.T - np.sum(dOh * Oh, axis=1, keepdims=True))
+            dqb[:, cq] = dSh @ Kh * scale
+        outs.append(dqb)
+    return np.concatenate(outs), None, None
+
+
+def _parse(v):
+    """Golden numbers may be written symbolically ("0.75*ln3")."""
+    if isinstance(v, list):
+        return [_parse(e) for e in v]
+    if isinstance(v, str):
+        return eval(v, {"__builtins__": {}}, {"ln3": math.log(3.0), "ln4": math.log(4.0)})
+    return v
+
+
+def test_hand_worked_two_token_example():
+    path = os.path.join(os.path.dirname(__file__), "golden", "attn_two_token.json")
+    g = json.load(open(path))
+    kw = dict(B=g["B"], S=g["S"], Hq=g["Hq"], Hkv=g["Hkv"], d=g["d"])
+    q, k, v = (np.array(_parse(g[n]), dtype=np.float64) for n in ("q", "k", "v"))
+    da = np.array(g["da"], dtype=np.float64)
+    mask = np.array(g["mask"], dtype=np.uint8)
+    e = {n: np.array(_parse(val), dtype=np.float64) for n, val in g["expect"].items()}
+    a, lse = O.attn_fwd(q, k, v, scale=g["scale"], **kw)
+    assert np.allclose(a, e["attn_out"], atol=1e-14)
+    assert np.allclose(lse, e["lse"], atol=1e-14)
+    dq, dk, dv = O.attn_bwd_filtered(q, k, v, a, lse, da, mask, scale=g["scale"], **kw)
+    assert np.allclose(dq, e["dq"], atol=1e-14)
+    assert np.allclose(dk, e["dk"], atol=1e-14)
+    assert np.allclose(dv, e["dv"], atol=1e-14)
+    # without the row drop token 0 would receive the gradients noted in the fixture
+    m1 = np.array([[0.0], [1.0]])
+    _, dk_u, dv_u = O.attn_bwd(q, k, v, a, lse, da * m1, scale=g["scale"], **kw)
+    assert np.isclose(dk_u[0, 0], e["dk_unfiltered_row0"]) and np.isclose(dv_u[0, 0], e["dv_unfiltered_row0"])
+
+
+# ---------------------------------------------------------------------------
+# row-local pieces: closed forms
+# ---------------------------------------------------------------------------
+
+def test_swiglu_backward_closed_forms():
+    d_act = np.array([[2.0, -3.0]])
+    up = np.array([[5.0, 7.0]])
+    # gate = 0: silu'(0) = 1/2, silu(0) = 0
+    dg, du = O.swiglu_bwd(d_act, np.zeros((1, 2)), up)
+    assert np.allclose(dg, d_act * up * 0.5) and np.allclose(du, 0.0)
+    # large gate: silu(z) -> z, silu'(z) -> 1
+    dg, du = O.swiglu_bwd(d_act, np.full((1, 2), 40.0), up)
+    assert np.allclose(dg, d_act * up) and np.allclose(du, d_act * 40.0)
+    assert np.isclose(O.silu(np.array(1.0)), 1.0 / (1.0 + math.exp(-1.0)))
+
+
+def test_rmsnorm_closed_forms():
+    # a constant row c has rms |c|: h = sign(c) * g
+    x = np.full((1, 8), -3.0)
+    g = np.arange(1.0, 9.0)
+    h, rstd = O.rmsnorm_fwd(x, g, 0.0)
+    assert np.allclose(h, -g) and np.isclose(rstd[0, 0], 1.0 / 3.0)
+    # the output is invariant to scaling x (eps = 0), so dx is orthogonal to x
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal((4, 8))
+    dh = rng.standard_normal((4, 8))
+    dx, dg = O.rmsnorm_bwd(dh, x, g, 0.0)
+    assert np.allclose(np.sum(dx * x, axis=1), 0.0, atol=1e-12)
+    n = x / np.sqrt(np.mean(x * x, axis=1, keepdims=True))
+    assert np.allclose(dg, np.sum(dh * n, axis=0))
+
+
+# ---------------------------------------------------------------------------
+# index build and gather: brute force
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("B,S,p", [(1, 1, 1.0), (3, 17, 0.5), (4, 64, 0.3), (2, 33, 0.0), (2, 33, 1.0)])
+def test_keep_index_against_library_routines(B, S, p):
+    rng = np.random.default_rng(B * 100 + S)
+    mask = (rng.random((B, S)) < p).astype(np.uint8)
+    idx, cu, n = O.keep_index(mask)
+    assert idx.dtype == np.int32 and cu.dtype == np.int32
+    assert np.array_equal(idx, np.flatnonzero(mask.reshape(-1)))
+    assert np.array_equal(cu, np.concatenate([[0], np.cumsum(mask.sum(axis=1))]))
+    assert n == int(mask.sum()) == cu[-1] == len(idx)
+    assert np.all(np.diff(idx) > 0)
+
+
+def test_gather_rows_against_take():
+    rng = np.random.default_rng(1)
+    src = rng.standard_normal((50, 7)).astype(np.float32)
+    idx = np.sort(rng.choice(50, size=20, replace=False)).astype(np.int32)
+    assert np.array_equal(O.gather_rows(src, idx), np.take(src, idx, axis=0))
+    assert O.gather_rows(src, idx[:0]).shape == (0, 7)
+
+
+# ---------------------------------------------------------------------------
+# degenerate cases
+# ---------------------------------------------------------------------------
+
+def test_nothing_kept_gives_all_zero_gradients():
+    c, W, x, dy, _ = _tiny_problem(20)
+    kw = _kw(c)
+    _, saved = O.layer_fwd(x, W, **kw)
+    out = O.layer_bwd(saved, W, dy, np.zeros((c["B"], c["S"]), np.uint8), **kw)
+    for k, val in out.items():
+        assert np.all(val == 0), k
+
+
+def test_only_last_token_kept_and_an_empty_sequence():
+    c, W, x, dy, _ = _tiny_problem(21)
+    kw = _kw(c)
+    mask = np.zeros((c["B"], c["S"]), np.uint8)
+    mask[0, -1] = 1                       # sequence 1 keeps nothing
+    _, saved = O.layer_fwd(x, W, **kw)
+    out = O.layer_bwd(saved, W, dy, mask, **kw)
+    t = c["S"] - 1
+    assert np.abs(out["dx"][t]).sum() > 0
+    assert np.all(np.delete(out["dx"], t, axis=0) == 0)
+    # dK/dV of the single kept token come from its own query only (P_tt)
+    assert np.abs(out["_dk"][t]).sum() > 0 and np.all(np.delete(out["_dk"], t, axis=0) == 0)
+
+
+def test_mha_and_gqa_group_sum():
+    """With G query heads per KV head, dk/dv are the sums of the per-head
+    results of an equivalent MHA problem with repeated K/V heads."""
+    q, k, v, da, mask, kw = _attn_problem(22)
+    B, S, Hq, Hkv, d = kw["B"], kw["S"], kw["Hq"], kw["Hkv"], kw["d"]
+    G = Hq // Hkv
+    scale = 1.0 / math.sqrt(d)
+    a, lse = O.attn_fwd(q, k, v, scale=scale, **kw)
+    dq, dk, dv = O.attn_bwd_filtered(q, k, v, a, lse, da, mask, **kw)
+    rep = lambda t: np.repeat(t.reshape(-1, Hkv, d), G, axis=1).reshape(-1, Hq * d)
+    kw2 = dict(kw, Hkv=Hq)
+    dq2, dk2, dv2 = O.attn_bwd_filtered(q, rep(k), rep(v), a, lse, da, mask, **kw2)
+    assert _relerr(dq, dq2) < 1e-14
+    assert _relerr(dk, dk2.reshape(-1, Hkv, G, d).sum(axis=2).reshape(-1, Hkv * d)) < 1e-13
+    assert _relerr(dv, dv2.reshape(-1, Hkv, G, d).sum(axis=2).reshape(-1, Hkv * d)) < 1e-13
+
+
+# ---------------------------------------------------------------------------
+# input generators (no arithmetic of the method; shapes and counts only)
+# ---------------------------------------------------------------------------
+
+def test_mask_generators_have_exact_counts():
+    rng = np.random.default_rng(0)
+    m = WL.mask_topk(rng, 3, 100, 0.7)
+    assert m.sum(axis=1).tolist() == [70, 70, 70]
+    m = WL.mask_spans(rng, 2, 4096, 0.5)
+    assert m.sum(axis=1).tolist() == [2048, 2048]
+    runs = np.diff(np.flatnonzero(np.diff(m[0].astype(int)) != 0))
+    assert np.median(runs) >= 8
+    m = WL.mask_ragged(rng, 1, 8192)
+    per = m.reshape(8, 1024).sum(axis=1) / 1024.0
+    assert np.allclose(np.sort(per), np.linspace(0.2, 0.8, 8), atol=1e-3)
+    assert WL.topk_count(0.7, 4096) == 2867 and WL.topk_count(0.3, 4096) == 1229
+
+
+def test_bf16_rounding_helper():
+    a = np.array([1.0, 1.00390625, 1.005859375, -3.1415927, 0.0], dtype=np.float32)
+    r = WL.round_to_bf16(a)
+    t = torch.tensor(a).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(r, t)
