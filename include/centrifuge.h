@@ -1,0 +1,179 @@
+/*
+ * centrifuge.h -- C ABI of the MI355X (gfx950) token-filtered decoder-layer backward.
+ *
+ * The library implements the hot path of backward token filtering with
+ * activation filtering (paper Sec. 3): the upstream gradient of a layer is
+ * row-sparse (filtered tokens carry zero gradient), so every per-token
+ * operation runs on the kept rows only ("dimension-reduced dense GEMM",
+ * Sec. 3.2), and the attention backward emits dK/dV for kept tokens only
+ * while dQ of a kept query still sees every key/value (Sec. 3.1, Eq. 3-4),
+ * which keeps the gradient handed to the layer below row-sparse.
+ *
+ * Conventions (all entry points)
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller; the
+ *     library never allocates or frees device memory and keeps no state
+ *     between calls.  Scratch space is the caller-provided workspace `ws`
+ *     (256-byte aligned); its required size comes from the *_workspace_bytes
+ *     calls.  Pointers named *_host are HOST pointers.
+ *   - Tokens are flat rows t = b*S + s.  Matrices are row-major and dense
+ *     (leading dimension = number of columns).  Weights are stored [in, out]
+ *     (Y = X * W).  "kept"/compact tensors have one row per kept token in
+ *     ascending token order.
+ *   - dtype CF_BF16: bfloat16 storage, fp32 accumulation and fp32 row
+ *     statistics; CF_F32: fp32 everywhere (check mode, not tuned).  LSE is
+ *     always fp32.  In CF_BF16 mode H, Hq*d, Hkv*d and F must be multiples of
+ *     8 and d must be 64 or 128; in CF_F32 mode they must be multiples of 4 and
+ *     d <= 256.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue work and return without synchronising, except where a
+ *     host result is requested (n_kept_host) -- see each function.
+ *   - Errors: argument errors are detected on the host before anything is
+ *     launched and reported as a cf_status; nothing is written in that case.
+ *     A HIP runtime failure is reported as CF_ERR_HIP.
+ */
+#ifndef CENTRIFUGE_H
+#define CENTRIFUGE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    CF_OK = 0,
+    CF_ERR_NULL = 1,        /* a required pointer is NULL */
+    CF_ERR_SHAPE = 2,       /* a size is non-positive, misaligned or inconsistent */
+    CF_ERR_DTYPE = 3,       /* dtype enum out of range */
+    CF_ERR_WORKSPACE = 4,   /* workspace missing, misaligned or too small */
+    CF_ERR_UNSUPPORTED = 5, /* valid request this build does not implement */
+    CF_ERR_HIP = 6          /* HIP runtime error */
+} cf_status;
+
+typedef enum { CF_BF16 = 0, CF_F32 = 1 } cf_dtype;
+
+typedef void* cf_stream;
+
+/* Shape of one decoder layer (RMSNorm -> GQA causal attention -> residual ->
+ * RMSNorm -> SwiGLU FFN -> residual) and of the batch. */
+typedef struct {
+    int32_t B, S;          /* sequences, tokens per sequence; T = B*S            */
+    int32_t H;             /* hidden size                                        */
+    int32_t Hq, Hkv, d;    /* query heads, key/value heads (Hq % Hkv == 0), head dim */
+    int32_t F;             /* SwiGLU width                                       */
+    int32_t dtype;         /* cf_dtype                                           */
+    float rms_eps;         /* RMSNorm epsilon                                    */
+    float softmax_scale;   /* 0 => 1/sqrt(d)                                     */
+} cf_layer_desc;
+
+/* Activations saved by the forward pass, full length (T rows). */
+typedef struct {
+    const void* x;         /* [T,H]     layer input                              */
+    const void* q;         /* [T,Hq*d]  queries as used by attention             */
+    const void* k;         /* [T,Hkv*d] keys                                     */
+    const void* v;         /* [T,Hkv*d] values                                   */
+    const void* attn_out;  /* [T,Hq*d]  attention output before the O projection */
+    const float* lse;      /* [B,Hq,S]  log-sum-exp of the scaled causal scores  */
+    const void* r;         /* [T,H]     x + attn_out*Wo (input of the 2nd norm)  */
+    const void* gate;      /* [T,F]     rmsnorm2(r)*Wg                           */
+    const void* up;        /* [T,F]     rmsnorm2(r)*Wu                           */
+} cf_saved;
+
+typedef struct {
+    const void *wq, *wk, *wv;  /* [H,Hq*d], [H,Hkv*d], [H,Hkv*d] */
+    const void *wo;            /* [Hq*d,H] */
+    const void *wg, *wu;       /* [H,F]    */
+    const void *wd;            /* [F,H]    */
+    const void *g1, *g2;       /* [H] RMSNorm gains */
+} cf_weights;
+
+/* Outputs.  Parameter gradients have the shapes of the parameters and are
+ * overwritten.  dx is [N_k,H] compact for the filtered call and [T,H] for the
+ * dense call. */
+typedef struct {
+    void *dwq, *dwk, *dwv, *dwo, *dwg, *dwu, *dwd, *dg1, *dg2;
+    void *dx;
+} cf_grads;
+
+const char* cf_status_str(cf_status s);
+
+/* Library version string (static storage). */
+const char* cf_version(void);
+
+/* ---- A1: keep-index build (Sec. 3.2: shrink the sequence dimension) --------
+ * Order-preserving compaction of the keep mask (Sec. 2.1 Eq. 2: 1 = token is
+ * selected; any non-zero byte counts as kept).
+ *   mask        [B*S] bytes, device
+ *   idx         [>= number kept] int32, device: flat row of the j-th kept token, ascending
+ *   cu_kept     [B+1] int32, device: kept tokens in sequences before b; cu_kept[B] = N_k
+ *   n_kept_dev  [1] int32, device (nullable)
+ *   n_kept_host [1] int32, host (nullable).  When non-NULL the call copies N_k
+ *               back and synchronises the stream before returning.
+ *   ws          device scratch of cf_index_workspace_bytes(B*S) bytes
+ * idx must have room for B*S entries unless the caller knows N_k in advance. */
+size_t cf_index_workspace_bytes(int64_t n_tokens);
+cf_status cf_build_keep_index(const uint8_t* mask, int32_t B, int32_t S,
+                              int32_t* idx, int32_t* cu_kept, int32_t* n_kept_dev,
+                              int32_t* n_kept_host, void* ws, size_t ws_bytes, cf_stream stream);
+
+/* ---- A2: row gather (Sec. 3.2: remove the filtered rows of saved tensors) --
+ * dst[j,:] = src[idx[j],:] for j < n_rows.  src is [src_rows, cols], dst is
+ * [n_rows, cols]; cols*sizeof(elt) must be a multiple of 4.  idx entries must lie
+ * in [0, src_rows) (not checked: they live on the device). */
+cf_status cf_gather_rows(const void* src, int64_t src_rows, int64_t cols, int32_t dtype,
+                         const int32_t* idx, int32_t n_rows, void* dst, cf_stream stream);
+
+/* ---- A3: dimension-reduced linear backward (Sec. 3.2, the two GEMM types) ---
+ * For Y = X*W with W [in,out]:
+ *   dx_kept [n_kept,in]  = dy_kept [n_kept,out] * W^T          (nullable: skipped)
+ *   dw      [in,out]     = dw_beta*dw + x_kept^T [in,n_kept] * dy_kept   (nullable: skipped)
+ * x_kept is [n_kept,in].  dw_beta is 0 (overwrite) or 1 (accumulate).
+ * n_kept == 0 is valid: dw is zeroed (beta 0) or left alone (beta 1). */
+cf_status cf_linear_bwd_reduced(const void* x_kept, const void* dy_kept, const void* w,
+                                int32_t n_kept, int32_t in, int32_t out, int32_t dtype,
+                                void* dx_kept, void* dw, float dw_beta, cf_stream stream);
+
+/* ---- A5: filtered attention backward (Sec. 3.1, Eq. 3 and Eq. 4) -----------
+ * Kept queries attend to ALL keys/values at positions <= their own (causal on
+ * original positions) for dQ; dK and dV are produced for kept tokens only.
+ *   q_kept, o_kept, do_kept  [n_kept,Hq*d]   compact rows (o = attention output, do = its gradient)
+ *   k_full, v_full           [T,Hkv*d]       full length
+ *   lse_full                 [B,Hq,S] fp32   forward's log-sum-exp over the full causal row
+ *   idx [n_kept], cu_kept [B+1]              from cf_build_keep_index
+ *   dq_kept [n_kept,Hq*d], dk_kept, dv_kept [n_kept,Hkv*d]   outputs, overwritten
+ * dk/dv are summed over the Hq/Hkv query heads that share a key/value head.
+ * Uses only B,S,Hq,Hkv,d,dtype,softmax_scale of desc. */
+size_t cf_attn_workspace_bytes(const cf_layer_desc* desc, int32_t n_kept);
+cf_status cf_attn_bwd_filtered(const cf_layer_desc* desc, const void* q_kept, const void* k_full,
+                               const void* v_full, const void* o_kept, const float* lse_full,
+                               const void* do_kept, const int32_t* idx, const int32_t* cu_kept,
+                               int32_t n_kept, void* dq_kept, void* dk_kept, void* dv_kept,
+                               void* ws, size_t ws_bytes, cf_stream stream);
+
+/* ---- whole layer -----------------------------------------------------------
+ * cf_layer_bwd_filtered: mask -> keep index -> row gathers -> all reduced GEMMs,
+ * row-local backward ops (SwiGLU, RMSNorm, residuals; Sec. 3.2 "G (.) g") and the
+ * filtered attention backward.  dy_full is the upstream gradient on all T rows
+ * (rows of filtered tokens are ignored).  Outputs: grads->dx compact [N_k,H] (the
+ * row-sparse gradient for the layer below), all parameter gradients; idx_out
+ * [T] / cu_kept_out [B+1] (device, nullable) receive the keep index;
+ * n_kept_host (host, required) receives N_k.  The call synchronises the stream
+ * once, right after the index build, to size the remaining launches.
+ * cf_layer_bwd_dense: the same kernels with every token kept and no index or
+ * gather; dx is [T,H].
+ * ws must hold cf_layer_workspace_bytes(desc, max_kept) bytes; max_kept = T is
+ * always sufficient. */
+size_t cf_layer_workspace_bytes(const cf_layer_desc* desc, int32_t max_kept);
+cf_status cf_layer_bwd_filtered(const cf_layer_desc* desc, const cf_saved* saved,
+                                const cf_weights* w, const void* dy_full, const uint8_t* mask,
+                                cf_grads* grads, int32_t* idx_out, int32_t* cu_kept_out,
+                                int32_t* n_kept_host, void* ws, size_t ws_bytes, cf_stream stream);
+cf_status cf_layer_bwd_dense(const cf_layer_desc* desc, const cf_saved* saved,
+                             const cf_weights* w, const void* dy_full, cf_grads* grads,
+                             void* ws, size_t ws_bytes, cf_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CENTRIFUGE_H */

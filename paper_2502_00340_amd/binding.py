@@ -1,0 +1,263 @@
+"""ctypes binding of the C-ABI library (include/centrifuge.h).
+
+Argument marshalling only: every step of the path runs inside the HIP
+library.  torch supplies device memory and the current stream.  There is no
+CPU fallback: if the library has not been built, `lib()` raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import math
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcentrifuge.so")
+
+CF_BF16, CF_F32 = 0, 1
+_STATUS = {0: "CF_OK", 1: "CF_ERR_NULL", 2: "CF_ERR_SHAPE", 3: "CF_ERR_DTYPE", 4: "CF_ERR_WORKSPACE",
+           5: "CF_ERR_UNSUPPORTED", 6: "CF_ERR_HIP"}
+
+EXPORTS = (
+    "cf_status_str", "cf_version", "cf_index_workspace_bytes", "cf_build_keep_index", "cf_gather_rows",
+    "cf_linear_bwd_reduced", "cf_attn_workspace_bytes", "cf_attn_bwd_filtered",
+    "cf_layer_workspace_bytes", "cf_layer_bwd_filtered", "cf_layer_bwd_dense",
+)
+
+
+class CfError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__("%s failed: %s (%d)" % (where, _STATUS.get(code, "?"), code))
+
+
+class LayerDesc(C.Structure):
+    _fields_ = [("B", C.c_int32), ("S", C.c_int32), ("H", C.c_int32), ("Hq", C.c_int32),
+                ("Hkv", C.c_int32), ("d", C.c_int32), ("F", C.c_int32), ("dtype", C.c_int32),
+                ("rms_eps", C.c_float), ("softmax_scale", C.c_float)]
+
+
+class Saved(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("x", "q", "k", "v", "attn_out", "lse", "r", "gate", "up")]
+
+
+class Weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g1", "g2")]
+
+
+class Grads(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("dwq", "dwk", "dwv", "dwo", "dwg", "dwu", "dwd", "dg1", "dg2", "dx")]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libcentrifuge.so (built by paper_2502_00340_amd.build).  Raises if missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("HIP library not built: %s is missing (run __graft_entry__.build())" % LIB_PATH)
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i64, sz, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t, C.c_float
+    L.cf_status_str.restype = C.c_char_p
+    L.cf_status_str.argtypes = [C.c_int]
+    L.cf_version.restype = C.c_char_p
+    L.cf_version.argtypes = []
+    L.cf_index_workspace_bytes.restype = sz
+    L.cf_index_workspace_bytes.argtypes = [i64]
+    L.cf_build_keep_index.restype = C.c_int
+    L.cf_build_keep_index.argtypes = [vp, i32, i32, vp, vp, vp, C.POINTER(i32), vp, sz, vp]
+    L.cf_gather_rows.restype = C.c_int
+    L.cf_gather_rows.argtypes = [vp, i64, i64, i32, vp, i32, vp, vp]
+    L.cf_linear_bwd_reduced.restype = C.c_int
+    L.cf_linear_bwd_reduced.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, f32, vp]
+    L.cf_attn_workspace_bytes.restype = sz
+    L.cf_attn_workspace_bytes.argtypes = [C.POINTER(LayerDesc), i32]
+    L.cf_attn_bwd_filtered.restype = C.c_int
+    L.cf_attn_bwd_filtered.argtypes = [C.POINTER(LayerDesc), vp, vp, vp, vp, vp, vp, vp, vp, i32,
+                                       vp, vp, vp, vp, sz, vp]
+    L.cf_layer_workspace_bytes.restype = sz
+    L.cf_layer_workspace_bytes.argtypes = [C.POINTER(LayerDesc), i32]
+    L.cf_layer_bwd_filtered.restype = C.c_int
+    L.cf_layer_bwd_filtered.argtypes = [C.POINTER(LayerDesc), C.POINTER(Saved), C.POINTER(Weights), vp, vp,
+                                        C.POINTER(Grads), vp, vp, C.POINTER(i32), vp, sz, vp]
+    L.cf_layer_bwd_dense.restype = C.c_int
+    L.cf_layer_bwd_dense.argtypes = [C.POINTER(LayerDesc), C.POINTER(Saved), C.POINTER(Weights), vp,
+                                     C.POINTER(Grads), vp, sz, vp]
+    _lib = L
+    return L
+
+
+def _check(code: int, where: str):
+    if code != 0:
+        raise CfError(code, where)
+
+
+_dummy = {}
+
+
+def _ptr(t):
+    """Device pointer of a tensor; an empty tensor (no storage) maps to a small
+    dummy allocation so that "zero rows" is not mistaken for a NULL argument."""
+    if t is None:
+        return None
+    if t.numel() == 0:
+        key = str(t.device)
+        if key not in _dummy:
+            _dummy[key] = torch.zeros(256, dtype=torch.uint8, device=t.device)
+        return C.c_void_p(_dummy[key].data_ptr())
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return CF_BF16
+    if t.dtype == torch.float32:
+        return CF_F32
+    raise TypeError("unsupported dtype %s" % t.dtype)
+
+
+def make_desc(B, S, H, Hq, Hkv, d, F, dtype, rms_eps=1e-5, softmax_scale=0.0) -> LayerDesc:
+    code = {"bf16": CF_BF16, "f32": CF_F32, torch.bfloat16: CF_BF16, torch.float32: CF_F32}[dtype]
+    return LayerDesc(B, S, H, Hq, Hkv, d, F, code, rms_eps, softmax_scale)
+
+
+def torch_dtype(desc: LayerDesc):
+    return torch.bfloat16 if desc.dtype == CF_BF16 else torch.float32
+
+
+# --------------------------------------------------------------------------
+# entry points (same names as the C ABI, without the prefix)
+# --------------------------------------------------------------------------
+
+def build_keep_index(mask: torch.Tensor, sync: bool = True):
+    """mask: uint8 [B,S] on the GPU.  Returns (idx [T] int32 - first N_k valid,
+    cu_kept [B+1] int32, n_kept_dev [1] int32, N_k or None)."""
+    assert mask.dtype == torch.uint8 and mask.is_cuda and mask.dim() == 2 and mask.is_contiguous()
+    B, S = mask.shape
+    dev = mask.device
+    idx = torch.empty(B * S, dtype=torch.int32, device=dev)
+    cu = torch.empty(B + 1, dtype=torch.int32, device=dev)
+    n_dev = torch.empty(1, dtype=torch.int32, device=dev)
+    wsb = lib().cf_index_workspace_bytes(B * S)
+    ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
+    n_host = C.c_int32(-1)
+    _check(lib().cf_build_keep_index(_ptr(mask), B, S, _ptr(idx), _ptr(cu), _ptr(n_dev),
+                                     C.byref(n_host) if sync else None, _ptr(ws), wsb, _stream()),
+           "cf_build_keep_index")
+    return idx, cu, n_dev, (int(n_host.value) if sync else None)
+
+
+def gather_rows(src: torch.Tensor, idx: torch.Tensor, n_rows: int, out: torch.Tensor | None = None):
+    assert src.is_cuda and src.dim() == 2 and src.is_contiguous() and idx.dtype == torch.int32
+    rows, cols = src.shape
+    if out is None:
+        out = torch.empty((n_rows, cols), dtype=src.dtype, device=src.device)
+    _check(lib().cf_gather_rows(_ptr(src), rows, cols, _dtype_code(src), _ptr(idx), n_rows, _ptr(out),
+                                _stream()), "cf_gather_rows")
+    return out
+
+
+def linear_bwd_reduced(x_kept, dy_kept, w, need_dx=True, need_dw=True, dw_accumulate_into=None):
+    """Returns (dx_kept or None, dw or None)."""
+    n_kept, out_f = dy_kept.shape
+    in_f = w.shape[0] if w is not None else x_kept.shape[1]
+    dev = dy_kept.device
+    dx = torch.empty((n_kept, in_f), dtype=dy_kept.dtype, device=dev) if need_dx else None
+    beta = 0.0
+    dw = None
+    if need_dw:
+        if dw_accumulate_into is not None:
+            dw, beta = dw_accumulate_into, 1.0
+        else:
+            dw = torch.empty((in_f, out_f), dtype=dy_kept.dtype, device=dev)
+    _check(lib().cf_linear_bwd_reduced(_ptr(x_kept), _ptr(dy_kept), _ptr(w), n_kept, in_f, out_f,
+                                       _dtype_code(dy_kept), _ptr(dx), _ptr(dw), beta, _stream()),
+           "cf_linear_bwd_reduced")
+    return dx, dw
+
+
+def attn_bwd_filtered(desc: LayerDesc, q_kept, k_full, v_full, o_kept, lse_full, do_kept, idx, cu_kept,
+                      n_kept: int):
+    dev = q_kept.device
+    Nq, Nkv = desc.Hq * desc.d, desc.Hkv * desc.d
+    dt = torch_dtype(desc)
+    dq = torch.empty((n_kept, Nq), dtype=dt, device=dev)
+    dk = torch.empty((n_kept, Nkv), dtype=dt, device=dev)
+    dv = torch.empty((n_kept, Nkv), dtype=dt, device=dev)
+    wsb = lib().cf_attn_workspace_bytes(C.byref(desc), n_kept)
+    ws = torch.empty(max(wsb, 256), dtype=torch.uint8, device=dev)
+    _check(lib().cf_attn_bwd_filtered(C.byref(desc), _ptr(q_kept), _ptr(k_full), _ptr(v_full), _ptr(o_kept),
+                                      _ptr(lse_full), _ptr(do_kept), _ptr(idx), _ptr(cu_kept), n_kept,
+                                      _ptr(dq), _ptr(dk), _ptr(dv), _ptr(ws), ws.numel(), _stream()),
+           "cf_attn_bwd_filtered")
+    return dq, dk, dv
+
+
+_SAVED = ("x", "q", "k", "v", "attn_out", "lse", "r", "gate", "up")
+_WEIGHTS = ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g1", "g2")
+
+
+class LayerBackward:
+    """Pre-allocated outputs + workspace for repeated calls on one layer shape."""
+
+    def __init__(self, desc: LayerDesc, device="cuda:0", max_kept: int | None = None):
+        self.desc = desc
+        self.device = torch.device(device)
+        dt = torch_dtype(desc)
+        T = desc.B * desc.S
+        H, F, Nq, Nkv = desc.H, desc.F, desc.Hq * desc.d, desc.Hkv * desc.d
+        self.max_kept = T if max_kept is None else max_kept
+        e = lambda *s: torch.empty(s, dtype=dt, device=self.device)
+        self.grads = dict(dwq=e(H, Nq), dwk=e(H, Nkv), dwv=e(H, Nkv), dwo=e(Nq, H), dwg=e(H, F), dwu=e(H, F),
+                          dwd=e(F, H), dg1=e(H), dg2=e(H), dx=e(T, H))
+        self.idx = torch.empty(T, dtype=torch.int32, device=self.device)
+        self.cu_kept = torch.empty(desc.B + 1, dtype=torch.int32, device=self.device)
+        self.ws_bytes = lib().cf_layer_workspace_bytes(C.byref(desc), self.max_kept)
+        if self.ws_bytes == 0:
+            raise CfError(2, "cf_layer_workspace_bytes")
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=self.device)
+        self._g = Grads(*[self.grads[n].data_ptr() for n, _ in Grads._fields_])
+
+    def _pack(self, saved: dict, weights: dict):
+        sv = Saved(*[saved[n].data_ptr() for n in _SAVED])
+        w = Weights(*[weights[n].data_ptr() for n in _WEIGHTS])
+        return sv, w
+
+    def filtered(self, saved: dict, weights: dict, dy: torch.Tensor, mask: torch.Tensor) -> int:
+        """Runs cf_layer_bwd_filtered; results land in self.grads (dx: first N_k rows), self.idx,
+        self.cu_kept.  Returns N_k."""
+        sv, w = self._pack(saved, weights)
+        n_host = C.c_int32(-1)
+        _check(lib().cf_layer_bwd_filtered(C.byref(self.desc), C.byref(sv), C.byref(w), _ptr(dy), _ptr(mask),
+                                           C.byref(self._g), _ptr(self.idx), _ptr(self.cu_kept),
+                                           C.byref(n_host), _ptr(self.ws), self.ws_bytes, _stream()),
+               "cf_layer_bwd_filtered")
+        return int(n_host.value)
+
+    def dense(self, saved: dict, weights: dict, dy: torch.Tensor) -> None:
+        sv, w = self._pack(saved, weights)
+        _check(lib().cf_layer_bwd_dense(C.byref(self.desc), C.byref(sv), C.byref(w), _ptr(dy),
+                                        C.byref(self._g), _ptr(self.ws), self.ws_bytes, _stream()),
+               "cf_layer_bwd_dense")
+
+
+def layer_bwd_filtered(desc, saved, weights, dy, mask):
+    plan = LayerBackward(desc, device=dy.device)
+    n = plan.filtered(saved, weights, dy, mask)
+    out = dict(plan.grads)
+    out["dx"] = out["dx"][:n]
+    return out, plan.idx[:n], plan.cu_kept, n
+
+
+def layer_bwd_dense(desc, saved, weights, dy):
+    plan = LayerBackward(desc, device=dy.device)
+    plan.dense(saved, weights, dy)
+    return dict(plan.grads)

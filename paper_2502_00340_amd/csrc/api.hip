@@ -1,0 +1,403 @@
+// C ABI: argument validation (host only, before any launch) and the layer
+// orchestration.  See include/centrifuge.h for the contract of each call.
+#include <math.h>
+
+#include "common.h"
+
+namespace cf {
+hipError_t launch_attn_bwd_ref(const cf_layer_desc& L, float scale, const void* q_kept,
+                               const void* k_full, const void* v_full, const float* lse_full,
+                               const void* do_kept, const float* Drow, const int32_t* idx,
+                               const int32_t* cu_kept, int n_kept, void* dq_kept, void* dk_kept,
+                               void* dv_kept, hipStream_t st);
+bool attn_mfma_supported(const cf_layer_desc& L);
+hipError_t launch_attn_bwd_mfma(const cf_layer_desc& L, float scale, const void* q_kept,
+                                const void* k_full, const void* v_full, const float* lse_full,
+                                const void* do_kept, const float* Drow, const int32_t* idx,
+                                const int32_t* cu_kept, int n_kept, void* dq_kept, void* dk_kept,
+                                void* dv_kept, hipStream_t st);
+}  // namespace cf
+
+using namespace cf;
+
+namespace {
+
+inline bool misaligned(const void* p, size_t a = 16) { return ((uintptr_t)p % a) != 0; }
+inline hipStream_t as_stream(cf_stream s) { return reinterpret_cast<hipStream_t>(s); }
+
+#define CF_HIP(expr)                                   \
+    do {                                               \
+        hipError_t e__ = (expr);                       \
+        if (e__ != hipSuccess) return CF_ERR_HIP;      \
+    } while (0)
+
+cf_status check_dtype(int dtype) {
+    return (dtype == CF_BF16 || dtype == CF_F32) ? CF_OK : CF_ERR_DTYPE;
+}
+
+bool pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
+
+// attention-relevant fields only
+cf_status check_attn_desc(const cf_layer_desc* L) {
+    if (!L) return CF_ERR_NULL;
+    cf_status s = check_dtype(L->dtype);
+    if (s != CF_OK) return s;
+    if (L->B <= 0 || L->S <= 0 || L->Hq <= 0 || L->Hkv <= 0 || L->d <= 0) return CF_ERR_SHAPE;
+    if ((int64_t)L->B * L->S > (int64_t)1 << 30) return CF_ERR_SHAPE;
+    if (L->Hq % L->Hkv != 0) return CF_ERR_SHAPE;
+    if (L->dtype == CF_BF16) {
+        if (L->d != 64 && L->d != 128) return CF_ERR_SHAPE;
+    } else {
+        if (!pow2(L->d) || L->d < 4 || L->d > 256) return CF_ERR_SHAPE;
+    }
+    if (!(L->softmax_scale >= 0.f)) return CF_ERR_SHAPE;
+    return CF_OK;
+}
+
+cf_status check_layer_desc(const cf_layer_desc* L) {
+    cf_status s = check_attn_desc(L);
+    if (s != CF_OK) return s;
+    if (L->H <= 0 || L->F <= 0) return CF_ERR_SHAPE;
+    const int mult = L->dtype == CF_BF16 ? 8 : 4;
+    if (L->H % mult || L->F % mult) return CF_ERR_SHAPE;
+    if (L->H > 256 * 8 * mult) return CF_ERR_SHAPE;     // row-norm kernels keep a row in registers
+    if (!(L->rms_eps >= 0.f)) return CF_ERR_SHAPE;
+    return CF_OK;
+}
+
+float eff_scale(const cf_layer_desc& L) {
+    return L.softmax_scale > 0.f ? L.softmax_scale : 1.0f / sqrtf((float)L.d);
+}
+
+// bump allocator over the caller's workspace
+struct Carver {
+    unsigned char* base;
+    size_t off = 0;
+    explicit Carver(void* p) : base(static_cast<unsigned char*>(p)) {}
+    void* take(size_t bytes) {
+        void* r = base ? base + off : nullptr;
+        off += align_up(bytes ? bytes : 1, 256);
+        return r;
+    }
+};
+
+struct LayerWs {
+    void* index_ws;
+    int32_t *idx, *cu_kept, *n_kept_dev;
+    void *dy_k, *bufF0, *bufF1, *bufHa, *bufHb, *dr, *a_k, *da, *q_k, *dq, *dk, *dv;
+    float *Drow, *dg_partial;
+    size_t total;
+};
+
+LayerWs carve_layer(const cf_layer_desc& L, int max_kept, void* ws) {
+    const size_t e = dtype_size(L.dtype);
+    const size_t N = (size_t)(max_kept > 0 ? max_kept : 1);
+    const size_t T = (size_t)L.B * L.S;
+    const size_t Nq = (size_t)L.Hq * L.d, Nkv = (size_t)L.Hkv * L.d;
+    Carver c(ws);
+    LayerWs w;
+    w.index_ws = c.take(index_ws_bytes((int64_t)T));
+    w.idx = (int32_t*)c.take(T * 4);
+    w.cu_kept = (int32_t*)c.take((size_t)(L.B + 1) * 4);
+    w.n_kept_dev = (int32_t*)c.take(4);
+    w.dy_k = c.take(N * L.H * e);
+    w.bufF0 = c.take(N * L.F * e);
+    w.bufF1 = c.take(N * L.F * e);
+    w.bufHa = c.take(N * L.H * e);
+    w.bufHb = c.take(N * L.H * e);
+    w.dr = c.take(N * L.H * e);
+    w.a_k = c.take(N * Nq * e);
+    w.da = c.take(N * Nq * e);
+    w.q_k = c.take(N * Nq * e);
+    w.dq = c.take(N * Nq * e);
+    w.dk = c.take(N * Nkv * e);
+    w.dv = c.take(N * Nkv * e);
+    w.Drow = (float*)c.take(N * L.Hq * 4);
+    w.dg_partial = (float*)c.take((size_t)rmsnorm_bwd_blocks((int)N) * L.H * 4);
+    w.total = c.off;
+    return w;
+}
+
+cf_status attn_dispatch(const cf_layer_desc& L, const void* q_kept, const void* k_full,
+                        const void* v_full, const void* o_kept, const float* lse_full,
+                        const void* do_kept, const int32_t* idx, const int32_t* cu_kept, int n_kept,
+                        void* dq_kept, void* dk_kept, void* dv_kept, float* Drow, hipStream_t st) {
+    if (n_kept <= 0) return CF_OK;
+    const float scale = eff_scale(L);
+    CF_HIP(launch_attn_rowdot(L.dtype, do_kept, o_kept, n_kept, L.Hq, L.d, Drow, st));
+    if (attn_mfma_supported(L))
+        CF_HIP(launch_attn_bwd_mfma(L, scale, q_kept, k_full, v_full, lse_full, do_kept, Drow, idx,
+                                    cu_kept, n_kept, dq_kept, dk_kept, dv_kept, st));
+    else
+        CF_HIP(launch_attn_bwd_ref(L, scale, q_kept, k_full, v_full, lse_full, do_kept, Drow, idx,
+                                   cu_kept, n_kept, dq_kept, dk_kept, dv_kept, st));
+    return CF_OK;
+}
+
+// Everything after the keep index is known.  N rows are live; idx == nullptr
+// means the dense backward (row j is token j).
+cf_status layer_core(const cf_layer_desc& L, const cf_saved& sv, const cf_weights& W,
+                     const void* dy_rows /*[N,H] compact*/, const int32_t* idx,
+                     const int32_t* cu_kept, int N, cf_grads& G, const LayerWs& w, hipStream_t st) {
+    const int dt = L.dtype;
+    const size_t e = dtype_size(dt);
+    const int H = L.H, F = L.F, Nq = L.Hq * L.d, Nkv = L.Hkv * L.d;
+
+    if (N == 0) {   // nothing kept: every gradient is zero, dx has no rows
+        void* outs[9] = {G.dwq, G.dwk, G.dwv, G.dwo, G.dwg, G.dwu, G.dwd, G.dg1, G.dg2};
+        size_t sz[9] = {(size_t)H * Nq, (size_t)H * Nkv, (size_t)H * Nkv, (size_t)Nq * H,
+                        (size_t)H * F, (size_t)H * F, (size_t)F * H, (size_t)H, (size_t)H};
+        for (int i = 0; i < 9; ++i) CF_HIP(launch_fill_zero(outs[i], sz[i] * e, st));
+        return CF_OK;
+    }
+
+    const void* a_rows = sv.attn_out;
+    const void* q_rows = sv.q;
+    if (idx) {
+        CF_HIP(launch_gather(sv.attn_out, (int64_t)Nq * e, idx, N, w.a_k, st));
+        CF_HIP(launch_gather(sv.q, (int64_t)Nq * e, idx, N, w.q_k, st));
+        a_rows = w.a_k;
+        q_rows = w.q_k;
+    }
+
+    // ---- SwiGLU FFN: y = r + act*Wd --------------------------------------------
+    void* act = w.bufF0;
+    void* d_act = w.bufF1;
+    CF_HIP(launch_swiglu_fwd(dt, sv.gate, sv.up, idx, N, F, act, st));
+    {   // d_act = dy * Wd^T          [N,F] = [N,H] x [F,H]^T
+        GemmSeg s{dy_rows, W.wd, H};
+        CF_HIP(launch_gemm(dt, 0, &s, 1, d_act, N, F, 0.f, st));
+    }
+    {   // dWd = act^T * dy           [F,H]
+        GemmSeg s{act, dy_rows, N};
+        CF_HIP(launch_gemm(dt, 1, &s, 1, G.dwd, F, H, 0.f, st));
+    }
+    void* d_gate = w.bufF1;   // in place over d_act
+    void* d_up = w.bufF0;     // act is dead after dWd
+    CF_HIP(launch_swiglu_bwd(dt, d_act, sv.gate, sv.up, idx, N, F, d_gate, d_up, st));
+
+    void* h2 = w.bufHa;
+    CF_HIP(launch_rmsnorm_fwd(dt, sv.r, W.g2, idx, N, H, L.rms_eps, h2, st));
+    {
+        GemmSeg s{h2, d_gate, N};
+        CF_HIP(launch_gemm(dt, 1, &s, 1, G.dwg, H, F, 0.f, st));
+        GemmSeg s2{h2, d_up, N};
+        CF_HIP(launch_gemm(dt, 1, &s2, 1, G.dwu, H, F, 0.f, st));
+    }
+    void* dh2 = w.bufHb;
+    {   // dh2 = d_gate*Wg^T + d_up*Wu^T   [N,H], contraction over F twice
+        GemmSeg s[2] = {{d_gate, W.wg, F}, {d_up, W.wu, F}};
+        CF_HIP(launch_gemm(dt, 0, s, 2, dh2, N, H, 0.f, st));
+    }
+    // dr = dy + rmsnorm_bwd(dh2; r, g2);  dg2
+    CF_HIP(launch_rmsnorm_bwd(dt, dh2, sv.r, W.g2, idx, dy_rows, N, H, L.rms_eps, w.dr, w.dg_partial,
+                              G.dg2, st));
+
+    // ---- attention block: r = x + attn_out*Wo ------------------------------------
+    {
+        GemmSeg s{a_rows, w.dr, N};                       // dWo = a^T * dr      [Nq,H]
+        CF_HIP(launch_gemm(dt, 1, &s, 1, G.dwo, Nq, H, 0.f, st));
+        GemmSeg s2{w.dr, W.wo, H};                        // da = dr * Wo^T      [N,Nq]
+        CF_HIP(launch_gemm(dt, 0, &s2, 1, w.da, N, Nq, 0.f, st));
+    }
+    cf_status as = attn_dispatch(L, q_rows, sv.k, sv.v, a_rows, sv.lse, w.da, idx, cu_kept, N, w.dq,
+                                 w.dk, w.dv, w.Drow, st);
+    if (as != CF_OK) return as;
+
+    void* h1 = w.bufHa;
+    CF_HIP(launch_rmsnorm_fwd(dt, sv.x, W.g1, idx, N, H, L.rms_eps, h1, st));
+    {
+        GemmSeg s{h1, w.dq, N};
+        CF_HIP(launch_gemm(dt, 1, &s, 1, G.dwq, H, Nq, 0.f, st));
+        GemmSeg s2{h1, w.dk, N};
+        CF_HIP(launch_gemm(dt, 1, &s2, 1, G.dwk, H, Nkv, 0.f, st));
+        GemmSeg s3{h1, w.dv, N};
+        CF_HIP(launch_gemm(dt, 1, &s3, 1, G.dwv, H, Nkv, 0.f, st));
+    }
+    void* dh1 = w.bufHb;
+    {   // dh1 = dq*Wq^T + dk*Wk^T + dv*Wv^T
+        GemmSeg s[3] = {{w.dq, W.wq, Nq}, {w.dk, W.wk, Nkv}, {w.dv, W.wv, Nkv}};
+        CF_HIP(launch_gemm(dt, 0, s, 3, dh1, N, H, 0.f, st));
+    }
+    // dx = dr + rmsnorm_bwd(dh1; x, g1);  dg1
+    CF_HIP(launch_rmsnorm_bwd(dt, dh1, sv.x, W.g1, idx, w.dr, N, H, L.rms_eps, G.dx, w.dg_partial,
+                              G.dg1, st));
+    return CF_OK;
+}
+
+cf_status check_layer_ptrs(const cf_saved* sv, const cf_weights* W, const void* dy, const cf_grads* G) {
+    if (!sv || !W || !dy || !G) return CF_ERR_NULL;
+    const void* req[] = {sv->x, sv->q, sv->k, sv->v, sv->attn_out, sv->lse, sv->r, sv->gate, sv->up,
+                         W->wq, W->wk, W->wv, W->wo, W->wg, W->wu, W->wd, W->g1, W->g2,
+                         G->dwq, G->dwk, G->dwv, G->dwo, G->dwg, G->dwu, G->dwd, G->dg1, G->dg2, G->dx,
+                         dy};
+    for (const void* p : req) {
+        if (!p) return CF_ERR_NULL;
+    }
+    for (const void* p : req) {
+        if (misaligned(p)) return CF_ERR_SHAPE;
+    }
+    return CF_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* cf_status_str(cf_status s) {
+    switch (s) {
+        case CF_OK: return "ok";
+        case CF_ERR_NULL: return "required pointer is NULL";
+        case CF_ERR_SHAPE: return "invalid, misaligned or inconsistent size";
+        case CF_ERR_DTYPE: return "unknown dtype";
+        case CF_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case CF_ERR_UNSUPPORTED: return "not supported by this build";
+        case CF_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+const char* cf_version(void) { return "centrifuge-mi355x 0.1 (gfx950)"; }
+
+size_t cf_index_workspace_bytes(int64_t n_tokens) { return index_ws_bytes(n_tokens); }
+
+cf_status cf_build_keep_index(const uint8_t* mask, int32_t B, int32_t S, int32_t* idx,
+                              int32_t* cu_kept, int32_t* n_kept_dev, int32_t* n_kept_host, void* ws,
+                              size_t ws_bytes, cf_stream stream) {
+    if (!mask || !idx || !cu_kept) return CF_ERR_NULL;
+    if (B <= 0 || S <= 0 || (int64_t)B * S > ((int64_t)1 << 30)) return CF_ERR_SHAPE;
+    if (misaligned(idx, 4) || misaligned(cu_kept, 4) || (n_kept_dev && misaligned(n_kept_dev, 4)))
+        return CF_ERR_SHAPE;
+    const size_t need = index_ws_bytes((int64_t)B * S);
+    if (!ws || ws_bytes < need || misaligned(ws, 256)) return CF_ERR_WORKSPACE;
+    hipStream_t st = as_stream(stream);
+    CF_HIP(launch_keep_index(mask, B, S, idx, cu_kept, n_kept_dev, ws, st));
+    if (n_kept_host) {
+        CF_HIP(hipMemcpyAsync(n_kept_host, cu_kept + B, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+        CF_HIP(hipStreamSynchronize(st));
+    }
+    return CF_OK;
+}
+
+cf_status cf_gather_rows(const void* src, int64_t src_rows, int64_t cols, int32_t dtype,
+                         const int32_t* idx, int32_t n_rows, void* dst, cf_stream stream) {
+    if (!src || !idx || !dst) return CF_ERR_NULL;
+    cf_status s = check_dtype(dtype);
+    if (s != CF_OK) return s;
+    if (src_rows <= 0 || cols <= 0 || n_rows < 0) return CF_ERR_SHAPE;
+    const int64_t row_bytes = cols * (int64_t)dtype_size(dtype);
+    if (row_bytes % 4 != 0 || misaligned(src, 4) || misaligned(dst, 4) || misaligned(idx, 4))
+        return CF_ERR_SHAPE;
+    if (row_bytes / 4 > INT32_MAX) return CF_ERR_SHAPE;
+    CF_HIP(launch_gather(src, row_bytes, idx, n_rows, dst, as_stream(stream)));
+    return CF_OK;
+}
+
+cf_status cf_linear_bwd_reduced(const void* x_kept, const void* dy_kept, const void* w, int32_t n_kept,
+                                int32_t in, int32_t out, int32_t dtype, void* dx_kept, void* dw,
+                                float dw_beta, cf_stream stream) {
+    cf_status s = check_dtype(dtype);
+    if (s != CF_OK) return s;
+    if (!dy_kept) return CF_ERR_NULL;
+    if (dx_kept && !w) return CF_ERR_NULL;
+    if (dw && !x_kept) return CF_ERR_NULL;
+    if (n_kept < 0 || in <= 0 || out <= 0) return CF_ERR_SHAPE;
+    const int mult = dtype == CF_BF16 ? 8 : 4;
+    if (in % mult || out % mult) return CF_ERR_SHAPE;
+    if (dw_beta != 0.f && dw_beta != 1.f) return CF_ERR_SHAPE;
+    if (misaligned(dy_kept) || (w && misaligned(w)) || (x_kept && misaligned(x_kept)) ||
+        (dx_kept && misaligned(dx_kept)) || (dw && misaligned(dw)))
+        return CF_ERR_SHAPE;
+    hipStream_t st = as_stream(stream);
+    if (dx_kept && n_kept > 0) {
+        GemmSeg seg{dy_kept, w, out};
+        CF_HIP(launch_gemm(dtype, 0, &seg, 1, dx_kept, n_kept, in, 0.f, st));
+    }
+    if (dw) {
+        GemmSeg seg{x_kept, dy_kept, n_kept};
+        CF_HIP(launch_gemm(dtype, 1, &seg, 1, dw, in, out, dw_beta, st));
+    }
+    return CF_OK;
+}
+
+size_t cf_attn_workspace_bytes(const cf_layer_desc* desc, int32_t n_kept) {
+    if (check_attn_desc(desc) != CF_OK || n_kept < 0) return 0;
+    return align_up((size_t)(n_kept > 0 ? n_kept : 1) * desc->Hq * sizeof(float), 256);
+}
+
+cf_status cf_attn_bwd_filtered(const cf_layer_desc* desc, const void* q_kept, const void* k_full,
+                               const void* v_full, const void* o_kept, const float* lse_full,
+                               const void* do_kept, const int32_t* idx, const int32_t* cu_kept,
+                               int32_t n_kept, void* dq_kept, void* dk_kept, void* dv_kept, void* ws,
+                               size_t ws_bytes, cf_stream stream) {
+    cf_status s = check_attn_desc(desc);
+    if (s != CF_OK) return s;
+    const void* req[] = {q_kept, k_full, v_full, o_kept, lse_full, do_kept, idx, cu_kept,
+                         dq_kept, dk_kept, dv_kept};
+    for (const void* p : req) {
+        if (!p) return CF_ERR_NULL;
+    }
+    if (n_kept < 0 || (int64_t)n_kept > (int64_t)desc->B * desc->S) return CF_ERR_SHAPE;
+    const int mult = desc->dtype == CF_BF16 ? 8 : 4;
+    if ((desc->Hq * desc->d) % mult || (desc->Hkv * desc->d) % mult) return CF_ERR_SHAPE;
+    for (const void* p : req) {
+        if (misaligned(p, (p == idx || p == cu_kept || p == lse_full) ? 4 : 16)) return CF_ERR_SHAPE;
+    }
+    if (!ws || misaligned(ws, 256) || ws_bytes < cf_attn_workspace_bytes(desc, n_kept))
+        return CF_ERR_WORKSPACE;
+    return attn_dispatch(*desc, q_kept, k_full, v_full, o_kept, lse_full, do_kept, idx, cu_kept,
+                         n_kept, dq_kept, dk_kept, dv_kept, static_cast<float*>(ws), as_stream(stream));
+}
+
+size_t cf_layer_workspace_bytes(const cf_layer_desc* desc, int32_t max_kept) {
+    if (check_layer_desc(desc) != CF_OK || max_kept < 0) return 0;
+    return carve_layer(*desc, max_kept, nullptr).total;
+}
+
+cf_status cf_layer_bwd_filtered(const cf_layer_desc* desc, const cf_saved* saved, const cf_weights* w,
+                                const void* dy_full, const uint8_t* mask, cf_grads* grads,
+                                int32_t* idx_out, int32_t* cu_kept_out, int32_t* n_kept_host, void* ws,
+                                size_t ws_bytes, cf_stream stream) {
+    cf_status s = check_layer_desc(desc);
+    if (s != CF_OK) return s;
+    s = check_layer_ptrs(saved, w, dy_full, grads);
+    if (s != CF_OK) return s;
+    if (!mask || !n_kept_host) return CF_ERR_NULL;
+    if ((idx_out && misaligned(idx_out, 4)) || (cu_kept_out && misaligned(cu_kept_out, 4)))
+        return CF_ERR_SHAPE;
+    const int T = desc->B * desc->S;
+    if (!ws || misaligned(ws, 256)) return CF_ERR_WORKSPACE;
+    // the kept count is not known yet: the workspace must at least hold the index part,
+    // and after the count is known it must hold the layout for that count
+    LayerWs w0 = carve_layer(*desc, 0, ws);
+    if (ws_bytes < w0.total) return CF_ERR_WORKSPACE;
+    hipStream_t st = as_stream(stream);
+    int32_t* idx = idx_out ? idx_out : w0.idx;
+    int32_t* cu = cu_kept_out ? cu_kept_out : w0.cu_kept;
+    CF_HIP(launch_keep_index(mask, desc->B, desc->S, idx, cu, w0.n_kept_dev, w0.index_ws, st));
+    CF_HIP(hipMemcpyAsync(n_kept_host, w0.n_kept_dev, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    CF_HIP(hipStreamSynchronize(st));
+    const int N = *n_kept_host;
+    if (N < 0 || N > T) return CF_ERR_HIP;
+    LayerWs wk = carve_layer(*desc, N, ws);
+    if (ws_bytes < wk.total) return CF_ERR_WORKSPACE;
+    if (N > 0)
+        CF_HIP(launch_gather(dy_full, (int64_t)desc->H * dtype_size(desc->dtype), idx, N, wk.dy_k, st));
+    return layer_core(*desc, *saved, *w, wk.dy_k, idx, cu, N, *grads, wk, st);
+}
+
+cf_status cf_layer_bwd_dense(const cf_layer_desc* desc, const cf_saved* saved, const cf_weights* w,
+                             const void* dy_full, cf_grads* grads, void* ws, size_t ws_bytes,
+                             cf_stream stream) {
+    cf_status s = check_layer_desc(desc);
+    if (s != CF_OK) return s;
+    s = check_layer_ptrs(saved, w, dy_full, grads);
+    if (s != CF_OK) return s;
+    const int T = desc->B * desc->S;
+    if (!ws || misaligned(ws, 256)) return CF_ERR_WORKSPACE;
+    LayerWs wk = carve_layer(*desc, T, ws);
+    if (ws_bytes < wk.total) return CF_ERR_WORKSPACE;
+    return layer_core(*desc, *saved, *w, dy_full, nullptr, nullptr, T, *grads, wk, as_stream(stream));
+}
+
+}  // extern "C"

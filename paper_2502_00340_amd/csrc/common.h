@@ -1,0 +1,126 @@
+// Internal helpers shared by the HIP translation units of the library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "centrifuge.h"
+
+namespace cf {
+
+typedef unsigned short bf16_t;   // raw bfloat16 bits
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t h) {
+    return __uint_as_float(((unsigned)h) << 16);
+}
+
+// round-to-nearest-even; inputs are finite in every use here
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    unsigned u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
+    return (unsigned)f32_to_bf16(lo) | ((unsigned)f32_to_bf16(hi) << 16);
+}
+
+// 16-byte vector access of VN elements, widened to fp32
+template <typename T> struct Vec;
+
+template <> struct Vec<float> {
+    static constexpr int N = 4;
+    __device__ static __forceinline__ void load(const float* p, float (&o)[4]) {
+        float4 v = *reinterpret_cast<const float4*>(p);
+        o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+    }
+    __device__ static __forceinline__ void store(float* p, const float (&i)[4]) {
+        *reinterpret_cast<float4*>(p) = make_float4(i[0], i[1], i[2], i[3]);
+    }
+};
+
+template <> struct Vec<bf16_t> {
+    static constexpr int N = 8;
+    __device__ static __forceinline__ void load(const bf16_t* p, float (&o)[8]) {
+        uint4 v = *reinterpret_cast<const uint4*>(p);
+        unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            o[2 * i] = __uint_as_float(w[i] << 16);
+            o[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+        }
+    }
+    __device__ static __forceinline__ void store(bf16_t* p, const float (&i)[8]) {
+        uint4 v;
+        v.x = pack_bf16x2(i[0], i[1]);
+        v.y = pack_bf16x2(i[2], i[3]);
+        v.z = pack_bf16x2(i[4], i[5]);
+        v.w = pack_bf16x2(i[6], i[7]);
+        *reinterpret_cast<uint4*>(p) = v;
+    }
+};
+
+template <typename T> __device__ __forceinline__ float to_f32(T v);
+template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f32<bf16_t>(bf16_t v) { return bf16_to_f32(v); }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return f32_to_bf16(v); }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+static inline size_t dtype_size(int dtype) { return dtype == CF_F32 ? 4 : 2; }
+
+// ---- internal launchers (one per translation unit) --------------------------
+
+// index.hip
+size_t index_ws_bytes(int64_t n_tokens);
+hipError_t launch_keep_index(const uint8_t* mask, int B, int S, int32_t* idx, int32_t* cu_kept,
+                             int32_t* n_kept_dev, void* ws, hipStream_t st);
+hipError_t launch_gather(const void* src, int64_t cols_bytes, const int32_t* idx, int n_rows,
+                         void* dst, hipStream_t st);
+
+// rowlocal.hip
+hipError_t launch_swiglu_fwd(int dtype, const void* gate, const void* up, const int32_t* idx,
+                             int n_rows, int F, void* act, hipStream_t st);
+hipError_t launch_swiglu_bwd(int dtype, const void* d_act, const void* gate, const void* up,
+                             const int32_t* idx, int n_rows, int F, void* d_gate, void* d_up,
+                             hipStream_t st);
+hipError_t launch_rmsnorm_fwd(int dtype, const void* x, const void* g, const int32_t* idx,
+                              int n_rows, int H, float eps, void* h, hipStream_t st);
+// dx_out = res + rmsnorm_bwd(dh; x, g); dg_partial is [rmsnorm_bwd_blocks(n_rows), H] fp32 scratch
+int rmsnorm_bwd_blocks(int n_rows);
+hipError_t launch_rmsnorm_bwd(int dtype, const void* dh, const void* x, const void* g,
+                              const int32_t* idx, const void* res, int n_rows, int H, float eps,
+                              void* dx_out, float* dg_partial, void* dg_out, hipStream_t st);
+hipError_t launch_attn_rowdot(int dtype, const void* da, const void* a, int n_rows, int Hq, int d,
+                              float* D, hipStream_t st);
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st);
+
+// gemm.hip
+struct GemmSeg {
+    const void* A;
+    const void* B;
+    int K;
+};
+// C[M,N] = beta*C + sum_seg op(A_seg)*op(B_seg); all matrices dense row-major.
+//   mode 0 ("NT"): A_seg [M,K], B_seg [N,K]      (C = A * B^T)
+//   mode 1 ("TN"): A_seg [K,M], B_seg [K,N]      (C = A^T * B)
+hipError_t launch_gemm(int dtype, int mode, const GemmSeg* segs, int nseg, void* C, int M, int N,
+                       float beta, hipStream_t st);
+
+// attn.hip
+size_t attn_ws_bytes(const cf_layer_desc& d, int n_kept);
+hipError_t launch_attn_bwd(const cf_layer_desc& d, const void* q_kept, const void* k_full,
+                           const void* v_full, const void* o_kept, const float* lse_full,
+                           const void* do_kept, const int32_t* idx, const int32_t* cu_kept,
+                           int n_kept, void* dq_kept, void* dk_kept, void* dv_kept, void* ws,
+                           hipStream_t st);
+
+}  // namespace cf

@@ -1,0 +1,302 @@
+// Row-local backward operators on kept rows (Sec. 3.2: element-wise products
+// of a row-sparse gradient inherit its row sparsity).  Every kernel takes an
+// optional kept-row index for tensors that are still stored full length, so
+// the gather of those tensors is folded into the read.  Arithmetic is fp32;
+// storage is fp32 or bf16.  All of them are HBM-bound streaming kernels.
+#include "common.h"
+
+namespace cf {
+
+__device__ __forceinline__ float sigmoidf_(float z) { return 1.0f / (1.0f + __expf(-z)); }
+
+// act[j,:] = silu(gate[row,:]) * up[row,:],   row = idx ? idx[j] : j
+template <typename T>
+__global__ __launch_bounds__(256) void swiglu_fwd_kernel(const T* __restrict__ gate,
+                                                         const T* __restrict__ up,
+                                                         const int32_t* __restrict__ idx,
+                                                         int n_rows, int F, T* __restrict__ act) {
+    constexpr int VN = Vec<T>::N;
+    const int vpr = F / VN;
+    const int64_t total = (int64_t)n_rows * vpr;
+    for (int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x; v < total; v += (int64_t)gridDim.x * 256) {
+        const int j = (int)(v / vpr);
+        const int c = (int)(v % vpr) * VN;
+        const int64_t row = idx ? idx[j] : j;
+        float g[VN], u[VN], a[VN];
+        Vec<T>::load(gate + row * F + c, g);
+        Vec<T>::load(up + row * F + c, u);
+#pragma unroll
+        for (int e = 0; e < VN; ++e) a[e] = g[e] * sigmoidf_(g[e]) * u[e];
+        Vec<T>::store(act + (int64_t)j * F + c, a);
+    }
+}
+
+// d_gate = d_act * up * s(1 + gate(1-s)), d_up = d_act * gate * s,  s = sigmoid(gate)
+template <typename T>
+__global__ __launch_bounds__(256) void swiglu_bwd_kernel(const T* __restrict__ d_act,
+                                                         const T* __restrict__ gate,
+                                                         const T* __restrict__ up,
+                                                         const int32_t* __restrict__ idx,
+                                                         int n_rows, int F, T* __restrict__ d_gate,
+                                                         T* __restrict__ d_up) {
+    constexpr int VN = Vec<T>::N;
+    const int vpr = F / VN;
+    const int64_t total = (int64_t)n_rows * vpr;
+    for (int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x; v < total; v += (int64_t)gridDim.x * 256) {
+        const int j = (int)(v / vpr);
+        const int c = (int)(v % vpr) * VN;
+        const int64_t row = idx ? idx[j] : j;
+        float g[VN], u[VN], da[VN], dg[VN], du[VN];
+        Vec<T>::load(gate + row * F + c, g);
+        Vec<T>::load(up + row * F + c, u);
+        Vec<T>::load(d_act + (int64_t)j * F + c, da);
+#pragma unroll
+        for (int e = 0; e < VN; ++e) {
+            const float s = sigmoidf_(g[e]);
+            dg[e] = da[e] * u[e] * s * (1.0f + g[e] * (1.0f - s));
+            du[e] = da[e] * g[e] * s;
+        }
+        Vec<T>::store(d_gate + (int64_t)j * F + c, dg);
+        Vec<T>::store(d_up + (int64_t)j * F + c, du);
+    }
+}
+
+static constexpr int RMS_MAX_VEC = 8;   // 16-byte vectors per thread: H <= 256*8*VN
+
+__device__ __forceinline__ void block_sum2(float& a, float& b, float* red /*8 floats*/) {
+    a = wave_sum(a);
+    b = wave_sum(b);
+    const int wave = threadIdx.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) { red[wave] = a; red[4 + wave] = b; }
+    __syncthreads();
+    a = red[0] + red[1] + red[2] + red[3];
+    b = red[4] + red[5] + red[6] + red[7];
+}
+
+// h[j,:] = x[row,:] * rstd * g,  rstd = (mean(x^2) + eps)^-1/2
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const T* __restrict__ x,
+                                                          const T* __restrict__ g,
+                                                          const int32_t* __restrict__ idx,
+                                                          int n_rows, int H, float eps,
+                                                          T* __restrict__ h) {
+    constexpr int VN = Vec<T>::N;
+    __shared__ float red[8];
+    const int vpr = H / VN;
+    for (int j = blockIdx.x; j < n_rows; j += gridDim.x) {
+        const int64_t row = idx ? idx[j] : j;
+        float xv[RMS_MAX_VEC][VN];
+        float ss = 0.f, dummy = 0.f;
+#pragma unroll
+        for (int i = 0; i < RMS_MAX_VEC; ++i) {
+            const int v = threadIdx.x + i * 256;
+            if (v < vpr) {
+                Vec<T>::load(x + row * H + v * VN, xv[i]);
+#pragma unroll
+                for (int e = 0; e < VN; ++e) ss += xv[i][e] * xv[i][e];
+            }
+        }
+        block_sum2(ss, dummy, red);
+        const float rstd = rsqrtf(ss / (float)H + eps);
+#pragma unroll
+        for (int i = 0; i < RMS_MAX_VEC; ++i) {
+            const int v = threadIdx.x + i * 256;
+            if (v < vpr) {
+                float gv[VN], o[VN];
+                Vec<T>::load(g + v * VN, gv);
+#pragma unroll
+                for (int e = 0; e < VN; ++e) o[e] = xv[i][e] * rstd * gv[e];
+                Vec<T>::store(h + (int64_t)j * H + v * VN, o);
+            }
+        }
+    }
+}
+
+// dx_out[j,:] = res[j,:] + rstd*(u - n*mean(u*n)),  n = x*rstd, u = dh*g
+// dg_partial[block,:] = sum over the block's rows of dh*n
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ dh,
+                                                          const T* __restrict__ x,
+                                                          const T* __restrict__ g,
+                                                          const int32_t* __restrict__ idx,
+                                                          const T* __restrict__ res, int n_rows,
+                                                          int H, float eps, T* __restrict__ dx_out,
+                                                          float* __restrict__ dg_partial) {
+    constexpr int VN = Vec<T>::N;
+    __shared__ float red[8];
+    const int vpr = H / VN;
+    float gv[RMS_MAX_VEC][VN], dgacc[RMS_MAX_VEC][VN];
+#pragma unroll
+    for (int i = 0; i < RMS_MAX_VEC; ++i) {
+        const int v = threadIdx.x + i * 256;
+#pragma unroll
+        for (int e = 0; e < VN; ++e) { dgacc[i][e] = 0.f; gv[i][e] = 0.f; }
+        if (v < vpr) Vec<T>::load(g + v * VN, gv[i]);
+    }
+    for (int j = blockIdx.x; j < n_rows; j += gridDim.x) {
+        const int64_t row = idx ? idx[j] : j;
+        float xv[RMS_MAX_VEC][VN], dv[RMS_MAX_VEC][VN];
+        float ss = 0.f, sd = 0.f;
+#pragma unroll
+        for (int i = 0; i < RMS_MAX_VEC; ++i) {
+            const int v = threadIdx.x + i * 256;
+            if (v < vpr) {
+                Vec<T>::load(x + row * H + v * VN, xv[i]);
+                Vec<T>::load(dh + (int64_t)j * H + v * VN, dv[i]);
+#pragma unroll
+                for (int e = 0; e < VN; ++e) {
+                    ss += xv[i][e] * xv[i][e];
+                    sd += dv[i][e] * gv[i][e] * xv[i][e];
+                }
+            }
+        }
+        block_sum2(ss, sd, red);
+        const float rstd = rsqrtf(ss / (float)H + eps);
+        const float c = sd * rstd / (float)H;          // mean(u*n)
+#pragma unroll
+        for (int i = 0; i < RMS_MAX_VEC; ++i) {
+            const int v = threadIdx.x + i * 256;
+            if (v < vpr) {
+                float rv[VN], o[VN];
+                Vec<T>::load(res + (int64_t)j * H + v * VN, rv);
+#pragma unroll
+                for (int e = 0; e < VN; ++e) {
+                    const float n = xv[i][e] * rstd;
+                    o[e] = rv[e] + rstd * (dv[i][e] * gv[i][e] - n * c);
+                    dgacc[i][e] += dv[i][e] * n;
+                }
+                Vec<T>::store(dx_out + (int64_t)j * H + v * VN, o);
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < RMS_MAX_VEC; ++i) {
+        const int v = threadIdx.x + i * 256;
+        if (v < vpr) {
+#pragma unroll
+            for (int e = 0; e < VN; ++e) dg_partial[(int64_t)blockIdx.x * H + v * VN + e] = dgacc[i][e];
+        }
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_finish_kernel(const float* __restrict__ partial,
+                                                            int nblk, int H, T* __restrict__ out) {
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= H) return;
+    float s = 0.f;
+    for (int b = 0; b < nblk; ++b) s += partial[(int64_t)b * H + c];
+    out[c] = from_f32<T>(s);
+}
+
+// D[j,h] = sum_c da[j,h*d+c] * a[j,h*d+c]   (the FlashAttention-backward row term)
+template <typename T>
+__global__ __launch_bounds__(256) void attn_rowdot_kernel(const T* __restrict__ da,
+                                                          const T* __restrict__ a, int n_rows,
+                                                          int Hq, int d, float* __restrict__ D) {
+    constexpr int VN = Vec<T>::N;
+    const int lanes = d / VN;                    // lanes per (row, head): power of two <= 64
+    const int64_t total = (int64_t)n_rows * Hq * lanes;
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    float s = 0.f;
+    int64_t pair = gid / lanes;
+    if (gid < total) {
+        const int part = (int)(gid % lanes);
+        float p[VN], q[VN];
+        Vec<T>::load(da + pair * d + part * VN, p);
+        Vec<T>::load(a + pair * d + part * VN, q);
+#pragma unroll
+        for (int e = 0; e < VN; ++e) s += p[e] * q[e];
+    }
+    for (int o = lanes >> 1; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+    if (gid < total && (gid % lanes) == 0) D[pair] = s;
+}
+
+// ---------------------------------------------------------------------------
+
+static int stream_grid(int64_t vec_total) {
+    int64_t g = (vec_total + 255) / 256;
+    if (g > 256 * 32) g = 256 * 32;
+    if (g < 1) g = 1;
+    return (int)g;
+}
+
+hipError_t launch_swiglu_fwd(int dtype, const void* gate, const void* up, const int32_t* idx,
+                             int n_rows, int F, void* act, hipStream_t st) {
+    if (n_rows <= 0) return hipSuccess;
+    if (dtype == CF_F32)
+        swiglu_fwd_kernel<float><<<stream_grid((int64_t)n_rows * F / 4), 256, 0, st>>>(
+            (const float*)gate, (const float*)up, idx, n_rows, F, (float*)act);
+    else
+        swiglu_fwd_kernel<bf16_t><<<stream_grid((int64_t)n_rows * F / 8), 256, 0, st>>>(
+            (const bf16_t*)gate, (const bf16_t*)up, idx, n_rows, F, (bf16_t*)act);
+    return hipGetLastError();
+}
+
+hipError_t launch_swiglu_bwd(int dtype, const void* d_act, const void* gate, const void* up,
+                             const int32_t* idx, int n_rows, int F, void* d_gate, void* d_up,
+                             hipStream_t st) {
+    if (n_rows <= 0) return hipSuccess;
+    if (dtype == CF_F32)
+        swiglu_bwd_kernel<float><<<stream_grid((int64_t)n_rows * F / 4), 256, 0, st>>>(
+            (const float*)d_act, (const float*)gate, (const float*)up, idx, n_rows, F,
+            (float*)d_gate, (float*)d_up);
+    else
+        swiglu_bwd_kernel<bf16_t><<<stream_grid((int64_t)n_rows * F / 8), 256, 0, st>>>(
+            (const bf16_t*)d_act, (const bf16_t*)gate, (const bf16_t*)up, idx, n_rows, F,
+            (bf16_t*)d_gate, (bf16_t*)d_up);
+    return hipGetLastError();
+}
+
+hipError_t launch_rmsnorm_fwd(int dtype, const void* x, const void* g, const int32_t* idx,
+                              int n_rows, int H, float eps, void* h, hipStream_t st) {
+    if (n_rows <= 0) return hipSuccess;
+    const int grid = n_rows < 256 * 16 ? n_rows : 256 * 16;
+    if (dtype == CF_F32)
+        rmsnorm_fwd_kernel<float><<<grid, 256, 0, st>>>((const float*)x, (const float*)g, idx,
+                                                        n_rows, H, eps, (float*)h);
+    else
+        rmsnorm_fwd_kernel<bf16_t><<<grid, 256, 0, st>>>((const bf16_t*)x, (const bf16_t*)g, idx,
+                                                         n_rows, H, eps, (bf16_t*)h);
+    return hipGetLastError();
+}
+
+int rmsnorm_bwd_blocks(int n_rows) {
+    if (n_rows < 1) return 1;
+    return n_rows < 512 ? n_rows : 512;
+}
+
+hipError_t launch_rmsnorm_bwd(int dtype, const void* dh, const void* x, const void* g,
+                              const int32_t* idx, const void* res, int n_rows, int H, float eps,
+                              void* dx_out, float* dg_partial, void* dg_out, hipStream_t st) {
+    const int nblk = rmsnorm_bwd_blocks(n_rows);
+    if (n_rows <= 0) return launch_fill_zero(dg_out, (size_t)H * dtype_size(dtype), st);
+    if (dtype == CF_F32) {
+        rmsnorm_bwd_kernel<float><<<nblk, 256, 0, st>>>((const float*)dh, (const float*)x,
+                                                        (const float*)g, idx, (const float*)res,
+                                                        n_rows, H, eps, (float*)dx_out, dg_partial);
+        colsum_finish_kernel<float><<<ceil_div(H, 256), 256, 0, st>>>(dg_partial, nblk, H, (float*)dg_out);
+    } else {
+        rmsnorm_bwd_kernel<bf16_t><<<nblk, 256, 0, st>>>((const bf16_t*)dh, (const bf16_t*)x,
+                                                         (const bf16_t*)g, idx, (const bf16_t*)res,
+                                                         n_rows, H, eps, (bf16_t*)dx_out, dg_partial);
+        colsum_finish_kernel<bf16_t><<<ceil_div(H, 256), 256, 0, st>>>(dg_partial, nblk, H, (bf16_t*)dg_out);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_rowdot(int dtype, const void* da, const void* a, int n_rows, int Hq, int d,
+                              float* D, hipStream_t st) {
+    if (n_rows <= 0) return hipSuccess;
+    const int vn = dtype == CF_F32 ? 4 : 8;
+    const int64_t total = (int64_t)n_rows * Hq * (d / vn);
+    const int grid = (int)((total + 255) / 256);
+    if (dtype == CF_F32)
+        attn_rowdot_kernel<float><<<grid, 256, 0, st>>>((const float*)da, (const float*)a, n_rows, Hq, d, D);
+    else
+        attn_rowdot_kernel<bf16_t><<<grid, 256, 0, st>>>((const bf16_t*)da, (const bf16_t*)a, n_rows, Hq, d, D);
+    return hipGetLastError();
+}
+
+}  // namespace cf
