@@ -1,0 +1,260 @@
+#!/usr/bin/env python3
+"""Benchmark of the token-filtered decoder-layer backward on one MI355X.
+
+A "step" is one pass of the whole hot path over one synthetic batch:
+keep mask -> keep index -> gathers -> reduced GEMMs, row-local ops, filtered
+attention backward -> compact dx + all parameter gradients
+(cf_layer_bwd_filtered).  Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line.  `value` = kept tokens per second of the filtered layer
+backward at keep ratio 0.5 on the Llama-3.1-8B-shaped layer (config 3); the
+same line carries the speedup over the library's own dense backward, a keep
+ratio sweep, the roofline of the dominant kernel (live HIP-event timing) and
+the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+import torch
+
+from paper_2502_00340_amd import binding as Bn
+from paper_2502_00340_amd import workloads as WL
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+DEV = "cuda:0"
+
+
+def log(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
+def to_dev(a: np.ndarray, dtype: str) -> torch.Tensor:
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(DEV)
+    return t.to(torch.bfloat16) if dtype == "bf16" else t
+
+
+def forward_fixture(q, k, v, shape: WL.LayerShape):
+    """attn_out and lse consistent with the drawn (q, k, v): plain torch on the
+    GPU, input preparation only (outside every timed region)."""
+    B, S, Hq, Hkv, d = shape.B, shape.S, shape.Hq, shape.Hkv, shape.d
+    G = Hq // Hkv
+    scale = 1.0 / math.sqrt(d)
+    out = torch.empty((B * S, Hq * d), dtype=torch.float32, device=DEV)
+    lse = torch.empty((B, Hq, S), dtype=torch.float32, device=DEV)
+    future = torch.triu(torch.ones(S, S, dtype=torch.bool, device=DEV), 1)
+    for b in range(B):
+        rows = slice(b * S, (b + 1) * S)
+        for h in range(Hq):
+            g = h // G
+            sc = (q[rows, h * d:(h + 1) * d].float() @ k[rows, g * d:(g + 1) * d].float().T) * scale
+            sc.masked_fill_(future, float("-inf"))
+            l = torch.logsumexp(sc, dim=1)
+            out[rows, h * d:(h + 1) * d] = torch.exp(sc - l[:, None]) @ v[rows, g * d:(g + 1) * d].float()
+            lse[b, h] = l
+    return out.to(q.dtype), lse
+
+
+def make_inputs(shape: WL.LayerShape, seed: int):
+    rng = np.random.default_rng(seed)
+    W = {k: to_dev(v, shape.dtype) for k, v in WL.make_weights(shape, rng).items()}
+    sv = {k: to_dev(v, shape.dtype) for k, v in WL.make_independent_activations(shape, rng).items()}
+    sv["attn_out"], sv["lse"] = forward_fixture(sv["q"], sv["k"], sv["v"], shape)
+    dy = to_dev(WL.make_normal(rng, shape.T, shape.H), shape.dtype)
+    mask = WL.make_mask(shape, rng)
+    return W, sv, dy, mask, rng
+
+
+def attn_alg_flops(shape: WL.LayerShape, mask: np.ndarray) -> float:
+    """2*d*Hq * sum over kept tokens of [3*(p+1) + 2*(c+1)]: three products over all
+    p+1 visible keys (S, dP, dS*K) and two over the c+1 kept keys (dV, dK)."""
+    tot = 0.0
+    for b in range(shape.B):
+        pos = np.flatnonzero(mask[b]).astype(np.float64)
+        rank = np.arange(len(pos), dtype=np.float64)
+        tot += float(np.sum(3.0 * (pos + 1.0) + 2.0 * (rank + 1.0)))
+    return 2.0 * shape.d * shape.Hq * tot
+
+
+def layer_alg_flops(shape: WL.LayerShape, mask: np.ndarray) -> float:
+    n_k = int(mask.sum())
+    return 4.0 * shape.P_layer * n_k + attn_alg_flops(shape, mask)
+
+
+def time_steps(fn, steps: int, warmup: int) -> float:
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def event_times(fn, reps: int, warmup: int = 2):
+    """Per-call durations (ms) from HIP events recorded on torch's current
+    stream, which is the stream the binding launches on."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    out = []
+    for _ in range(reps):
+        s = torch.cuda.Event(enable_timing=True)
+        e = torch.cuda.Event(enable_timing=True)
+        s.record()
+        fn()
+        e.record()
+        e.synchronize()
+        out.append(s.elapsed_time(e))
+    return out
+
+
+def roofline_leg(shape: WL.LayerShape, n_k: int, reps: int = 20):
+    """Dominant kernel: the parameter-gradient GEMM dW = X_kept^T * dY_kept (the
+    contraction runs over the kept tokens) at the layer's largest shape, the FFN
+    projections [F x H x N_k]."""
+    dt = torch.bfloat16
+    x = torch.randn((n_k, shape.F), device=DEV).to(dt)
+    dy = torch.randn((n_k, shape.H), device=DEV).to(dt)
+    dw = torch.empty((shape.F, shape.H), dtype=dt, device=DEV)
+
+    # raw call with a pre-allocated output keeps allocator work out of the event window
+    lib = Bn.lib()
+    import ctypes as C
+
+    def call_raw():
+        rc = lib.cf_linear_bwd_reduced(C.c_void_p(x.data_ptr()), C.c_void_p(dy.data_ptr()), None, n_k,
+                                       shape.F, shape.H, Bn.CF_BF16, None, C.c_void_p(dw.data_ptr()),
+                                       0.0, C.c_void_p(torch.cuda.current_stream().cuda_stream))
+        assert rc == 0, rc
+
+    ms = event_times(call_raw, reps)
+    avg = sum(ms) / len(ms)
+    flops = 2.0 * n_k * shape.F * shape.H
+    ach = flops / (avg * 1e-3) / 1e12
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("gemm_tn_dwd_bytes_per_launch")
+        except Exception:
+            traffic = None
+    return {"bound": "mfma", "achieved": round(ach, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
+            "kernel": "gemm_bf16_kernel<TN,4,4> dW[F,H] = X_kept^T dY_kept",
+            "flops_per_launch": flops, "avg_launch_ms": round(avg, 4), "launches": reps}
+
+
+def cpu_baseline_leg(shape: WL.LayerShape, W, sv, dy, mask):
+    """The CPU oracle (fp32 arrays, numpy) on a bounded sample of the same
+    workload: the first sequence of the batch."""
+    from oracle import layer_oracle as O      # cpu_baseline leg only
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count()
+    S = shape.S
+    rows = slice(0, S)
+    f = lambda t: t[rows].float().cpu().numpy()
+    saved = {k: f(v) for k, v in sv.items() if k != "lse"}
+    saved["lse"] = sv["lse"][0:1].float().cpu().numpy()
+    Wn = {k: v.float().cpu().numpy() for k, v in W.items()}
+    m = mask[0:1]
+    t0 = time.perf_counter()
+    O.layer_bwd(saved, Wn, f(dy), m, B=1, S=S, Hq=shape.Hq, Hkv=shape.Hkv, d=shape.d)
+    dt = time.perf_counter() - t0
+    n_k = int(m.sum())
+    return {"value": round(n_k / dt, 1), "unit": "kept-tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": "numpy fp32 oracle, filtered backward of sequence 0 only (B=1,S=%d, %d kept tokens), %.1f s"
+                      % (S, n_k, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=3, help="index into the workload table (default: 8B shape)")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the keep-ratio sweep")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on one GPU only (collectives and sharding are out of scope); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    Bn.lib()        # fail loudly if the HIP library is missing
+
+    shape = WL.CONFIGS[a.config]
+    log("config %d %s: generating inputs" % (a.config, shape.name))
+    W, sv, dy, mask, rng = make_inputs(shape, WL.config_seed(a.config))
+    mask_dev = torch.from_numpy(mask).to(DEV)
+    desc = Bn.make_desc(shape.B, shape.S, shape.H, shape.Hq, shape.Hkv, shape.d, shape.F, shape.dtype)
+    plan = Bn.LayerBackward(desc, device=DEV)
+    n_k = int(mask.sum())
+
+    log("timing filtered backward (n_kept=%d of %d)" % (n_k, shape.T))
+    t_f = time_steps(lambda: plan.filtered(sv, W, dy, mask_dev), a.steps, a.warmup)
+    ev_f = event_times(lambda: plan.filtered(sv, W, dy, mask_dev), a.steps, 0)
+    log("timing dense backward")
+    t_d = time_steps(lambda: plan.dense(sv, W, dy), a.steps, a.warmup)
+    flops_f = layer_alg_flops(shape, mask)
+    flops_d = layer_alg_flops(shape, np.ones_like(mask))
+
+    sweep = {}
+    if not a.no_sweep:
+        for rho in (1.0, 0.7, 0.5, 0.3):
+            m = WL.mask_topk(rng, shape.B, shape.S, rho)
+            md = torch.from_numpy(m).to(DEV)
+            t = time_steps(lambda: plan.filtered(sv, W, dy, md), a.steps, a.warmup)
+            sweep["%.1f" % rho] = {"ms": round(t * 1e3, 4), "speedup_vs_dense": round(t_d / t, 4),
+                                   "kept_tokens_per_s": round(int(m.sum()) / t, 1),
+                                   "tflops": round(layer_alg_flops(shape, m) / t / 1e12, 1)}
+            log("rho %.1f: %.3f ms, speedup %.3f" % (rho, t * 1e3, t_d / t))
+
+    log("roofline leg")
+    roof = roofline_leg(shape, n_k)
+    cpu = None
+    if not a.no_cpu:
+        log("cpu oracle leg")
+        cpu = cpu_baseline_leg(shape, W, sv, dy, mask)
+
+    tfl = flops_f / t_f / 1e12
+    out = {
+        "metric": "filtered layer-bwd kept-tokens/s + speedup vs dense bwd at 50% keep; MFMA % peak",
+        "value": round(n_k / t_f, 1), "unit": "kept-tokens/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(t_f * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": shape.dtype,
+        "data": "synthetic",
+        "config": {"workload": "config %d: %s layer, B=%d S=%d H=%d Hq=%d Hkv=%d d=%d F=%d, keep ratio %.2f, mask %s"
+                               % (a.config, shape.name, shape.B, shape.S, shape.H, shape.Hq, shape.Hkv, shape.d,
+                                  shape.F, n_k / shape.T, shape.mask_kind),
+                   "n_kept": n_k, "tokens": shape.T},
+        "speedup_vs_dense": round(t_d / t_f, 4),
+        "dense_ms_per_step": round(t_d * 1e3, 4),
+        "median_ms_per_step_events": round(float(np.median(ev_f)), 4),
+        "algorithmic_tflops": round(tfl, 1), "mfma_frac_of_peak_layer": round(tfl / PEAK_BF16_TFLOPS, 4),
+        "dense_algorithmic_tflops": round(flops_d / t_d / 1e12, 1),
+        "keep_ratio_sweep": sweep,
+        "roofline": roof,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
