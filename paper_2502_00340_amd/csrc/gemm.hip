@@ -45,20 +45,57 @@ __device__ __forceinline__ int nt_lds_off(int row, int chunk) {
     return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4);
 }
 
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
+// Workgroup barrier that orders LDS traffic only: global loads that are still
+// in flight (the register prefetch of a later K-step) stay in flight.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+#define CF_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// Buffer resource over [base, base+bytes): loads past the end return zeros, which is
+// how ragged tiles are predicated without branches.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, int64_t bytes) {
+    const int64_t lim = bytes < 0 ? 0 : (bytes > 0xFFFFFFFFll ? 0xFFFFFFFFll : bytes);
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)(unsigned)lim, 0x00020000);
+}
+
+// Tile order: consecutive logical tiles form bands of GROUP_M tile rows walked
+// column by column, and each of the 8 XCDs (block id mod 8) takes one contiguous
+// run of logical tiles, so the blocks resident on one XCD share operand panels
+// in that XCD's L2.
+__device__ __forceinline__ void tile_coords(int pid, int tiles_m, int tiles_n, int& bm, int& bn) {
+    constexpr int GROUP_M = 8;
+    const int nb = tiles_m * tiles_n;
+    const int xcd = pid & 7, local = pid >> 3;
+    const int base = nb >> 3, rem = nb & 7;
+    const int l = xcd * base + (xcd < rem ? xcd : rem) + local;
+    const int band = l / (GROUP_M * tiles_n);
+    const int first_m = band * GROUP_M;
+    const int gsize = min(GROUP_M, tiles_m - first_m);
+    const int r = l - band * GROUP_M * tiles_n;
+    bm = first_m + r % gsize;
+    bn = r / gsize;
+}
+
 template <int MODE, int TM, int TN>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     constexpr int BM = 2 * TM * 32, BN = 2 * TN * 32;
     constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
     constexpr int A_LD = BM / 32, B_LD = BN / 32;   // 16-byte chunks per thread per tile
+    constexpr unsigned OOB = 0xFFFFFFFFu;
     extern __shared__ __align__(16) unsigned char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int slot = lane & 31, hh = lane >> 5;
 
-    // tile mapping: consecutive blocks walk down M inside a band of 8 N-tiles... keep simple:
-    const int tiles_m = (g.M + BM - 1) / BM;
-    const int bm = blockIdx.x % tiles_m, bn = blockIdx.x / tiles_m;
+    int bm, bn;
+    tile_coords(blockIdx.x, (g.M + BM - 1) / BM, (g.N + BN - 1) / BN, bm, bn);
     const int m0 = bm * BM, n0 = bn * BN;
 
     f32x16_t acc[TM][TN];
@@ -69,49 +106,62 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    uint4 ra[A_LD], rb[B_LD];
-
     int total_steps = 0;
     for (int s = 0; s < g.nseg; ++s) total_steps += (g.K[s] + BK - 1) / BK;
 
-    // ---- global -> registers for K-step (seg, k0) --------------------------
-    auto load_global = [&](int seg, int k0) {
-        const bf16_t* A = static_cast<const bf16_t*>(g.A[seg]);
-        const bf16_t* B = static_cast<const bf16_t*>(g.B[seg]);
+    // ---- global -> registers: one K-step of both operand tiles -----------------
+    // Offsets are relative to the block's first row/column so they fit 32 bits.
+    u32x4_t ra[A_LD], rb[B_LD];
+    int seg = 0, k0 = 0;                 // K-step the NEXT issue_global() fetches
+    __amdgpu_buffer_rsrc_t rsA, rsB;
+    auto open_segment = [&](int s) {
+        const bf16_t* A = static_cast<const bf16_t*>(g.A[s]);
+        const bf16_t* B = static_cast<const bf16_t*>(g.B[s]);
+        const int64_t K = g.K[s];
+        if (MODE == 0) {
+            rsA = make_rsrc(A + (int64_t)m0 * K, ((int64_t)g.M - m0) * K * 2);
+            rsB = make_rsrc(B + (int64_t)n0 * K, ((int64_t)g.N - n0) * K * 2);
+        } else {
+            rsA = make_rsrc(A + m0, (K * g.M - m0) * 2);
+            rsB = make_rsrc(B + n0, (K * g.N - n0) * 2);
+        }
+    };
+    auto issue_global = [&]() {
         const int K = g.K[seg];
         if (MODE == 0) {
-            const int c = tid & 7, kk = k0 + c * 8;
+            const int c = tid & 7;
+            const unsigned kb = (k0 + c * 8 < K) ? (unsigned)(k0 + c * 8) * 2u : OOB;
 #pragma unroll
             for (int i = 0; i < A_LD; ++i) {
-                const int row = (tid >> 3) + 32 * i;
-                const bool ok = (m0 + row < g.M) && (kk < K);
-                ra[i] = ok ? *reinterpret_cast<const uint4*>(A + (int64_t)(m0 + row) * K + kk)
-                           : make_uint4(0, 0, 0, 0);
+                const unsigned row = (tid >> 3) + 32 * i;
+                ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rsA, kb == OOB ? OOB : row * (unsigned)K * 2u + kb, 0, 0);
             }
 #pragma unroll
             for (int i = 0; i < B_LD; ++i) {
-                const int row = (tid >> 3) + 32 * i;
-                const bool ok = (n0 + row < g.N) && (kk < K);
-                rb[i] = ok ? *reinterpret_cast<const uint4*>(B + (int64_t)(n0 + row) * K + kk)
-                           : make_uint4(0, 0, 0, 0);
+                const unsigned row = (tid >> 3) + 32 * i;
+                rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rsB, kb == OOB ? OOB : row * (unsigned)K * 2u + kb, 0, 0);
             }
         } else {
 #pragma unroll
             for (int i = 0; i < A_LD; ++i) {
                 const int q = tid + 256 * i;
                 const int kr = q / (BM / 8), c = q % (BM / 8);
-                const bool ok = (k0 + kr < K) && (m0 + c * 8 < g.M);
-                ra[i] = ok ? *reinterpret_cast<const uint4*>(A + (int64_t)(k0 + kr) * g.M + m0 + c * 8)
-                           : make_uint4(0, 0, 0, 0);
+                const unsigned off = (unsigned)(k0 + kr) * (unsigned)g.M * 2u + c * 16u;
+                ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rsA, (m0 + c * 8 < g.M && k0 + kr < K) ? off : OOB, 0, 0);
             }
 #pragma unroll
             for (int i = 0; i < B_LD; ++i) {
                 const int q = tid + 256 * i;
                 const int kr = q / (BN / 8), c = q % (BN / 8);
-                const bool ok = (k0 + kr < K) && (n0 + c * 8 < g.N);
-                rb[i] = ok ? *reinterpret_cast<const uint4*>(B + (int64_t)(k0 + kr) * g.N + n0 + c * 8)
-                           : make_uint4(0, 0, 0, 0);
+                const unsigned off = (unsigned)(k0 + kr) * (unsigned)g.N * 2u + c * 16u;
+                rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rsB, (n0 + c * 8 < g.N && k0 + kr < K) ? off : OOB, 0, 0);
             }
+        }
+        k0 += BK;
+        if (k0 >= K) {
+            k0 = 0;
+            ++seg;
+            if (seg < g.nseg) open_segment(seg);
         }
     };
 
@@ -122,31 +172,33 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
             const int c = tid & 7;
 #pragma unroll
             for (int i = 0; i < A_LD; ++i)
-                *reinterpret_cast<uint4*>(sa + nt_lds_off((tid >> 3) + 32 * i, c)) = ra[i];
+                *reinterpret_cast<u32x4_t*>(sa + nt_lds_off((tid >> 3) + 32 * i, c)) = ra[i];
 #pragma unroll
             for (int i = 0; i < B_LD; ++i)
-                *reinterpret_cast<uint4*>(sb + nt_lds_off((tid >> 3) + 32 * i, c)) = rb[i];
+                *reinterpret_cast<u32x4_t*>(sb + nt_lds_off((tid >> 3) + 32 * i, c)) = rb[i];
         } else {
 #pragma unroll
             for (int i = 0; i < A_LD; ++i)
-                *reinterpret_cast<uint4*>(sa + (tid + 256 * i) * 16) = ra[i];
+                *reinterpret_cast<u32x4_t*>(sa + (tid + 256 * i) * 16) = ra[i];
 #pragma unroll
             for (int i = 0; i < B_LD; ++i)
-                *reinterpret_cast<uint4*>(sb + (tid + 256 * i) * 16) = rb[i];
+                *reinterpret_cast<u32x4_t*>(sb + (tid + 256 * i) * 16) = rb[i];
         }
     };
 
-    // ---- fragments of one 16-wide K sub-step ---------------------------------
-    auto load_frags_nt = [&](const unsigned char* tile, int row0, int ks, auto& frag, auto ntiles) {
+    // ---- LDS -> MFMA fragments of one 16-wide K sub-step ------------------------
+    struct Frags {
+        bf16x8_t a[TM], b[TN];
+    };
+    auto frags_nt = [&](const unsigned char* tile, int row0, int ks, bf16x8_t* frag, auto ntiles) {
         constexpr int NT_ = decltype(ntiles)::value;
 #pragma unroll
-        for (int i = 0; i < NT_; ++i) {
-            const uint4 v = *reinterpret_cast<const uint4*>(tile + nt_lds_off(row0 + i * 32 + slot, ks * 2 + hh));
-            frag[i] = __builtin_bit_cast(bf16x8_t, v);
-        }
+        for (int i = 0; i < NT_; ++i)
+            frag[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(
+                                                       tile + nt_lds_off(row0 + i * 32 + slot, ks * 2 + hh)));
     };
     // tile is [64][W] bf16 as in memory; the lane owns columns col0 + slot*NT_ .. +NT_-1
-    auto load_frags_tn = [&](const unsigned char* tile, int W, int col0, int ks, auto& frag, auto ntiles) {
+    auto frags_tn = [&](const unsigned char* tile, int W, int col0, int ks, bf16x8_t* frag, auto ntiles) {
         constexpr int NT_ = decltype(ntiles)::value;
         static_assert(NT_ == 2 || NT_ == 4, "TM/TN must be 2 or 4");
         unsigned r[8][NT_ / 2];
@@ -163,57 +215,79 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
         }
 #pragma unroll
         for (int i = 0; i < NT_; ++i) {
-            uint4 v;
-            unsigned w[4];
+            u32x4_t v;
 #pragma unroll
             for (int pq = 0; pq < 4; ++pq) {
                 const unsigned lo = r[2 * pq][i >> 1], hi = r[2 * pq + 1][i >> 1];
-                w[pq] = (i & 1) ? ((lo >> 16) | (hi & 0xFFFF0000u)) : ((lo & 0xFFFFu) | (hi << 16));
+                v[pq] = (i & 1) ? ((lo >> 16) | (hi & 0xFFFF0000u)) : ((lo & 0xFFFFu) | (hi << 16));
             }
-            v.x = w[0]; v.y = w[1]; v.z = w[2]; v.w = w[3];
             frag[i] = __builtin_bit_cast(bf16x8_t, v);
         }
     };
-
-    auto compute = [&](int stage) {
+    auto load_frags = [&](int stage, int ks, Frags& f) {
         const unsigned char* sa = smem + stage * STAGE;
         const unsigned char* sb = sa + A_BYTES;
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8_t fa[TM], fb[TN];
-            if (MODE == 0) {
-                load_frags_nt(sa, wm * TM * 32, ks, fa, std::integral_constant<int, TM>());
-                load_frags_nt(sb, wn * TN * 32, ks, fb, std::integral_constant<int, TN>());
-            } else {
-                load_frags_tn(sa, BM, wm * TM * 32, ks, fa, std::integral_constant<int, TM>());
-                load_frags_tn(sb, BN, wn * TN * 32, ks, fb, std::integral_constant<int, TN>());
-            }
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        if (MODE == 0) {
+            frags_nt(sa, wm * TM * 32, ks, f.a, std::integral_constant<int, TM>());
+            frags_nt(sb, wn * TN * 32, ks, f.b, std::integral_constant<int, TN>());
+        } else {
+            frags_tn(sa, BM, wm * TM * 32, ks, f.a, std::integral_constant<int, TM>());
+            frags_tn(sb, BN, wn * TN * 32, ks, f.b, std::integral_constant<int, TN>());
         }
     };
-
-    // ---- main loop over (segment, k0) steps, flattened ------------------------
-    int seg = 0, k0 = 0;
-    auto advance = [&]() {
-        k0 += BK;
-        if (k0 >= g.K[seg]) { k0 = 0; ++seg; }
+    auto mma = [&](const Frags& f) {
+#ifdef CF_EXP_NOMMA
+        if (g.beta == 123.f)
+#endif
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
     };
+
+    // ---- software-pipelined main loop ----------------------------------------------
+    // Iteration t multiplies tile t out of LDS stage t&1 while
+    //   * tile t+1 (fetched into registers during iteration t-1) is written to the other stage,
+    //   * tile t+2 is fetched from global memory into the same registers,
+    //   * fragments of the next 16-wide sub-step are read from LDS ahead of the MFMAs that
+    //     use the current ones.
+    // One LDS barrier per iteration, placed before the last sub-step so that the first
+    // fragments of tile t+1 are already on their way when iteration t+1 starts.
     if (total_steps > 0) {
-        load_global(seg, k0);
-        advance();
+        Frags f0, f1;
+        open_segment(0);
+        issue_global();
         store_lds(0);
-        __syncthreads();
-        for (int step = 0; step < total_steps; ++step) {
-            const int cur = step & 1;
-            const bool more = step + 1 < total_steps;
-            if (more) { load_global(seg, k0); advance(); }
-            compute(cur);
-            if (more) store_lds(cur ^ 1);
-            __syncthreads();
+        if (total_steps > 1) issue_global();
+        lds_barrier();
+        load_frags(0, 0, f0);
+        for (int t = 0; t < total_steps; ++t) {
+            const int cur = t & 1;
+#ifndef CF_EXP_NOSTORE
+            if (t + 1 < total_steps) store_lds(cur ^ 1);
+#endif
+#ifndef CF_EXP_NOGLOBAL
+            if (t + 2 < total_steps) issue_global();
+#endif
+            CF_SCHED_FENCE();
+            load_frags(cur, 1, f1);
+            CF_SCHED_FENCE();
+            mma(f0);
+            CF_SCHED_FENCE();
+            load_frags(cur, 2, f0);
+            CF_SCHED_FENCE();
+            mma(f1);
+            CF_SCHED_FENCE();
+            load_frags(cur, 3, f1);
+            CF_SCHED_FENCE();
+            mma(f0);
+            CF_SCHED_FENCE();
+            lds_barrier();
+            if (t + 1 < total_steps) load_frags(cur ^ 1, 0, f0);
+            CF_SCHED_FENCE();
+            mma(f1);
+            CF_SCHED_FENCE();
         }
     }
 
