@@ -9,15 +9,25 @@
 // between (e.g. d_gate*Wg^T + d_up*Wu^T).
 //
 // bf16 path: 32x32x16 bf16 MFMA, fp32 accumulators, 256 threads = 2x2 waves,
-// block tile (2*TM*32) x (2*TN*32) x 64, double-buffered LDS, global loads of
-// the next K-step issued before the MFMAs of the current one.
-//   NT tiles sit in LDS as [row][64] with the 16-byte chunk index XOR-swizzled
-//   by the row so that the 16 lanes of a ds_read_b128 hit distinct banks.
-//   TN tiles sit in LDS exactly as in memory ([k][m]); a lane reads, for 8
-//   consecutive k, the TM (TN) adjacent m (n) values it owns and transposes the
-//   8 x TM block of 16-bit values in registers.  Fragment i of a lane then
-//   belongs to output row  slot*TM + i  instead of  i*32 + slot; the epilogue
-//   undoes this, and gets TN adjacent columns per lane to store together.
+// block tile (2*TM*32) x (2*TN*32), K step 32, four LDS stages.
+//   * Operand tiles go from global memory straight into LDS (buffer_load ... lds,
+//     16 bytes per lane, no register hop); three K-steps are in flight while one
+//     is multiplied.  Ragged edges come from the buffer descriptor's range check,
+//     which returns zeros, so there are no branches around loads.
+//   * One LDS barrier per K-step, placed between the two 16-wide sub-steps, and the
+//     fragments of the next sub-step are read ahead of the MFMAs of the current one.
+//   * NT tiles sit in LDS as [row][32] (64-byte rows) with the 16-byte chunk index
+//     XOR-ed with (row/4)%4, which makes the 16 lanes of a ds_read_b128 hit distinct
+//     banks; a lane of the loading wave picks the global chunk that belongs in its
+//     (fixed) LDS slot.
+//   * TN tiles sit in LDS exactly as in memory ([k][m]); a lane reads, for 8
+//     consecutive k, the TM (TN) adjacent m (n) values it owns and transposes the
+//     8 x TM block of 16-bit values in registers.  Fragment i of a lane then
+//     belongs to output row  slot*TM + i  instead of  i*32 + slot.
+//   * The MFMA is issued with the operands swapped in NT mode (D = B-frag x A-frag),
+//     so in both modes a lane ends up with groups of 4 adjacent output columns; the
+//     epilogue packs them to bf16, stages the whole C tile in LDS (the operand
+//     stages are dead by then) and writes full rows with 16-byte stores.
 // fp32 path (check mode): plain LDS-tiled FMA kernel.
 #include <type_traits>
 
@@ -27,6 +37,8 @@ namespace cf {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
 struct GemmArgs {
     const void* A[3];
@@ -38,17 +50,10 @@ struct GemmArgs {
     float beta;
 };
 
-static constexpr int BK = 64;
+static constexpr int BK = 32;        // K step
+static constexpr int STAGES = 4;     // LDS stages (3 K-steps in flight)
 
-// ---- LDS addressing for NT tiles: row pitch 128 B, 8 chunks of 16 B ----------
-__device__ __forceinline__ int nt_lds_off(int row, int chunk) {
-    return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4);
-}
-
-typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
-
-// Workgroup barrier that orders LDS traffic only: global loads that are still
-// in flight (the register prefetch of a later K-step) stay in flight.
+// Workgroup barrier that orders LDS traffic only: global loads still in flight stay in flight.
 __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
     __builtin_amdgcn_s_barrier();
@@ -57,11 +62,39 @@ __device__ __forceinline__ void lds_barrier() {
 
 #define CF_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-// Buffer resource over [base, base+bytes): loads past the end return zeros, which is
-// how ragged tiles are predicated without branches.
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, int64_t bytes) {
+// s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt = imm[15:14]:imm[3:0], expcnt imm[6:4], lgkmcnt imm[11:8])
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
+
+// Raw buffer descriptor over [base, base+bytes): loads past the end return zeros.
+__device__ __forceinline__ i32x4_t make_rsrc(const void* base, int64_t bytes) {
     const int64_t lim = bytes < 0 ? 0 : (bytes > 0xFFFFFFFFll ? 0xFFFFFFFFll : bytes);
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)(unsigned)lim, 0x00020000);
+    const uint64_t b = reinterpret_cast<uint64_t>(base);
+    i32x4_t r;
+    r.x = (int)(unsigned)b;
+    r.y = (int)(unsigned)((b >> 32) & 0xFFFFu);     // stride 0: raw buffer
+    r.z = (int)(unsigned)lim;
+    r.w = 0x00020000;
+    return r;
+}
+
+// 16 bytes per lane from global memory straight into LDS: lane l of the wave writes
+// LDS bytes [lds_base + 16*l, +16).  Issued as inline assembly so that the compiler
+// does not serialise later LDS reads against it; completion is tracked by hand with
+// vmcnt (the loads of a wave retire in order).
+__device__ __forceinline__ void dma16(unsigned lds_base /*wave-uniform*/, i32x4_t rsrc, unsigned voffset) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_base), "v"(voffset), "s"(rsrc)
+                 : "memory");
+}
+
+__device__ __forceinline__ unsigned lds_addr_of(const void* p) {
+    return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
 }
 
 // Tile order: consecutive logical tiles form bands of GROUP_M tile rows walked
@@ -86,8 +119,10 @@ template <int MODE, int TM, int TN>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     constexpr int BM = 2 * TM * 32, BN = 2 * TN * 32;
     constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
-    constexpr int A_LD = BM / 32, B_LD = BN / 32;   // 16-byte chunks per thread per tile
+    constexpr int A_LD = A_BYTES / 4096, B_LD = B_BYTES / 4096;   // 1 KB wave-loads per wave per tile
+    constexpr int LD = A_LD + B_LD;
     constexpr unsigned OOB = 0xFFFFFFFFu;
+    constexpr int C_PITCH = BN * 2 + 16;                           // staged C tile row pitch (bytes)
     extern __shared__ __align__(16) unsigned char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -109,80 +144,67 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     int total_steps = 0;
     for (int s = 0; s < g.nseg; ++s) total_steps += (g.K[s] + BK - 1) / BK;
 
-    // ---- global -> registers: one K-step of both operand tiles -----------------
-    // Offsets are relative to the block's first row/column so they fit 32 bits.
-    u32x4_t ra[A_LD], rb[B_LD];
-    int seg = 0, k0 = 0;                 // K-step the NEXT issue_global() fetches
-    __amdgpu_buffer_rsrc_t rsA, rsB;
+    // ---- global -> LDS: one K-step of both operand tiles -------------------------
+    // Wave w, load i fills LDS bytes [(4*i + w) KB, +1 KB) of the tile; lane l owns
+    // the 16 bytes at +16*l.  Offsets are relative to the block's first row / column.
+    int seg = 0, k0 = 0, Kseg = 0;       // K-step that the next issue_loads() fetches
+    i32x4_t rsA, rsB;
+    unsigned ldA = 0, ldB = 0;           // row pitch in bytes of the current segment's operands
     auto open_segment = [&](int s) {
         const bf16_t* A = static_cast<const bf16_t*>(g.A[s]);
         const bf16_t* B = static_cast<const bf16_t*>(g.B[s]);
-        const int64_t K = g.K[s];
+        Kseg = g.K[s];
+        const int64_t K = Kseg;
         if (MODE == 0) {
             rsA = make_rsrc(A + (int64_t)m0 * K, ((int64_t)g.M - m0) * K * 2);
             rsB = make_rsrc(B + (int64_t)n0 * K, ((int64_t)g.N - n0) * K * 2);
+            ldA = ldB = (unsigned)K * 2u;
         } else {
             rsA = make_rsrc(A + m0, (K * g.M - m0) * 2);
             rsB = make_rsrc(B + n0, (K * g.N - n0) * 2);
+            ldA = (unsigned)g.M * 2u;
+            ldB = (unsigned)g.N * 2u;
         }
     };
-    auto issue_global = [&]() {
-        const int K = g.K[seg];
+    auto issue_loads = [&](int stage) {
+        const unsigned sa = __builtin_amdgcn_readfirstlane(lds_addr_of(smem) + stage * STAGE + wave * 1024);
+        const unsigned sb = sa + A_BYTES;
         if (MODE == 0) {
-            const int c = tid & 7;
-            const unsigned kb = (k0 + c * 8 < K) ? (unsigned)(k0 + c * 8) * 2u : OOB;
+            // slot = 16 rows x 4 chunks per wave-load; the chunk a lane fetches undoes the XOR swizzle
+            const unsigned lc = (lane & 3) ^ ((lane >> 4) & 3);
+            const unsigned kb = (k0 + (int)lc * 8 < Kseg) ? (unsigned)(k0 + (int)lc * 8) * 2u : OOB;
 #pragma unroll
             for (int i = 0; i < A_LD; ++i) {
-                const unsigned row = (tid >> 3) + 32 * i;
-                ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rsA, kb == OOB ? OOB : row * (unsigned)K * 2u + kb, 0, 0);
+                const unsigned row = (4 * i + wave) * 16 + (lane >> 2);
+                dma16(sa + i * 4096, rsA, kb == OOB ? OOB : row * ldA + kb);
             }
 #pragma unroll
             for (int i = 0; i < B_LD; ++i) {
-                const unsigned row = (tid >> 3) + 32 * i;
-                rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rsB, kb == OOB ? OOB : row * (unsigned)K * 2u + kb, 0, 0);
+                const unsigned row = (4 * i + wave) * 16 + (lane >> 2);
+                dma16(sb + i * 4096, rsB, kb == OOB ? OOB : row * ldB + kb);
             }
         } else {
+            // tile [32][BM] as in memory: a wave-load covers 1024 / (BM*2) k-rows
 #pragma unroll
             for (int i = 0; i < A_LD; ++i) {
-                const int q = tid + 256 * i;
+                const int q = (4 * i + wave) * 64 + lane;
                 const int kr = q / (BM / 8), c = q % (BM / 8);
-                const unsigned off = (unsigned)(k0 + kr) * (unsigned)g.M * 2u + c * 16u;
-                ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rsA, (m0 + c * 8 < g.M && k0 + kr < K) ? off : OOB, 0, 0);
+                const bool ok = (m0 + c * 8 < g.M) && (k0 + kr < Kseg);
+                dma16(sa + i * 4096, rsA, ok ? (unsigned)(k0 + kr) * ldA + c * 16u : OOB);
             }
 #pragma unroll
             for (int i = 0; i < B_LD; ++i) {
-                const int q = tid + 256 * i;
+                const int q = (4 * i + wave) * 64 + lane;
                 const int kr = q / (BN / 8), c = q % (BN / 8);
-                const unsigned off = (unsigned)(k0 + kr) * (unsigned)g.N * 2u + c * 16u;
-                rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rsB, (n0 + c * 8 < g.N && k0 + kr < K) ? off : OOB, 0, 0);
+                const bool ok = (n0 + c * 8 < g.N) && (k0 + kr < Kseg);
+                dma16(sb + i * 4096, rsB, ok ? (unsigned)(k0 + kr) * ldB + c * 16u : OOB);
             }
         }
         k0 += BK;
-        if (k0 >= K) {
+        if (k0 >= Kseg) {
             k0 = 0;
             ++seg;
             if (seg < g.nseg) open_segment(seg);
-        }
-    };
-
-    auto store_lds = [&](int stage) {
-        unsigned char* sa = smem + stage * STAGE;
-        unsigned char* sb = sa + A_BYTES;
-        if (MODE == 0) {
-            const int c = tid & 7;
-#pragma unroll
-            for (int i = 0; i < A_LD; ++i)
-                *reinterpret_cast<u32x4_t*>(sa + nt_lds_off((tid >> 3) + 32 * i, c)) = ra[i];
-#pragma unroll
-            for (int i = 0; i < B_LD; ++i)
-                *reinterpret_cast<u32x4_t*>(sb + nt_lds_off((tid >> 3) + 32 * i, c)) = rb[i];
-        } else {
-#pragma unroll
-            for (int i = 0; i < A_LD; ++i)
-                *reinterpret_cast<u32x4_t*>(sa + (tid + 256 * i) * 16) = ra[i];
-#pragma unroll
-            for (int i = 0; i < B_LD; ++i)
-                *reinterpret_cast<u32x4_t*>(sb + (tid + 256 * i) * 16) = rb[i];
         }
     };
 
@@ -190,14 +212,16 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     struct Frags {
         bf16x8_t a[TM], b[TN];
     };
+    // NT: tile [rows][32]; the lane reads row row0 + i*32 + slot, logical chunk ks*2 + hh
+    const int nt_sw = (slot >> 2) & 3;
     auto frags_nt = [&](const unsigned char* tile, int row0, int ks, bf16x8_t* frag, auto ntiles) {
         constexpr int NT_ = decltype(ntiles)::value;
+        const unsigned char* p = tile + (row0 + slot) * 64 + (((ks * 2 + hh) ^ nt_sw) << 4);
 #pragma unroll
         for (int i = 0; i < NT_; ++i)
-            frag[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(
-                                                       tile + nt_lds_off(row0 + i * 32 + slot, ks * 2 + hh)));
+            frag[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(p + i * 32 * 64));
     };
-    // tile is [64][W] bf16 as in memory; the lane owns columns col0 + slot*NT_ .. +NT_-1
+    // TN: tile [32][W] as in memory; the lane owns columns col0 + slot*NT_ .. +NT_-1
     auto frags_tn = [&](const unsigned char* tile, int W, int col0, int ks, bf16x8_t* frag, auto ntiles) {
         constexpr int NT_ = decltype(ntiles)::value;
         static_assert(NT_ == 2 || NT_ == 4, "TM/TN must be 2 or 4");
@@ -235,105 +259,117 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
             frags_tn(sb, BN, wn * TN * 32, ks, f.b, std::integral_constant<int, TN>());
         }
     };
+    // NT: D = Bfrag x Afrag  -> lane = output row (m slot), registers = output columns
+    // TN: D = Afrag x Bfrag  -> lane = n slot (TN adjacent columns per lane), registers = m slots
     auto mma = [&](const Frags& f) {
-#ifdef CF_EXP_NOMMA
-        if (g.beta == 123.f)
-#endif
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
+                acc[i][j] = (MODE == 0)
+                                ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[j], f.a[i], acc[i][j], 0, 0, 0)
+                                : __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
     };
 
-    // ---- software-pipelined main loop ----------------------------------------------
-    // Iteration t multiplies tile t out of LDS stage t&1 while
-    //   * tile t+1 (fetched into registers during iteration t-1) is written to the other stage,
-    //   * tile t+2 is fetched from global memory into the same registers,
-    //   * fragments of the next 16-wide sub-step are read from LDS ahead of the MFMAs that
-    //     use the current ones.
-    // One LDS barrier per iteration, placed before the last sub-step so that the first
-    // fragments of tile t+1 are already on their way when iteration t+1 starts.
+    // ---- main loop ------------------------------------------------------------------
+    // Iteration t multiplies K-step t out of stage t%4.  At its start the loads of K-step
+    // t+3 are issued into the stage that K-step t-1 used (all its reads were issued before
+    // the barrier of iteration t-1).  Between the two sub-steps every wave waits until its
+    // own loads of K-step t+1 have landed, then the barrier publishes them.
     if (total_steps > 0) {
         Frags f0, f1;
         open_segment(0);
-        issue_global();
-        store_lds(0);
-        if (total_steps > 1) issue_global();
+        issue_loads(0);
+        if (total_steps > 1) issue_loads(1);
+        if (total_steps > 2) issue_loads(2);
+        if (total_steps > 2) wait_vmcnt<2 * LD>();
+        else if (total_steps > 1) wait_vmcnt<LD>();
+        else wait_vmcnt<0>();
         lds_barrier();
         load_frags(0, 0, f0);
         for (int t = 0; t < total_steps; ++t) {
-            const int cur = t & 1;
-#ifndef CF_EXP_NOSTORE
-            if (t + 1 < total_steps) store_lds(cur ^ 1);
-#endif
-#ifndef CF_EXP_NOGLOBAL
-            if (t + 2 < total_steps) issue_global();
-#endif
+            const int cur = t & (STAGES - 1);
+            if (t + 3 < total_steps) issue_loads((t + 3) & (STAGES - 1));
             CF_SCHED_FENCE();
             load_frags(cur, 1, f1);
             CF_SCHED_FENCE();
             mma(f0);
             CF_SCHED_FENCE();
-            load_frags(cur, 2, f0);
-            CF_SCHED_FENCE();
-            mma(f1);
-            CF_SCHED_FENCE();
-            load_frags(cur, 3, f1);
-            CF_SCHED_FENCE();
-            mma(f0);
-            CF_SCHED_FENCE();
+            if (t + 3 < total_steps) wait_vmcnt<2 * LD>();
+            else if (t + 2 < total_steps) wait_vmcnt<LD>();
+            else wait_vmcnt<0>();
             lds_barrier();
-            if (t + 1 < total_steps) load_frags(cur ^ 1, 0, f0);
+            if (t + 1 < total_steps) load_frags((t + 1) & (STAGES - 1), 0, f0);
             CF_SCHED_FENCE();
             mma(f1);
             CF_SCHED_FENCE();
         }
     }
 
-    // ---- epilogue ---------------------------------------------------------------
-    bf16_t* C = static_cast<bf16_t*>(g.C);
-    const float beta = g.beta;
+    // ---- epilogue: acc -> bf16 -> LDS C tile -> global with 16-byte stores -----------
+    lds_barrier();      // every wave is done reading operand stages
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int rslot = 8 * (v >> 2) + 4 * hh + (v & 3);
-            if (MODE == 0) {
-                const int m = m0 + wm * TM * 32 + i * 32 + rslot;
-                if (m < g.M) {
+        for (int j = 0; j < TN; ++j) {
 #pragma unroll
-                    for (int j = 0; j < TN; ++j) {
-                        const int n = n0 + wn * TN * 32 + j * 32 + slot;
-                        if (n < g.N) {
-                            bf16_t* p = C + (int64_t)m * g.N + n;
-                            float val = acc[i][j][v];
-                            if (beta != 0.f) val += beta * bf16_to_f32(*p);
-                            *p = f32_to_bf16(val);
-                        }
+            for (int v4 = 0; v4 < 4; ++v4) {
+                int r, c;     // tile-local row and first column of 4 adjacent outputs
+                uint2 o;
+                if (MODE == 0) {
+                    r = wm * TM * 32 + i * 32 + slot;
+                    c = wn * TN * 32 + j * 32 + 8 * v4 + 4 * hh;
+                    o.x = pack_bf16x2(acc[i][j][4 * v4 + 0], acc[i][j][4 * v4 + 1]);
+                    o.y = pack_bf16x2(acc[i][j][4 * v4 + 2], acc[i][j][4 * v4 + 3]);
+                    *reinterpret_cast<uint2*>(smem + r * C_PITCH + c * 2) = o;
+                }
+            }
+        }
+    }
+    if (MODE == 1) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int r = wm * TM * 32 + (8 * (v >> 2) + 4 * hh + (v & 3)) * TM + i;
+                const int c = wn * TN * 32 + slot * TN;
+                if (TN == 4) {
+                    uint2 o;
+                    o.x = pack_bf16x2(acc[i][0][v], acc[i][1][v]);
+                    o.y = pack_bf16x2(acc[i][TN - 2][v], acc[i][TN - 1][v]);
+                    *reinterpret_cast<uint2*>(smem + r * C_PITCH + c * 2) = o;
+                } else {
+                    *reinterpret_cast<unsigned*>(smem + r * C_PITCH + c * 2) = pack_bf16x2(acc[i][0][v], acc[i][1][v]);
+                }
+            }
+        }
+    }
+    lds_barrier();
+    {
+        bf16_t* C = static_cast<bf16_t*>(g.C);
+        const float beta = g.beta;
+        constexpr int CPR = BN / 8;                  // 16-byte chunks per tile row
+        constexpr int RPP = 256 / CPR;               // rows per pass
+        const int c = tid % CPR, r0 = tid / CPR;
+        const int n = n0 + c * 8;
+        if (n < g.N) {                                // N is a multiple of 8
+#pragma unroll 4
+            for (int r = r0; r < BM; r += RPP) {
+                const int m = m0 + r;
+                if (m >= g.M) break;
+                u32x4_t val = *reinterpret_cast<const u32x4_t*>(smem + r * C_PITCH + c * 16);
+                bf16_t* p = C + (int64_t)m * g.N + n;
+                if (beta != 0.f) {
+                    const u32x4_t old = *reinterpret_cast<const u32x4_t*>(p);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float lo = __uint_as_float(val[e] << 16) + beta * __uint_as_float(old[e] << 16);
+                        const float hi = __uint_as_float(val[e] & 0xFFFF0000u) +
+                                         beta * __uint_as_float(old[e] & 0xFFFF0000u);
+                        val[e] = pack_bf16x2(lo, hi);
                     }
                 }
-            } else {
-                const int m = m0 + wm * TM * 32 + rslot * TM + i;
-                const int n = n0 + wn * TN * 32 + slot * TN;     // TN consecutive columns
-                if (m < g.M && n < g.N) {                          // N is a multiple of 8 >= TN
-                    bf16_t* p = C + (int64_t)m * g.N + n;
-                    float val[TN];
-#pragma unroll
-                    for (int j = 0; j < TN; ++j) val[j] = acc[i][j][v];
-                    if (beta != 0.f) {
-#pragma unroll
-                        for (int j = 0; j < TN; ++j) val[j] += beta * bf16_to_f32(p[j]);
-                    }
-                    if (TN == 4) {
-                        uint2 o;
-                        o.x = pack_bf16x2(val[0], val[1]);
-                        o.y = pack_bf16x2(val[TN - 2], val[TN - 1]);
-                        *reinterpret_cast<uint2*>(p) = o;
-                    } else {
-                        *reinterpret_cast<unsigned*>(p) = pack_bf16x2(val[0], val[1]);
-                    }
-                }
+                *reinterpret_cast<u32x4_t*>(p) = val;
             }
         }
     }
@@ -402,7 +438,9 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g) {
 template <int MODE, int TM, int TN>
 static hipError_t launch_bf16(const GemmArgs& g, hipStream_t st) {
     constexpr int BM = 2 * TM * 32, BN = 2 * TN * 32;
-    constexpr int smem = 2 * (BM + BN) * BK * 2;
+    constexpr int stages = STAGES * (BM + BN) * BK * 2;
+    constexpr int ctile = BM * (BN * 2 + 16);
+    constexpr int smem = stages > ctile ? stages : ctile;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<MODE, TM, TN>),
