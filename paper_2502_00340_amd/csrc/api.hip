@@ -11,11 +11,12 @@ hipError_t launch_attn_bwd_ref(const cf_layer_desc& L, float scale, const void* 
                                const int32_t* cu_kept, int n_kept, void* dq_kept, void* dk_kept,
                                void* dv_kept, hipStream_t st);
 bool attn_mfma_supported(const cf_layer_desc& L);
+size_t attn_mfma_partial_bytes(const cf_layer_desc& L, int n_kept);
 hipError_t launch_attn_bwd_mfma(const cf_layer_desc& L, float scale, const void* q_kept,
                                 const void* k_full, const void* v_full, const float* lse_full,
                                 const void* do_kept, const float* Drow, const int32_t* idx,
                                 const int32_t* cu_kept, int n_kept, void* dq_kept, void* dk_kept,
-                                void* dv_kept, hipStream_t st);
+                                void* dv_kept, float* partials, hipStream_t st);
 }  // namespace cf
 
 using namespace cf;
@@ -69,6 +70,15 @@ float eff_scale(const cf_layer_desc& L) {
     return L.softmax_scale > 0.f ? L.softmax_scale : 1.0f / sqrtf((float)L.d);
 }
 
+size_t attn_drow_bytes(const cf_layer_desc& L, int n_kept) {
+    return align_up((size_t)(n_kept > 0 ? n_kept : 1) * L.Hq * sizeof(float), 256);
+}
+
+// D row statistics followed by the per-head dK/dV partials of the matrix-core path
+size_t attn_ws_total(const cf_layer_desc& L, int n_kept) {
+    return attn_drow_bytes(L, n_kept) + attn_mfma_partial_bytes(L, n_kept);
+}
+
 // bump allocator over the caller's workspace
 struct Carver {
     unsigned char* base;
@@ -85,7 +95,8 @@ struct LayerWs {
     void* index_ws;
     int32_t *idx, *cu_kept, *n_kept_dev;
     void *dy_k, *bufF0, *bufF1, *bufHa, *bufHb, *dr, *a_k, *da, *q_k, *dq, *dk, *dv;
-    float *Drow, *dg_partial;
+    void* attn_ws;
+    float* dg_partial;
     size_t total;
 };
 
@@ -112,7 +123,7 @@ LayerWs carve_layer(const cf_layer_desc& L, int max_kept, void* ws) {
     w.dq = c.take(N * Nq * e);
     w.dk = c.take(N * Nkv * e);
     w.dv = c.take(N * Nkv * e);
-    w.Drow = (float*)c.take(N * L.Hq * 4);
+    w.attn_ws = c.take(attn_ws_total(L, (int)N));
     w.dg_partial = (float*)c.take((size_t)rmsnorm_bwd_blocks((int)N) * L.H * 4);
     w.total = c.off;
     return w;
@@ -121,13 +132,15 @@ LayerWs carve_layer(const cf_layer_desc& L, int max_kept, void* ws) {
 cf_status attn_dispatch(const cf_layer_desc& L, const void* q_kept, const void* k_full,
                         const void* v_full, const void* o_kept, const float* lse_full,
                         const void* do_kept, const int32_t* idx, const int32_t* cu_kept, int n_kept,
-                        void* dq_kept, void* dk_kept, void* dv_kept, float* Drow, hipStream_t st) {
+                        void* dq_kept, void* dk_kept, void* dv_kept, void* attn_ws, hipStream_t st) {
     if (n_kept <= 0) return CF_OK;
     const float scale = eff_scale(L);
+    float* Drow = static_cast<float*>(attn_ws);
+    float* partials = reinterpret_cast<float*>(static_cast<unsigned char*>(attn_ws) + attn_drow_bytes(L, n_kept));
     CF_HIP(launch_attn_rowdot(L.dtype, do_kept, o_kept, n_kept, L.Hq, L.d, Drow, st));
     if (attn_mfma_supported(L))
         CF_HIP(launch_attn_bwd_mfma(L, scale, q_kept, k_full, v_full, lse_full, do_kept, Drow, idx,
-                                    cu_kept, n_kept, dq_kept, dk_kept, dv_kept, st));
+                                    cu_kept, n_kept, dq_kept, dk_kept, dv_kept, partials, st));
     else
         CF_HIP(launch_attn_bwd_ref(L, scale, q_kept, k_full, v_full, lse_full, do_kept, Drow, idx,
                                    cu_kept, n_kept, dq_kept, dk_kept, dv_kept, st));
@@ -201,7 +214,7 @@ cf_status layer_core(const cf_layer_desc& L, const cf_saved& sv, const cf_weight
         CF_HIP(launch_gemm(dt, 0, &s2, 1, w.da, N, Nq, 0.f, st));
     }
     cf_status as = attn_dispatch(L, q_rows, sv.k, sv.v, a_rows, sv.lse, w.da, idx, cu_kept, N, w.dq,
-                                 w.dk, w.dv, w.Drow, st);
+                                 w.dk, w.dv, w.attn_ws, st);
     if (as != CF_OK) return as;
 
     void* h1 = w.bufHa;
@@ -322,7 +335,7 @@ cf_status cf_linear_bwd_reduced(const void* x_kept, const void* dy_kept, const v
 
 size_t cf_attn_workspace_bytes(const cf_layer_desc* desc, int32_t n_kept) {
     if (check_attn_desc(desc) != CF_OK || n_kept < 0) return 0;
-    return align_up((size_t)(n_kept > 0 ? n_kept : 1) * desc->Hq * sizeof(float), 256);
+    return attn_ws_total(*desc, n_kept);
 }
 
 cf_status cf_attn_bwd_filtered(const cf_layer_desc* desc, const void* q_kept, const void* k_full,
@@ -346,7 +359,7 @@ cf_status cf_attn_bwd_filtered(const cf_layer_desc* desc, const void* q_kept, co
     if (!ws || misaligned(ws, 256) || ws_bytes < cf_attn_workspace_bytes(desc, n_kept))
         return CF_ERR_WORKSPACE;
     return attn_dispatch(*desc, q_kept, k_full, v_full, o_kept, lse_full, do_kept, idx, cu_kept,
-                         n_kept, dq_kept, dk_kept, dv_kept, static_cast<float*>(ws), as_stream(stream));
+                         n_kept, dq_kept, dk_kept, dv_kept, ws, as_stream(stream));
 }
 
 size_t cf_layer_workspace_bytes(const cf_layer_desc* desc, int32_t max_kept) {

@@ -6,11 +6,18 @@
 //               tiles up to the last query's original position; P is rebuilt
 //               from the saved LSE, so filtered keys contribute exactly as in
 //               the forward pass.
-//   dK/dV kernel (Eq. 3): a block owns 128 KEPT keys of one (sequence, KV head) and
-//               walks over the kept queries at or after them, for every query
-//               head of the group; rows of filtered tokens are never formed.
-//               Kept rows are in position order, so causality is "compact query
-//               index >= compact key index".
+//   dK/dV kernel (Eq. 3): a block owns 128 KEPT keys of one (sequence, QUERY head) and
+//               walks over the kept queries at or after them; rows of filtered
+//               tokens are never formed.  Kept rows are in position order, so
+//               causality is "compact query index >= compact key index".  With
+//               grouped heads each query head writes an fp32 partial and a small
+//               kernel sums the G partials of a KV head in a fixed order.
+//
+// Block order: the (head, sequence) index varies fastest and the tile index
+// slowest with the heaviest tiles first, so that the 8 XCDs (block id mod 8)
+// receive equal shares of every tile weight and the tail of the launch is made
+// of light blocks.  K/V (dQ kernel) and Q/dO (dK/dV kernel) tiles go from global
+// memory straight into LDS (16 bytes per lane), one tile ahead of the MFMAs.
 //
 // Operand orientation is chosen so that no score tile ever goes through LDS:
 // the dQ kernel forms S^T = K*Q^T (accumulator lane = query, registers = keys),
@@ -27,12 +34,11 @@
 // rows {16j + 4hh + e, 16j + 8 + 4hh + e}; the transpose reads fetch exactly
 // those rows for the other operand.
 #include "common.h"
+#include "mfma_util.h"
 
 namespace cf {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4_t;
 typedef __attribute__((address_space(3))) s16x4_t* lds_s16x4_ptr;
 
@@ -43,7 +49,8 @@ struct AttnParams {
     const float *lse_full, *Drow;
     const int32_t *idx, *cu_kept;
     bf16_t *dq_kept, *dk_kept, *dv_kept;
-    int B, S, Hq, Hkv;
+    float *dk_part, *dv_part;      // [G][n_kept][Hkv*d] fp32 per-query-head partials (G > 1 only)
+    int B, S, Hq, Hkv, n_kept;
     float scale;
 };
 
@@ -97,23 +104,47 @@ __device__ __forceinline__ bf16x8_t frag_tokens(const unsigned char* tile, int r
 }
 
 // ---------------------------------------------------------------------------
+// global -> LDS copy of a [64][D] tile whose rows are `row_stride` bytes apart in
+// memory; rows >= rows_valid are zero-filled through the descriptor's range check.
+// Wave w, load i fills LDS bytes [(4*i + w) KB, +1 KB) of the tile: 1 KB = 1024/(2D)
+// rows; the lane fetches the global chunk that belongs in its (swizzled) LDS slot.
+// ---------------------------------------------------------------------------
+template <int D>
+__device__ __forceinline__ void dma_tile(unsigned lds_tile /*uniform*/, i32x4_t rsrc, unsigned base_off,
+                                         unsigned row_stride, int rows_valid, int wave, int lane) {
+    constexpr int NCH = D / 8;                  // 16-byte chunks per row
+    constexpr int RPL = 64 / NCH;               // rows per 1 KB wave-load
+    constexpr int NLD = 64 / RPL / 4;           // wave-loads per wave per tile
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+        const int row = (4 * i + wave) * RPL + lane / NCH;
+        const int pc = lane % NCH;
+        const int g = (D == 128) ? (((row & 3) << 2) | ((row >> 2) & 3))
+                                 : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
+        const unsigned off = base_off + (unsigned)row * row_stride + (unsigned)((pc ^ g) << 4);
+        dma16(__builtin_amdgcn_readfirstlane(lds_tile + (4 * i + wave) * 1024), rsrc,
+              row < rows_valid ? off : 0xFFFFFFFFu);
+    }
+}
+
+// ---------------------------------------------------------------------------
 // dQ kernel
 // ---------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(256) void attn_dq_kernel(AttnParams p) {
-    constexpr int NCH = D / 8, KS = D / 16, NT = D / 32;
+__global__ __launch_bounds__(256, 2) void attn_dq_kernel(AttnParams p) {
+    constexpr int KS = D / 16, NT = D / 32;
     constexpr int TILE = 64 * D * 2;            // one 64-token tile in bytes
-    constexpr int LD = 64 * NCH / 256;          // 16-byte chunks per thread per tile
+    constexpr int NLD = D / 32;                 // wave-loads per wave per tile
     extern __shared__ __align__(16) unsigned char smem[];   // [2 stages][K tile, V tile]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int slot = lane & 31, hh = lane >> 5;
-    const int b = blockIdx.z, h = blockIdx.y, g = h / (p.Hq / p.Hkv);
+    const int h = blockIdx.x % p.Hq, b = blockIdx.x / p.Hq, g = h / (p.Hq / p.Hkv);
     const int Nq = p.Hq * D, Nkv = p.Hkv * D;
     const int seq_begin = p.cu_kept ? p.cu_kept[b] : b * p.S;
     const int seq_end = p.cu_kept ? p.cu_kept[b + 1] : (b + 1) * p.S;
     const int cnt = seq_end - seq_begin;
-    const int qt = gridDim.x - 1 - blockIdx.x;        // heaviest (latest) query tiles first
+    const int qt = gridDim.y - 1 - blockIdx.y;        // heaviest (latest) query tiles first
     if (qt * 128 >= cnt) return;
     const int j0 = seq_begin + qt * 128;
     const int rows_in_tile = min(128, cnt - qt * 128);
@@ -154,75 +185,50 @@ __global__ __launch_bounds__(256) void attn_dq_kernel(AttnParams p) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[nt][v] = 0.f;
 
-    uint4 rk[LD], rv[LD];
-    auto load_kv = [&](int kt) {
-#pragma unroll
-        for (int i = 0; i < LD; ++i) {
-            const int q = tid + 256 * i;
-            const int row = q / NCH, c = q % NCH;
-            const int key = kt * 64 + row;
-            if (key <= maxpos) {
-                const int64_t off = ((int64_t)b * p.S + key) * Nkv + g * D + c * 8;
-                rk[i] = *reinterpret_cast<const uint4*>(p.k_full + off);
-                rv[i] = *reinterpret_cast<const uint4*>(p.v_full + off);
-            } else {
-                rk[i] = make_uint4(0, 0, 0, 0);
-                rv[i] = make_uint4(0, 0, 0, 0);
-            }
-        }
-    };
-    auto store_kv = [&](int stage) {
-        unsigned char* sk = smem + stage * 2 * TILE;
-        unsigned char* sv = sk + TILE;
-#pragma unroll
-        for (int i = 0; i < LD; ++i) {
-            const int q = tid + 256 * i;
-            const int off = tile_off<D>(q / NCH, q % NCH);
-            *reinterpret_cast<uint4*>(sk + off) = rk[i];
-            *reinterpret_cast<uint4*>(sv + off) = rv[i];
-        }
+    // K and V of this sequence and KV head: rows are Nkv*2 bytes apart
+    const i32x4_t rsK = make_rsrc(p.k_full + ((int64_t)b * p.S) * Nkv + g * D, ((int64_t)p.S * Nkv - g * D) * 2);
+    const i32x4_t rsV = make_rsrc(p.v_full + ((int64_t)b * p.S) * Nkv + g * D, ((int64_t)p.S * Nkv - g * D) * 2);
+    const unsigned lds0 = __builtin_amdgcn_readfirstlane(lds_addr_of(smem));
+    auto issue_kv = [&](int kt, int stage) {
+        const unsigned sk = lds0 + stage * 2 * TILE;
+        const unsigned base = (unsigned)(kt * 64) * (unsigned)(Nkv * 2);
+        const int valid = maxpos + 1 - kt * 64;
+        dma_tile<D>(sk, rsK, base, Nkv * 2, valid, wave, lane);
+        dma_tile<D>(sk + TILE, rsV, base, Nkv * 2, valid, wave, lane);
     };
 
-    load_kv(0);
-    store_kv(0);
-    __syncthreads();
+    issue_kv(0, 0);
+    wait_vmcnt<0>();
+    lds_barrier();
     for (int kt = 0; kt < nkt; ++kt) {
         const int cur = kt & 1;
-        const bool more = kt + 1 < nkt;
-        if (more) load_kv(kt + 1);
+        if (kt + 1 < nkt) issue_kv(kt + 1, cur ^ 1);
         if (kt * 64 <= wave_maxpos) {
             const unsigned char* sk = smem + cur * 2 * TILE;
             const unsigned char* sv = sk + TILE;
-            f32x16_t st[2], dpt[2];
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) { st[mt][v] = 0.f; dpt[mt][v] = 0.f; }
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-#pragma unroll
-                for (int mt = 0; mt < 2; ++mt) {
-                    st[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        frag_rows<D>(sk, mt * 32 + slot, ks, hh), qf[ks], st[mt], 0, 0, 0);
-                    dpt[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        frag_rows<D>(sv, mt * 32 + slot, ks, hh), dof[ks], dpt[mt], 0, 0, 0);
-                }
-            }
-            // dS^T = P^T o (dP^T - D): lane = query, register = key
+            // one 32-key half of the tile at a time keeps the score registers at 2 x 16
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt) {
+                f32x16_t st, dpt;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) { st[v] = 0.f; dpt[v] = 0.f; }
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sk, mt * 32 + slot, ks, hh), qf[ks],
+                                                                 st, 0, 0, 0);
+                    dpt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sv, mt * 32 + slot, ks, hh), dof[ks],
+                                                                  dpt, 0, 0, 0);
+                }
+                // dS^T = P^T o (dP^T - D): lane = query, register = key
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int key = kt * 64 + mt * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
-                    const float pr = key <= pos ? __builtin_amdgcn_exp2f(st[mt][v] * scale2 - lse2) : 0.f;
-                    st[mt][v] = pr * (dpt[mt][v] - Dq);
+                    const float pr = key <= pos ? __builtin_amdgcn_exp2f(st[v] * scale2 - lse2) : 0.f;
+                    st[v] = pr * (dpt[v] - Dq);
                 }
-            }
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt) {
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
-                    const bf16x8_t a = pack8(st[mt], j);
+                    const bf16x8_t a = pack8(st, j);
 #pragma unroll
                     for (int nt = 0; nt < NT; ++nt)
                         acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
@@ -230,8 +236,8 @@ __global__ __launch_bounds__(256) void attn_dq_kernel(AttnParams p) {
                 }
             }
         }
-        if (more) store_kv(cur ^ 1);
-        __syncthreads();
+        wait_vmcnt<0>();
+        lds_barrier();
     }
 
     // dq[query][d]: lane = d column, registers = query rows
@@ -247,24 +253,24 @@ __global__ __launch_bounds__(256) void attn_dq_kernel(AttnParams p) {
 }
 
 // ---------------------------------------------------------------------------
-// dK/dV kernel
+// dK/dV kernel: one (key tile, query head) per block
 // ---------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(256) void attn_dkv_kernel(AttnParams p) {
-    constexpr int NCH = D / 8, KS = D / 16, NT = D / 32;
+__global__ __launch_bounds__(256, D == 128 ? 1 : 2) void attn_dkv_kernel(AttnParams p) {
+    constexpr int KS = D / 16, NT = D / 32;
     constexpr int TILE = 64 * D * 2;
-    constexpr int LD = 64 * NCH / 256;
     constexpr int STAGE = 2 * TILE + 512;       // Q tile, dO tile, lse2[64], D[64]
     extern __shared__ __align__(16) unsigned char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int slot = lane & 31, hh = lane >> 5;
-    const int b = blockIdx.z, g = blockIdx.y, G = p.Hq / p.Hkv;
+    const int G = p.Hq / p.Hkv;
+    const int h = blockIdx.x % p.Hq, b = blockIdx.x / p.Hq, g = h / G;
     const int Nq = p.Hq * D, Nkv = p.Hkv * D;
     const int seq_begin = p.cu_kept ? p.cu_kept[b] : b * p.S;
     const int seq_end = p.cu_kept ? p.cu_kept[b + 1] : (b + 1) * p.S;
     const int cnt = seq_end - seq_begin;
-    const int kt = blockIdx.x;
+    const int kt = blockIdx.y;                      // early key tiles see the most queries: heaviest first
     if (kt * 128 >= cnt) return;
     const int c0 = seq_begin + kt * 128;            // compact row of the tile's first key
     const int keys_in_tile = min(128, cnt - kt * 128);
@@ -287,8 +293,7 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(AttnParams p) {
         }
     }
     const float scale2 = p.scale * LOG2E;
-    const int ntq = (seq_end - c0 + 63) / 64;       // query tiles from the first key to the sequence end
-    const int steps = G * ntq;
+    const int steps = (seq_end - c0 + 63) / 64;     // query tiles from the first key to the sequence end
     const int wave_first_key = c0 + wave * 32;
 
     f32x16_t dk[NT], dv[NT];
@@ -297,80 +302,55 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(AttnParams p) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) { dk[nt][v] = 0.f; dv[nt][v] = 0.f; }
 
-    uint4 rq[LD], rdo[LD];
-    float rl = 0.f, rd = 0.f;
-    auto load_q = [&](int step) {
-        const int h = g * G + step / ntq;
-        const int qbase = c0 + (step % ntq) * 64;
-#pragma unroll
-        for (int i = 0; i < LD; ++i) {
-            const int q = tid + 256 * i;
-            const int row = qbase + q / NCH, c = q % NCH;
-            if (row < seq_end) {
-                const int64_t off = (int64_t)row * Nq + h * D + c * 8;
-                rq[i] = *reinterpret_cast<const uint4*>(p.q_kept + off);
-                rdo[i] = *reinterpret_cast<const uint4*>(p.do_kept + off);
-            } else {
-                rq[i] = make_uint4(0, 0, 0, 0);
-                rdo[i] = make_uint4(0, 0, 0, 0);
-            }
-        }
+    // Q and dO rows of this sequence from its first key on, this head's columns
+    const i32x4_t rsQ = make_rsrc(p.q_kept + (int64_t)c0 * Nq + h * D, ((int64_t)(seq_end - c0) * Nq - h * D) * 2);
+    const i32x4_t rsO = make_rsrc(p.do_kept + (int64_t)c0 * Nq + h * D, ((int64_t)(seq_end - c0) * Nq - h * D) * 2);
+    const unsigned lds0 = __builtin_amdgcn_readfirstlane(lds_addr_of(smem));
+    auto issue_q = [&](int step, int stage) {
+        const unsigned sq = lds0 + stage * STAGE;
+        const unsigned base = (unsigned)(step * 64) * (unsigned)(Nq * 2);
+        const int valid = seq_end - c0 - step * 64;
+        dma_tile<D>(sq, rsQ, base, Nq * 2, valid, wave, lane);
+        dma_tile<D>(sq + TILE, rsO, base, Nq * 2, valid, wave, lane);
         if (tid < 64) {
-            const int row = qbase + tid;
+            float* sl = reinterpret_cast<float*>(smem + stage * STAGE + 2 * TILE);
+            const int row = c0 + step * 64 + tid;
+            float rl = __builtin_inff(), rd = 0.f;          // exp2(x - inf) = 0 past the sequence end
             if (row < seq_end) {
                 const int pos = (p.idx ? p.idx[row] : row) - b * p.S;
                 rl = p.lse_full[((int64_t)b * p.Hq + h) * p.S + pos] * LOG2E;
                 rd = p.Drow[(int64_t)row * p.Hq + h];
-            } else {
-                rl = __builtin_inff();      // exp2(x - inf) = 0 for rows past the sequence end
-                rd = 0.f;
             }
+            sl[tid] = rl;
+            sl[64 + tid] = rd;
         }
-    };
-    auto store_q = [&](int stage) {
-        unsigned char* sq = smem + stage * STAGE;
-        unsigned char* sdo = sq + TILE;
-        float* sl = reinterpret_cast<float*>(sq + 2 * TILE);
-#pragma unroll
-        for (int i = 0; i < LD; ++i) {
-            const int q = tid + 256 * i;
-            const int off = tile_off<D>(q / NCH, q % NCH);
-            *reinterpret_cast<uint4*>(sq + off) = rq[i];
-            *reinterpret_cast<uint4*>(sdo + off) = rdo[i];
-        }
-        if (tid < 64) { sl[tid] = rl; sl[64 + tid] = rd; }
     };
 
-    load_q(0);
-    store_q(0);
-    __syncthreads();
+    issue_q(0, 0);
+    wait_vmcnt<0>();
+    lds_barrier();
     for (int step = 0; step < steps; ++step) {
         const int cur = step & 1;
-        const bool more = step + 1 < steps;
-        if (more) load_q(step + 1);
-        const int qbase = c0 + (step % ntq) * 64;
+        if (step + 1 < steps) issue_q(step + 1, cur ^ 1);
+        const int qbase = c0 + step * 64;
         if (qbase + 63 >= wave_first_key && wave * 32 < keys_in_tile) {
             const unsigned char* sq = smem + cur * STAGE;
             const unsigned char* sdo = sq + TILE;
             const float* sl = reinterpret_cast<const float*>(sq + 2 * TILE);
-            f32x16_t st[2], dpt[2];
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) { st[mt][v] = 0.f; dpt[mt][v] = 0.f; }
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-#pragma unroll
-                for (int mt = 0; mt < 2; ++mt) {
-                    st[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        frag_rows<D>(sq, mt * 32 + slot, ks, hh), kf[ks], st[mt], 0, 0, 0);
-                    dpt[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        frag_rows<D>(sdo, mt * 32 + slot, ks, hh), vf[ks], dpt[mt], 0, 0, 0);
-                }
-            }
-            // P and dS: lane = key, register = query
+            // one 32-query half of the tile at a time keeps the score registers at 2 x 16
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt) {
+                f32x16_t st, dpt;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) { st[v] = 0.f; dpt[v] = 0.f; }
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sq, mt * 32 + slot, ks, hh), kf[ks],
+                                                                 st, 0, 0, 0);
+                    dpt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sdo, mt * 32 + slot, ks, hh), vf[ks],
+                                                                  dpt, 0, 0, 0);
+                }
+                // P and dS: lane = key, register = query
 #pragma unroll
                 for (int v4 = 0; v4 < 4; ++v4) {
                     const int ql = mt * 32 + 8 * v4 + 4 * hh;
@@ -382,18 +362,15 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(AttnParams p) {
                     for (int e = 0; e < 4; ++e) {
                         const int v = 4 * v4 + e;
                         const bool ok = kvalid && (qbase + ql + e >= jk);
-                        const float pr = ok ? __builtin_amdgcn_exp2f(st[mt][v] * scale2 - lv[e]) : 0.f;
-                        st[mt][v] = pr;
-                        dpt[mt][v] = pr * (dpt[mt][v] - dd[e]);
+                        const float pr = ok ? __builtin_amdgcn_exp2f(st[v] * scale2 - lv[e]) : 0.f;
+                        st[v] = pr;
+                        dpt[v] = pr * (dpt[v] - dd[e]);
                     }
                 }
-            }
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt) {
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
-                    const bf16x8_t ap = pack8(st[mt], j);
-                    const bf16x8_t ads = pack8(dpt[mt], j);
+                    const bf16x8_t ap = pack8(st, j);
+                    const bf16x8_t ads = pack8(dpt, j);
 #pragma unroll
                     for (int nt = 0; nt < NT; ++nt) {
                         dv[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
@@ -404,26 +381,73 @@ __global__ __launch_bounds__(256) void attn_dkv_kernel(AttnParams p) {
                 }
             }
         }
-        if (more) store_q(cur ^ 1);
-        __syncthreads();
+        wait_vmcnt<0>();
+        lds_barrier();
     }
 
+    if (G == 1) {
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
+        for (int nt = 0; nt < NT; ++nt) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int r = wave * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
-            if (r < keys_in_tile) {
-                const int64_t off = (int64_t)(c0 + r) * Nkv + g * D + nt * 32 + slot;
-                p.dk_kept[off] = f32_to_bf16(dk[nt][v] * p.scale);
-                p.dv_kept[off] = f32_to_bf16(dv[nt][v]);
+            for (int v = 0; v < 16; ++v) {
+                const int r = wave * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
+                if (r < keys_in_tile) {
+                    const int64_t off = (int64_t)(c0 + r) * Nkv + g * D + nt * 32 + slot;
+                    p.dk_kept[off] = f32_to_bf16(dk[nt][v] * p.scale);
+                    p.dv_kept[off] = f32_to_bf16(dv[nt][v]);
+                }
+            }
+        }
+    } else {
+        const int64_t part = (int64_t)(h - g * G) * p.n_kept * Nkv;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int r = wave * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
+                if (r < keys_in_tile) {
+                    const int64_t off = part + (int64_t)(c0 + r) * Nkv + g * D + nt * 32 + slot;
+                    p.dk_part[off] = dk[nt][v];
+                    p.dv_part[off] = dv[nt][v];
+                }
             }
         }
     }
 }
 
+// dk = scale * sum_g dk_part[g], dv = sum_g dv_part[g]   (fixed order: deterministic)
+__global__ __launch_bounds__(256) void attn_dkv_reduce_kernel(const float* __restrict__ dk_part,
+                                                              const float* __restrict__ dv_part, int G,
+                                                              int64_t n_elems, float scale,
+                                                              bf16_t* __restrict__ dk, bf16_t* __restrict__ dv) {
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
+    if (i >= n_elems) return;
+    float sk[8], sv[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { sk[e] = 0.f; sv[e] = 0.f; }
+    for (int g = 0; g < G; ++g) {
+        const float4* pk = reinterpret_cast<const float4*>(dk_part + (int64_t)g * n_elems + i);
+        const float4* pv = reinterpret_cast<const float4*>(dv_part + (int64_t)g * n_elems + i);
+        const float4 a0 = pk[0], a1 = pk[1], b0 = pv[0], b1 = pv[1];
+        sk[0] += a0.x; sk[1] += a0.y; sk[2] += a0.z; sk[3] += a0.w;
+        sk[4] += a1.x; sk[5] += a1.y; sk[6] += a1.z; sk[7] += a1.w;
+        sv[0] += b0.x; sv[1] += b0.y; sv[2] += b0.z; sv[3] += b0.w;
+        sv[4] += b1.x; sv[5] += b1.y; sv[6] += b1.z; sv[7] += b1.w;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) sk[e] *= scale;
+    Vec<bf16_t>::store(dk + i, sk);
+    Vec<bf16_t>::store(dv + i, sv);
+}
+
 bool attn_mfma_supported(const cf_layer_desc& L) {
     return L.dtype == CF_BF16 && (L.d == 64 || L.d == 128);
+}
+
+// bytes of fp32 per-head partials behind the D row statistics (0 for MHA)
+size_t attn_mfma_partial_bytes(const cf_layer_desc& L, int n_kept) {
+    if (!attn_mfma_supported(L) || L.Hq == L.Hkv) return 0;
+    return align_up((size_t)2 * (size_t)(n_kept > 0 ? n_kept : 1) * L.Hq * L.d * sizeof(float), 256);
 }
 
 template <int D>
@@ -442,8 +466,13 @@ static hipError_t launch_t(const AttnParams& p, int n_kept, hipStream_t st) {
     }
     const int max_per_seq = n_kept < p.S ? n_kept : p.S;
     const int tiles = ceil_div(max_per_seq, 128);
-    attn_dq_kernel<D><<<dim3(tiles, p.Hq, p.B), 256, smem_dq, st>>>(p);
-    attn_dkv_kernel<D><<<dim3(tiles, p.Hkv, p.B), 256, smem_dkv, st>>>(p);
+    attn_dq_kernel<D><<<dim3(p.Hq * p.B, tiles), 256, smem_dq, st>>>(p);
+    attn_dkv_kernel<D><<<dim3(p.Hq * p.B, tiles), 256, smem_dkv, st>>>(p);
+    if (p.Hq != p.Hkv) {
+        const int64_t n_elems = (int64_t)n_kept * p.Hkv * D;
+        attn_dkv_reduce_kernel<<<ceil_div(n_elems / 8, 256), 256, 0, st>>>(p.dk_part, p.dv_part, p.Hq / p.Hkv,
+                                                                          n_elems, p.scale, p.dk_kept, p.dv_kept);
+    }
     return hipGetLastError();
 }
 
@@ -451,12 +480,15 @@ hipError_t launch_attn_bwd_mfma(const cf_layer_desc& L, float scale, const void*
                                 const void* k_full, const void* v_full, const float* lse_full,
                                 const void* do_kept, const float* Drow, const int32_t* idx,
                                 const int32_t* cu_kept, int n_kept, void* dq_kept, void* dk_kept,
-                                void* dv_kept, hipStream_t st) {
+                                void* dv_kept, float* partials, hipStream_t st) {
     AttnParams p;
     p.q_kept = (const bf16_t*)q_kept; p.k_full = (const bf16_t*)k_full; p.v_full = (const bf16_t*)v_full;
     p.do_kept = (const bf16_t*)do_kept; p.lse_full = lse_full; p.Drow = Drow; p.idx = idx;
     p.cu_kept = cu_kept; p.dq_kept = (bf16_t*)dq_kept; p.dk_kept = (bf16_t*)dk_kept;
     p.dv_kept = (bf16_t*)dv_kept; p.B = L.B; p.S = L.S; p.Hq = L.Hq; p.Hkv = L.Hkv; p.scale = scale;
+    p.n_kept = n_kept;
+    p.dk_part = partials;
+    p.dv_part = partials ? partials + (size_t)n_kept * L.Hq * L.d : nullptr;
     if (L.d == 64) return launch_t<64>(p, n_kept, st);
     return launch_t<128>(p, n_kept, st);
 }

@@ -120,12 +120,4 @@ struct GemmSeg {
 hipError_t launch_gemm(int dtype, int mode, const GemmSeg* segs, int nseg, void* C, int M, int N,
                        float beta, hipStream_t st);
 
-// attn.hip
-size_t attn_ws_bytes(const cf_layer_desc& d, int n_kept);
-hipError_t launch_attn_bwd(const cf_layer_desc& d, const void* q_kept, const void* k_full,
-                           const void* v_full, const void* o_kept, const float* lse_full,
-                           const void* do_kept, const int32_t* idx, const int32_t* cu_kept,
-                           int n_kept, void* dq_kept, void* dk_kept, void* dv_kept, void* ws,
-                           hipStream_t st);
-
 }  // namespace cf

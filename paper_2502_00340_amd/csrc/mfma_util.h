@@ -1,0 +1,61 @@
+// Device helpers shared by the matrix-core kernels (gfx950): vector types, the
+// LDS-only barrier, manual vmcnt waits and the global -> LDS 16-byte-per-lane load.
+#pragma once
+
+#include "common.h"
+
+namespace cf {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
+// Workgroup barrier that orders LDS traffic only: global loads still in flight stay in flight.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+#define CF_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt = imm[15:14]:imm[3:0], expcnt imm[6:4], lgkmcnt imm[11:8])
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
+
+// Raw buffer descriptor over [base, base+bytes): loads past the end return zeros.
+__device__ __forceinline__ i32x4_t make_rsrc(const void* base, int64_t bytes) {
+    const int64_t lim = bytes < 0 ? 0 : (bytes > 0xFFFFFFFFll ? 0xFFFFFFFFll : bytes);
+    const uint64_t b = reinterpret_cast<uint64_t>(base);
+    i32x4_t r;
+    r.x = (int)(unsigned)b;
+    r.y = (int)(unsigned)((b >> 32) & 0xFFFFu);     // stride 0: raw buffer
+    r.z = (int)(unsigned)lim;
+    r.w = 0x00020000;
+    // the descriptor lives in scalar registers: make the uniformity explicit
+    r.x = __builtin_amdgcn_readfirstlane(r.x);
+    r.y = __builtin_amdgcn_readfirstlane(r.y);
+    r.z = __builtin_amdgcn_readfirstlane(r.z);
+    return r;
+}
+
+// 16 bytes per lane from global memory straight into LDS: lane l of the wave writes
+// LDS bytes [lds_base + 16*l, +16).  Issued as inline assembly so that the compiler
+// does not serialise later LDS reads against it; completion is tracked by hand with
+// vmcnt (the loads of a wave retire in order).
+__device__ __forceinline__ void dma16(unsigned lds_base /*wave-uniform*/, i32x4_t rsrc, unsigned voffset) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_base), "v"(voffset), "s"(rsrc)
+                 : "memory");
+}
+
+__device__ __forceinline__ unsigned lds_addr_of(const void* p) {
+    return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+
+}  // namespace cf
