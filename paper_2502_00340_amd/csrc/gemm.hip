@@ -67,18 +67,20 @@ __device__ __forceinline__ void tile_coords(int pid, int tiles_m, int tiles_n, i
     bn = r / gsize;
 }
 
-template <int MODE, int TM, int TN>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
-    constexpr int BM = 2 * TM * 32, BN = 2 * TN * 32;
+template <int MODE, int WGM, int WGN, int TM, int TN>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(GemmArgs g) {
+    constexpr int NW = WGM * WGN, NTHREADS = 64 * NW;
+    constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
     constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
-    constexpr int A_LD = A_BYTES / 4096, B_LD = B_BYTES / 4096;   // 1 KB wave-loads per wave per tile
+    constexpr int A_LD = A_BYTES / (1024 * NW), B_LD = B_BYTES / (1024 * NW);   // 1 KB wave-loads per wave per tile
+    static_assert(A_LD >= 1 && B_LD >= 1, "tile too small for the wave count");
     constexpr int LD = A_LD + B_LD;
     constexpr unsigned OOB = 0xFFFFFFFFu;
     constexpr int C_PITCH = BN * 2 + 16;                           // staged C tile row pitch (bytes)
     extern __shared__ __align__(16) unsigned char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WGN, wn = wave % WGN;
     const int slot = lane & 31, hh = lane >> 5;
 
     int bm, bn;
@@ -97,12 +99,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     for (int s = 0; s < g.nseg; ++s) total_steps += (g.K[s] + BK - 1) / BK;
 
     // ---- global -> LDS: one K-step of both operand tiles -------------------------
-    // Wave w, load i fills LDS bytes [(4*i + w) KB, +1 KB) of the tile; lane l owns
+    // Wave w, load i fills LDS bytes [(NW*i + w) KB, +1 KB) of the tile; lane l owns
     // the 16 bytes at +16*l.  Offsets are relative to the block's first row / column.
     int seg = 0, k0 = 0, Kseg = 0;       // K-step that the next issue_loads() fetches
     i32x4_t rsA, rsB;
     unsigned ldA = 0, ldB = 0;           // row pitch in bytes of the current segment's operands
-    auto open_segment = [&](int s) {
+    auto open_segment = [&](int s) __attribute__((always_inline)) {
         const bf16_t* A = static_cast<const bf16_t*>(g.A[s]);
         const bf16_t* B = static_cast<const bf16_t*>(g.B[s]);
         Kseg = g.K[s];
@@ -118,7 +120,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
             ldB = (unsigned)g.N * 2u;
         }
     };
-    auto issue_loads = [&](int stage) {
+    auto issue_loads = [&](int stage) __attribute__((always_inline)) {
         const unsigned sa = __builtin_amdgcn_readfirstlane(lds_addr_of(smem) + stage * STAGE + wave * 1024);
         const unsigned sb = sa + A_BYTES;
         if (MODE == 0) {
@@ -127,29 +129,29 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
             const unsigned kb = (k0 + (int)lc * 8 < Kseg) ? (unsigned)(k0 + (int)lc * 8) * 2u : OOB;
 #pragma unroll
             for (int i = 0; i < A_LD; ++i) {
-                const unsigned row = (4 * i + wave) * 16 + (lane >> 2);
-                dma16(sa + i * 4096, rsA, kb == OOB ? OOB : row * ldA + kb);
+                const unsigned row = (NW * i + wave) * 16 + (lane >> 2);
+                dma16(sa + i * NW * 1024, rsA, kb == OOB ? OOB : row * ldA + kb);
             }
 #pragma unroll
             for (int i = 0; i < B_LD; ++i) {
-                const unsigned row = (4 * i + wave) * 16 + (lane >> 2);
-                dma16(sb + i * 4096, rsB, kb == OOB ? OOB : row * ldB + kb);
+                const unsigned row = (NW * i + wave) * 16 + (lane >> 2);
+                dma16(sb + i * NW * 1024, rsB, kb == OOB ? OOB : row * ldB + kb);
             }
         } else {
             // tile [32][BM] as in memory: a wave-load covers 1024 / (BM*2) k-rows
 #pragma unroll
             for (int i = 0; i < A_LD; ++i) {
-                const int q = (4 * i + wave) * 64 + lane;
+                const int q = (NW * i + wave) * 64 + lane;
                 const int kr = q / (BM / 8), c = q % (BM / 8);
                 const bool ok = (m0 + c * 8 < g.M) && (k0 + kr < Kseg);
-                dma16(sa + i * 4096, rsA, ok ? (unsigned)(k0 + kr) * ldA + c * 16u : OOB);
+                dma16(sa + i * NW * 1024, rsA, ok ? (unsigned)(k0 + kr) * ldA + c * 16u : OOB);
             }
 #pragma unroll
             for (int i = 0; i < B_LD; ++i) {
-                const int q = (4 * i + wave) * 64 + lane;
+                const int q = (NW * i + wave) * 64 + lane;
                 const int kr = q / (BN / 8), c = q % (BN / 8);
                 const bool ok = (n0 + c * 8 < g.N) && (k0 + kr < Kseg);
-                dma16(sb + i * 4096, rsB, ok ? (unsigned)(k0 + kr) * ldB + c * 16u : OOB);
+                dma16(sb + i * NW * 1024, rsB, ok ? (unsigned)(k0 + kr) * ldB + c * 16u : OOB);
             }
         }
         k0 += BK;
@@ -166,7 +168,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     };
     // NT: tile [rows][32]; the lane reads row row0 + i*32 + slot, logical chunk ks*2 + hh
     const int nt_sw = (slot >> 2) & 3;
-    auto frags_nt = [&](const unsigned char* tile, int row0, int ks, bf16x8_t* frag, auto ntiles) {
+    auto frags_nt = [&](const unsigned char* tile, int row0, int ks, bf16x8_t* frag, auto ntiles) __attribute__((always_inline)) {
         constexpr int NT_ = decltype(ntiles)::value;
         const unsigned char* p = tile + (row0 + slot) * 64 + (((ks * 2 + hh) ^ nt_sw) << 4);
 #pragma unroll
@@ -174,7 +176,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
             frag[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(p + i * 32 * 64));
     };
     // TN: tile [32][W] as in memory; the lane owns columns col0 + slot*NT_ .. +NT_-1
-    auto frags_tn = [&](const unsigned char* tile, int W, int col0, int ks, bf16x8_t* frag, auto ntiles) {
+    auto frags_tn = [&](const unsigned char* tile, int W, int col0, int ks, bf16x8_t* frag, auto ntiles) __attribute__((always_inline)) {
         constexpr int NT_ = decltype(ntiles)::value;
         static_assert(NT_ == 2 || NT_ == 4, "TM/TN must be 2 or 4");
         unsigned r[8][NT_ / 2];
@@ -200,10 +202,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
             frag[i] = __builtin_bit_cast(bf16x8_t, v);
         }
     };
-    auto load_frags = [&](int stage, int ks, Frags& f) {
-#ifdef CF_EXP_NOFRAG
-        if (g.beta != 123.f) return;
-#endif
+    auto load_frags = [&](int stage, int ks, Frags& f) __attribute__((always_inline)) {
         const unsigned char* sa = smem + stage * STAGE;
         const unsigned char* sb = sa + A_BYTES;
         if (MODE == 0) {
@@ -216,10 +215,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     };
     // NT: D = Bfrag x Afrag  -> lane = output row (m slot), registers = output columns
     // TN: D = Afrag x Bfrag  -> lane = n slot (TN adjacent columns per lane), registers = m slots
-    auto mma = [&](const Frags& f) {
-#ifdef CF_EXP_NOMMA
-        if (g.beta == 123.f)
-#endif
+    auto mma = [&](const Frags& f) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -247,9 +243,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
         load_frags(0, 0, f0);
         for (int t = 0; t < total_steps; ++t) {
             const int cur = t & (STAGES - 1);
-#ifndef CF_EXP_NOGLOBAL
             if (t + 3 < total_steps) issue_loads((t + 3) & (STAGES - 1));
-#endif
             CF_SCHED_FENCE();
             load_frags(cur, 1, f1);
             CF_SCHED_FENCE();
@@ -267,9 +261,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     }
 
     // ---- epilogue: acc -> bf16 -> LDS C tile -> global with 16-byte stores -----------
-#ifdef CF_EXP_NOEPI
-    if (g.beta != 123.f) return;
-#endif
     lds_barrier();      // every wave is done reading operand stages
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
@@ -312,12 +303,236 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
         bf16_t* C = static_cast<bf16_t*>(g.C);
         const float beta = g.beta;
         constexpr int CPR = BN / 8;                  // 16-byte chunks per tile row
-        constexpr int RPP = 256 / CPR;               // rows per pass
+        constexpr int RPP = NTHREADS / CPR;          // rows per pass
         const int c = tid % CPR, r0 = tid / CPR;
         const int n = n0 + c * 8;
         if (n < g.N) {                                // N is a multiple of 8
 #pragma unroll 4
             for (int r = r0; r < BM; r += RPP) {
+                const int m = m0 + r;
+                if (m >= g.M) break;
+                u32x4_t val = *reinterpret_cast<const u32x4_t*>(smem + r * C_PITCH + c * 16);
+                bf16_t* p = C + (int64_t)m * g.N + n;
+                if (beta != 0.f) {
+                    const u32x4_t old = *reinterpret_cast<const u32x4_t*>(p);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float lo = __uint_as_float(val[e] << 16) + beta * __uint_as_float(old[e] << 16);
+                        const float hi = __uint_as_float(val[e] & 0xFFFF0000u) +
+                                         beta * __uint_as_float(old[e] & 0xFFFF0000u);
+                        val[e] = pack_bf16x2(lo, hi);
+                    }
+                }
+                *reinterpret_cast<u32x4_t*>(p) = val;
+            }
+        }
+    }
+}
+
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4_t;
+typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8_t;
+typedef __attribute__((address_space(3))) s16x4_t* lds_s16x4_ptr;
+
+// per-k-row XOR (in units of 32 bytes) of the K-major tiles: the 8 rows one transpose read
+// touches, {4j + r, 8 + 4j + r : r < 4}, land in 8 different 32-byte bank groups
+__device__ __forceinline__ int tn_swz(int k) { return (k & 3) | ((k & 8) >> 1); }
+
+// ---------------------------------------------------------------------------
+// Large-tile kernel: 256x256 block, 4 waves of 128x128 (the wave tile with the
+// fewest LDS bytes per MFMA), K step 64 so that every global->LDS load moves whole
+// 128-byte lines, two LDS stages.  The instruction stream of a K-step is laid out
+// by hand: each of the 64 MFMAs of a wave is preceded by at most one global->LDS
+// load (the 16 loads of the next K-step go out during the first 16 MFMAs) and at
+// most one fragment read for the following 16-wide sub-step, so no burst of
+// memory instructions ever stands between two MFMAs.
+// ---------------------------------------------------------------------------
+template <int MODE>
+__global__ __launch_bounds__(256) void gemm_bf16_k64_kernel(GemmArgs g) {
+    constexpr int TM = 4, TN = 4, BM = 256, BN = 256, KB = 64;
+    constexpr int A_BYTES = BM * KB * 2, STAGE = 2 * A_BYTES;
+    constexpr unsigned OOB = 0xFFFFFFFFu;
+    constexpr int C_PITCH = BN * 2 + 16;
+    extern __shared__ __align__(16) unsigned char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int slot = lane & 31, hh = lane >> 5;
+
+    int bm, bn;
+    tile_coords(blockIdx.x, (g.M + BM - 1) / BM, (g.N + BN - 1) / BN, bm, bn);
+    const int m0 = bm * BM, n0 = bn * BN;
+
+    f32x16_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int total_steps = (g.K[0] + KB - 1) / KB + (g.K[1] + KB - 1) / KB + (g.K[2] + KB - 1) / KB;
+
+    // ---- global -> LDS -----------------------------------------------------------
+    int seg = 0, k0 = 0, Kseg = 0;
+    i32x4_t rsA, rsB;
+    unsigned ldA = 0, ldB = 0;
+    auto open_segment = [&](int s) __attribute__((always_inline)) {
+        // static indices keep the arguments in the kernarg segment (scalar loads); past the last
+        // segment the descriptor of segment 0 is reused with Kseg = 0, so every load is out of range
+        const bool live = s < g.nseg;
+        const bf16_t* A = static_cast<const bf16_t*>(s == 1 ? g.A[1] : (s == 2 ? g.A[2] : g.A[0]));
+        const bf16_t* B = static_cast<const bf16_t*>(s == 1 ? g.B[1] : (s == 2 ? g.B[2] : g.B[0]));
+        const int Kraw = s == 1 ? g.K[1] : (s == 2 ? g.K[2] : g.K[0]);
+        Kseg = live ? Kraw : 0;
+        const int64_t K = Kraw;
+        if (MODE == 0) {
+            rsA = make_rsrc(A + (int64_t)m0 * K, ((int64_t)g.M - m0) * K * 2);
+            rsB = make_rsrc(B + (int64_t)n0 * K, ((int64_t)g.N - n0) * K * 2);
+            ldA = ldB = (unsigned)K * 2u;
+        } else {
+            rsA = make_rsrc(A + m0, (K * g.M - m0) * 2);
+            rsB = make_rsrc(B + n0, (K * g.N - n0) * 2);
+            ldA = (unsigned)g.M * 2u;
+            ldB = (unsigned)g.N * 2u;
+        }
+    };
+    const unsigned lds0 = __builtin_amdgcn_readfirstlane(lds_addr_of(smem) + wave * 1024);
+    // load q (0..15) of the K-step (seg, k0): q < 8 -> A tile, else B tile; wave-load index 4*(q%8) + wave
+    // NT: a wave-load is 8 rows x 8 chunks of a [256][64] tile, chunk XOR-swizzled by (row/2)%8
+    // TN: a wave-load is 2 k-rows of a [64][256] tile, stored as in memory
+    const unsigned nt_lc = (unsigned)((lane & 7) ^ ((((wave & 1) << 2) | (lane >> 4)) & 7));
+    auto dma_one = [&](int stage, int q) __attribute__((always_inline)) {
+        const bool isA = q < 8;
+        const int i = q & 7;
+        const unsigned dst = lds0 + stage * STAGE + (isA ? 0 : A_BYTES) + i * 4096;
+        unsigned off;
+        if (MODE == 0) {
+            // row = (4*i + wave)*8 + lane/8; (row/2)%8 = ((wave&1)*4 + lane/16) % 8 for every i
+            const unsigned row = (4 * i + wave) * 8 + (lane >> 3);
+            const int kk = k0 + (int)nt_lc * 8;
+            off = (kk < Kseg) ? row * (isA ? ldA : ldB) + (unsigned)kk * 2u : OOB;
+        } else {
+            const int qq = (4 * i + wave) * 64 + lane;
+            const int kr = qq >> 5;                           // 32 chunks per 256-wide row
+            const int c = (qq & 31) ^ (tn_swz(kr) << 1);      // global chunk that belongs in this LDS slot
+            const bool ok = ((isA ? m0 : n0) + c * 8 < (isA ? g.M : g.N)) && (k0 + kr < Kseg);
+            off = ok ? (unsigned)(k0 + kr) * (isA ? ldA : ldB) + c * 16u : OOB;
+        }
+        if (isA) dma16(dst, rsA, off);
+        else dma16(dst, rsB, off);
+    };
+#define CF_ADVANCE_KSTEP()          \
+    do {                            \
+        k0 += KB;                   \
+        if (k0 >= Kseg) {           \
+            k0 = 0;                 \
+            ++seg;                  \
+            open_segment(seg);      \
+        }                           \
+    } while (0)
+
+    // ---- LDS -> fragments ------------------------------------------------------------
+    bf16x8_t fa[2][TM], fb[2][TN];
+    const int nt_sw = (slot >> 1) & 7;
+    // NT: fragment u (0..3 = A rows, 4..7 = B rows) of sub-step ks
+    auto frag_nt_one = [&](int stage, int ks, int u, int buf) __attribute__((always_inline)) {
+        const bool isA = u < 4;
+        const int i = u & 3;
+        const unsigned char* tile = smem + stage * STAGE + (isA ? 0 : A_BYTES);
+        const int row = (isA ? wm : wn) * 128 + i * 32 + slot;
+        const u32x4_t v = *reinterpret_cast<const u32x4_t*>(tile + row * 128 + (((ks * 2 + hh) ^ nt_sw) << 4));
+        if (isA) fa[buf][i] = __builtin_bit_cast(bf16x8_t, v);
+        else fb[buf][i] = __builtin_bit_cast(bf16x8_t, v);
+    };
+    // TN: tile [64 k][256 m] as in memory, 16-byte chunks XOR-swizzled per k-row; the fragment is
+    // fetched with two LDS transpose reads (4 k-rows x 16 columns per 16 lanes each)
+    auto frag_tn_one = [&](int stage, int ks, int u, int buf) __attribute__((always_inline)) {
+        const bool isA = u < 4;
+        const int i = u & 3;
+        const unsigned char* tile = smem + stage * STAGE + (isA ? 0 : A_BYTES);
+        const int k = ks * 16 + 8 * hh + ((lane & 15) >> 2);
+        const int lc = ((isA ? wm : wn) * 128 + i * 32) / 8 + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+        const int sub = (lane & 1) * 8;
+        const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (lds_s16x4_ptr)(tile + k * 512 + ((lc ^ (tn_swz(k) << 1)) << 4) + sub));
+        const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (lds_s16x4_ptr)(tile + (k + 4) * 512 + ((lc ^ (tn_swz(k + 4) << 1)) << 4) + sub));
+        const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        if (isA) fa[buf][i] = __builtin_bit_cast(bf16x8_t, both);
+        else fb[buf][i] = __builtin_bit_cast(bf16x8_t, both);
+    };
+    // MFMA q (0..15) of a sub-step
+    auto mma_one = [&](int q, int buf) __attribute__((always_inline)) {
+        const int i = q >> 2, j = q & 3;
+        // D = Bfrag x Afrag: lane = output row, registers = groups of 4 adjacent output columns
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][j], fa[buf][i], acc[i][j], 0, 0, 0);
+    };
+    // one 16-wide sub-step: MFMAs on fragment buffer `buf`, next fragments (stage ns, sub-step nks)
+    // into the other buffer, optionally the loads of the next K-step
+    auto substep = [&](int buf, int ns, int nks, bool with_dma, int dma_stage) __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            if (with_dma) dma_one(dma_stage, q);
+            if ((q & 1) == 0) {
+                if (MODE == 0) frag_nt_one(ns, nks, q >> 1, buf ^ 1);
+                else frag_tn_one(ns, nks, q >> 1, buf ^ 1);
+            }
+            CF_SCHED_FENCE();
+            mma_one(q, buf);
+            CF_SCHED_FENCE();
+        }
+    };
+
+    if (total_steps > 0) {
+        open_segment(0);
+#pragma unroll
+        for (int q = 0; q < 16; ++q) dma_one(0, q);
+        CF_ADVANCE_KSTEP();
+        wait_vmcnt<0>();
+        lds_barrier();
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            if (MODE == 0) frag_nt_one(0, 0, u, 0);
+            else frag_tn_one(0, 0, u, 0);
+        }
+        for (int t = 0; t < total_steps; ++t) {
+            const int cur = t & 1;
+            substep(0, cur, 1, true, cur ^ 1);      // loads of K-step t+1 (out of range past the end)
+            CF_ADVANCE_KSTEP();
+            substep(1, cur, 2, false, 0);
+            substep(0, cur, 3, false, 0);
+            wait_vmcnt<0>();
+            lds_barrier();
+            substep(1, cur ^ 1, 0, false, 0);
+        }
+    }
+
+#undef CF_ADVANCE_KSTEP
+
+    // ---- epilogue (same as the small-tile kernel) -----------------------------------------
+    lds_barrier();
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4) {
+                const int r = wm * 128 + i * 32 + slot;
+                const int c = wn * 128 + j * 32 + 8 * v4 + 4 * hh;
+                uint2 o;
+                o.x = pack_bf16x2(acc[i][j][4 * v4 + 0], acc[i][j][4 * v4 + 1]);
+                o.y = pack_bf16x2(acc[i][j][4 * v4 + 2], acc[i][j][4 * v4 + 3]);
+                *reinterpret_cast<uint2*>(smem + r * C_PITCH + c * 2) = o;
+            }
+    lds_barrier();
+    {
+        bf16_t* C = static_cast<bf16_t*>(g.C);
+        const float beta = g.beta;
+        const int c = tid & 31, r0 = tid >> 5;
+        const int n = n0 + c * 8;
+        if (n < g.N) {
+#pragma unroll 4
+            for (int r = r0; r < BM; r += 8) {
                 const int m = m0 + r;
                 if (m >= g.M) break;
                 u32x4_t val = *reinterpret_cast<const u32x4_t*>(smem + r * C_PITCH + c * 16);
@@ -398,21 +613,36 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g) {
     }
 }
 
-template <int MODE, int TM, int TN>
+template <int MODE>
+static hipError_t launch_k64(const GemmArgs& g, hipStream_t st) {
+    constexpr int smem = 256 * (256 * 2 + 16);      // C tile staging > 2 operand stages of 64 KB
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_k64_kernel<MODE>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int grid = ceil_div(g.M, 256) * ceil_div(g.N, 256);
+    gemm_bf16_k64_kernel<MODE><<<grid, 256, smem, st>>>(g);
+    return hipGetLastError();
+}
+
+template <int MODE, int WGM, int WGN, int TM, int TN>
 static hipError_t launch_bf16(const GemmArgs& g, hipStream_t st) {
-    constexpr int BM = 2 * TM * 32, BN = 2 * TN * 32;
+    constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
     constexpr int stages = STAGES * (BM + BN) * BK * 2;
     constexpr int ctile = BM * (BN * 2 + 16);
     constexpr int smem = stages > ctile ? stages : ctile;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<MODE, TM, TN>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<MODE, WGM, WGN, TM, TN>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int grid = ceil_div(g.M, BM) * ceil_div(g.N, BN);
-    gemm_bf16_kernel<MODE, TM, TN><<<grid, 256, smem, st>>>(g);
+    gemm_bf16_kernel<MODE, WGM, WGN, TM, TN><<<grid, 64 * WGM * WGN, smem, st>>>(g);
     return hipGetLastError();
 }
 
@@ -444,8 +674,10 @@ hipError_t launch_gemm(int dtype, int mode, const GemmSeg* segs, int nseg, void*
     // tile choice: big tiles when they still give every CU work, else 128x128
     const int64_t big_tiles = (int64_t)ceil_div(M, 256) * ceil_div(N, 256);
     const bool big = big_tiles >= 200;
-    if (mode == 0) return big ? launch_bf16<0, 4, 4>(g, st) : launch_bf16<0, 2, 2>(g, st);
-    return big ? launch_bf16<1, 4, 4>(g, st) : launch_bf16<1, 2, 2>(g, st);
+    // big: 256x256 block, 8 waves (2 per SIMD) of 128x64; small: 128x128 block, 4 waves of 64x64
+    if (big) return mode == 0 ? launch_k64<0>(g, st) : launch_k64<1>(g, st);
+    if (mode == 0) return big ? launch_bf16<0, 2, 4, 4, 2>(g, st) : launch_bf16<0, 2, 2, 2, 2>(g, st);
+    return big ? launch_bf16<1, 2, 4, 4, 2>(g, st) : launch_bf16<1, 2, 2, 2, 2>(g, st);
 }
 
 }  // namespace cf

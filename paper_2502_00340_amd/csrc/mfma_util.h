@@ -48,6 +48,12 @@ __device__ __forceinline__ i32x4_t make_rsrc(const void* base, int64_t bytes) {
 // does not serialise later LDS reads against it; completion is tracked by hand with
 // vmcnt (the loads of a wave retire in order).
 __device__ __forceinline__ void dma16(unsigned lds_base /*wave-uniform*/, i32x4_t rsrc, unsigned voffset) {
+    // both scalar operands are wave-uniform by construction; say so (free when the compiler already knows)
+    lds_base = __builtin_amdgcn_readfirstlane(lds_base);
+    rsrc.x = __builtin_amdgcn_readfirstlane(rsrc.x);
+    rsrc.y = __builtin_amdgcn_readfirstlane(rsrc.y);
+    rsrc.z = __builtin_amdgcn_readfirstlane(rsrc.z);
+    rsrc.w = __builtin_amdgcn_readfirstlane(rsrc.w);
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                  :
                  : "s"(lds_base), "v"(voffset), "s"(rsrc)
