@@ -339,17 +339,23 @@ __device__ __forceinline__ int tn_swz(int k) { return (k & 3) | ((k & 8) >> 1); 
 
 // ---------------------------------------------------------------------------
 // Large-tile kernel: 256x256 block, 4 waves of 128x128 (the wave tile with the
-// fewest LDS bytes per MFMA), K step 64 so that every global->LDS load moves whole
-// 128-byte lines, two LDS stages.  The instruction stream of a K-step is laid out
-// by hand: each of the 64 MFMAs of a wave is preceded by at most one global->LDS
-// load (the 16 loads of the next K-step go out during the first 16 MFMAs) and at
-// most one fragment read for the following 16-wide sub-step, so no burst of
-// memory instructions ever stands between two MFMAs.
+// fewest LDS bytes per MFMA).  Operand tiles move in K-steps of 32 through a ring
+// of five 32 KB LDS stages; the loads of two consecutive K-steps (one whole
+// 128-byte line of every operand row) are issued back to back, a full 64-wide
+// step ahead of the barrier that publishes them.  The instruction stream is laid
+// out by hand: each MFMA is preceded by at most one global->LDS load and one
+// fragment read for the following 16-wide sub-step, so no burst of memory
+// instructions stands between two MFMAs.  One LDS barrier per 64 MFMAs of a wave.
+//   NT stage: [256 rows][32 k], 64-byte rows, 16-byte chunk XOR (row/4)%4.
+//   TN stage: [32 k][256 m] as in memory with the chunk index XOR-swizzled per
+//   k-row; fragments come out of LDS through the transpose read, in the same
+//   register layout as the NT ones, so MFMA order and epilogue are shared.
 // ---------------------------------------------------------------------------
 template <int MODE>
-__global__ __launch_bounds__(256) void gemm_bf16_k64_kernel(GemmArgs g) {
-    constexpr int TM = 4, TN = 4, BM = 256, BN = 256, KB = 64;
-    constexpr int A_BYTES = BM * KB * 2, STAGE = 2 * A_BYTES;
+__global__ __launch_bounds__(256) void gemm_bf16_ring_kernel(GemmArgs g) {
+    constexpr int TM = 4, TN = 4, BM = 256, BN = 256, KB = 32, NST = 5;
+    constexpr int A_BYTES = BM * KB * 2, STAGE = 2 * A_BYTES;       // 16 KB + 16 KB
+    constexpr int LDH = 8;                                          // wave-loads per wave per K-step
     constexpr unsigned OOB = 0xFFFFFFFFu;
     constexpr int C_PITCH = BN * 2 + 16;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -373,12 +379,14 @@ __global__ __launch_bounds__(256) void gemm_bf16_k64_kernel(GemmArgs g) {
     const int total_steps = (g.K[0] + KB - 1) / KB + (g.K[1] + KB - 1) / KB + (g.K[2] + KB - 1) / KB;
 
     // ---- global -> LDS -----------------------------------------------------------
+    // (seg, k0): the K-step that the next load group fetches.  Past the last segment the
+    // descriptor of segment 0 stays in place with Kseg = 0, so every load is out of range
+    // (zero fill into a stage nobody reads): the number of loads per K-step never changes,
+    // which keeps the vmcnt bookkeeping constant.
     int seg = 0, k0 = 0, Kseg = 0;
     i32x4_t rsA, rsB;
     unsigned ldA = 0, ldB = 0;
     auto open_segment = [&](int s) __attribute__((always_inline)) {
-        // static indices keep the arguments in the kernarg segment (scalar loads); past the last
-        // segment the descriptor of segment 0 is reused with Kseg = 0, so every load is out of range
         const bool live = s < g.nseg;
         const bf16_t* A = static_cast<const bf16_t*>(s == 1 ? g.A[1] : (s == 2 ? g.A[2] : g.A[0]));
         const bf16_t* B = static_cast<const bf16_t*>(s == 1 ? g.B[1] : (s == 2 ? g.B[2] : g.B[0]));
@@ -396,31 +404,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_k64_kernel(GemmArgs g) {
             ldB = (unsigned)g.N * 2u;
         }
     };
-    const unsigned lds0 = __builtin_amdgcn_readfirstlane(lds_addr_of(smem) + wave * 1024);
-    // load q (0..15) of the K-step (seg, k0): q < 8 -> A tile, else B tile; wave-load index 4*(q%8) + wave
-    // NT: a wave-load is 8 rows x 8 chunks of a [256][64] tile, chunk XOR-swizzled by (row/2)%8
-    // TN: a wave-load is 2 k-rows of a [64][256] tile, stored as in memory
-    const unsigned nt_lc = (unsigned)((lane & 7) ^ ((((wave & 1) << 2) | (lane >> 4)) & 7));
-    auto dma_one = [&](int stage, int q) __attribute__((always_inline)) {
-        const bool isA = q < 8;
-        const int i = q & 7;
-        const unsigned dst = lds0 + stage * STAGE + (isA ? 0 : A_BYTES) + i * 4096;
-        unsigned off;
-        if (MODE == 0) {
-            // row = (4*i + wave)*8 + lane/8; (row/2)%8 = ((wave&1)*4 + lane/16) % 8 for every i
-            const unsigned row = (4 * i + wave) * 8 + (lane >> 3);
-            const int kk = k0 + (int)nt_lc * 8;
-            off = (kk < Kseg) ? row * (isA ? ldA : ldB) + (unsigned)kk * 2u : OOB;
-        } else {
-            const int qq = (4 * i + wave) * 64 + lane;
-            const int kr = qq >> 5;                           // 32 chunks per 256-wide row
-            const int c = (qq & 31) ^ (tn_swz(kr) << 1);      // global chunk that belongs in this LDS slot
-            const bool ok = ((isA ? m0 : n0) + c * 8 < (isA ? g.M : g.N)) && (k0 + kr < Kseg);
-            off = ok ? (unsigned)(k0 + kr) * (isA ? ldA : ldB) + c * 16u : OOB;
-        }
-        if (isA) dma16(dst, rsA, off);
-        else dma16(dst, rsB, off);
-    };
 #define CF_ADVANCE_KSTEP()          \
     do {                            \
         k0 += KB;                   \
@@ -431,85 +414,137 @@ __global__ __launch_bounds__(256) void gemm_bf16_k64_kernel(GemmArgs g) {
         }                           \
     } while (0)
 
+    const unsigned lds0 = __builtin_amdgcn_readfirstlane(lds_addr_of(smem) + wave * 1024);
+    // wave-load u (0..7) of K-step (seg, kk0): u < 4 -> A tile, else B tile; tile bytes [(4*(u%4) + wave) KB, +1 KB)
+    // NT: 16 rows x 4 chunks, the chunk a lane fetches undoes the XOR swizzle of its LDS slot
+    // TN: 2 k-rows x 32 chunks
+    const unsigned nt_lc = (unsigned)((lane & 3) ^ ((lane >> 4) & 3));
+    auto dma_one = [&](int stage, int u, int kk0) __attribute__((always_inline)) {
+        const bool isA = u < 4;
+        const int i = u & 3;
+        const unsigned dst = lds0 + stage * STAGE + (isA ? 0 : A_BYTES) + i * 4096;
+        unsigned off;
+        if (MODE == 0) {
+            const unsigned row = (4 * i + wave) * 16 + (lane >> 2);
+            const int kk = kk0 + (int)nt_lc * 8;
+            off = (kk < Kseg) ? row * (isA ? ldA : ldB) + (unsigned)kk * 2u : OOB;
+        } else {
+            const int qq = (4 * i + wave) * 64 + lane;
+            const int kr = qq >> 5;
+            const int c = (qq & 31) ^ (tn_swz(kr) << 1);
+            const bool ok = ((isA ? m0 : n0) + c * 8 < (isA ? g.M : g.N)) && (kk0 + kr < Kseg);
+            off = ok ? (unsigned)(kk0 + kr) * (isA ? ldA : ldB) + c * 16u : OOB;
+        }
+        if (isA) dma16(dst, rsA, off);
+        else dma16(dst, rsB, off);
+    };
+
     // ---- LDS -> fragments ------------------------------------------------------------
     bf16x8_t fa[2][TM], fb[2][TN];
-    const int nt_sw = (slot >> 1) & 7;
-    // NT: fragment u (0..3 = A rows, 4..7 = B rows) of sub-step ks
-    auto frag_nt_one = [&](int stage, int ks, int u, int buf) __attribute__((always_inline)) {
+    const int nt_sw = (slot >> 2) & 3;
+    auto frag_one = [&](int stage, int ks, int u, int buf) __attribute__((always_inline)) {
         const bool isA = u < 4;
         const int i = u & 3;
         const unsigned char* tile = smem + stage * STAGE + (isA ? 0 : A_BYTES);
-        const int row = (isA ? wm : wn) * 128 + i * 32 + slot;
-        const u32x4_t v = *reinterpret_cast<const u32x4_t*>(tile + row * 128 + (((ks * 2 + hh) ^ nt_sw) << 4));
-        if (isA) fa[buf][i] = __builtin_bit_cast(bf16x8_t, v);
-        else fb[buf][i] = __builtin_bit_cast(bf16x8_t, v);
+        bf16x8_t f;
+        if (MODE == 0) {
+            const int row = (isA ? wm : wn) * 128 + i * 32 + slot;
+            f = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(
+                                                 tile + row * 64 + (((ks * 2 + hh) ^ nt_sw) << 4)));
+        } else {
+            const int k = ks * 16 + 8 * hh + ((lane & 15) >> 2);
+            const int lc = ((isA ? wm : wn) * 128 + i * 32) / 8 + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+            const int sub = (lane & 1) * 8;
+            const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (lds_s16x4_ptr)(tile + k * 512 + ((lc ^ (tn_swz(k) << 1)) << 4) + sub));
+            const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (lds_s16x4_ptr)(tile + (k + 4) * 512 + ((lc ^ (tn_swz(k + 4) << 1)) << 4) + sub));
+            f = __builtin_bit_cast(bf16x8_t, (s16x8_t)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        }
+        if (isA) fa[buf][i] = f;
+        else fb[buf][i] = f;
     };
-    // TN: tile [64 k][256 m] as in memory, 16-byte chunks XOR-swizzled per k-row; the fragment is
-    // fetched with two LDS transpose reads (4 k-rows x 16 columns per 16 lanes each)
-    auto frag_tn_one = [&](int stage, int ks, int u, int buf) __attribute__((always_inline)) {
-        const bool isA = u < 4;
-        const int i = u & 3;
-        const unsigned char* tile = smem + stage * STAGE + (isA ? 0 : A_BYTES);
-        const int k = ks * 16 + 8 * hh + ((lane & 15) >> 2);
-        const int lc = ((isA ? wm : wn) * 128 + i * 32) / 8 + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
-        const int sub = (lane & 1) * 8;
-        const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (lds_s16x4_ptr)(tile + k * 512 + ((lc ^ (tn_swz(k) << 1)) << 4) + sub));
-        const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (lds_s16x4_ptr)(tile + (k + 4) * 512 + ((lc ^ (tn_swz(k + 4) << 1)) << 4) + sub));
-        const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        if (isA) fa[buf][i] = __builtin_bit_cast(bf16x8_t, both);
-        else fb[buf][i] = __builtin_bit_cast(bf16x8_t, both);
-    };
-    // MFMA q (0..15) of a sub-step
+    // MFMA q (0..15) of a sub-step: D = Bfrag x Afrag, lane = output row, registers = 4-column groups
     auto mma_one = [&](int q, int buf) __attribute__((always_inline)) {
         const int i = q >> 2, j = q & 3;
-        // D = Bfrag x Afrag: lane = output row, registers = groups of 4 adjacent output columns
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][j], fa[buf][i], acc[i][j], 0, 0, 0);
     };
-    // one 16-wide sub-step: MFMAs on fragment buffer `buf`, next fragments (stage ns, sub-step nks)
-    // into the other buffer, optionally the loads of the next K-step
-    auto substep = [&](int buf, int ns, int nks, bool with_dma, int dma_stage) __attribute__((always_inline)) {
+    // one 16-wide sub-step: MFMAs on fragment buffer `buf`; the fragments of (stage ns, sub-step nks)
+    // go into the other buffer; with_dma: the 16 loads of the next two K-steps, one per MFMA,
+    // the two halves of each 128-byte line adjacent
+    auto substep = [&](int buf, int ns, int nks, bool with_dma, int st0, int st1) __attribute__((always_inline)) {
 #pragma unroll
         for (int q = 0; q < 16; ++q) {
-            if (with_dma) dma_one(dma_stage, q);
-            if ((q & 1) == 0) {
-                if (MODE == 0) frag_nt_one(ns, nks, q >> 1, buf ^ 1);
-                else frag_tn_one(ns, nks, q >> 1, buf ^ 1);
+            if (with_dma) {
+                if ((q & 1) == 0) dma_one(st0, q >> 1, k0);
+                else dma_one(st1, q >> 1, k0 + KB);
             }
+            if ((q & 1) == 0) frag_one(ns, nks, q >> 1, buf ^ 1);
             CF_SCHED_FENCE();
             mma_one(q, buf);
             CF_SCHED_FENCE();
         }
     };
-
-    if (total_steps > 0) {
-        open_segment(0);
-#pragma unroll
-        for (int q = 0; q < 16; ++q) dma_one(0, q);
-        CF_ADVANCE_KSTEP();
-        wait_vmcnt<0>();
-        lds_barrier();
+    // loads of two consecutive K-steps outside the MFMA stream (prologue)
+    auto issue_pair = [&](int st0, int st1) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            if (MODE == 0) frag_nt_one(0, 0, u, 0);
-            else frag_tn_one(0, 0, u, 0);
+            dma_one(st0, u, k0);
+            dma_one(st1, u, k0 + KB);
         }
-        for (int t = 0; t < total_steps; ++t) {
-            const int cur = t & 1;
-            substep(0, cur, 1, true, cur ^ 1);      // loads of K-step t+1 (out of range past the end)
-            CF_ADVANCE_KSTEP();
-            substep(1, cur, 2, false, 0);
-            substep(0, cur, 3, false, 0);
-            wait_vmcnt<0>();
-            lds_barrier();
-            substep(1, cur ^ 1, 0, false, 0);
+    };
+    // A pair never straddles a segment boundary unless the segment's K is not a multiple of 64;
+    // then the second half reads past Kseg and is zero-filled, and the next pair restarts at
+    // the new segment (see advance below): K-steps are counted per segment in units of 32, and
+    // a segment with an odd count gets one all-zero K-step appended.
+#define CF_ADVANCE_PAIR()            \
+    do {                             \
+        k0 += 2 * KB;                \
+        if (k0 >= Kseg) {            \
+            k0 = 0;                  \
+            ++seg;                   \
+            open_segment(seg);       \
+        }                            \
+    } while (0)
+
+    // number of K-steps of 32 including the zero padding of odd segments
+    const int steps = 2 * ((g.K[0] + 2 * KB - 1) / (2 * KB) + (g.K[1] + 2 * KB - 1) / (2 * KB) +
+                           (g.K[2] + 2 * KB - 1) / (2 * KB));
+    (void)total_steps;
+
+    if (steps > 0) {
+        open_segment(0);
+        issue_pair(0, 1);
+        CF_ADVANCE_PAIR();
+        issue_pair(2, 3);
+        CF_ADVANCE_PAIR();
+        wait_vmcnt<2 * LDH>();          // K-steps 0 and 1 have landed; 2 and 3 may be in flight
+        lds_barrier();
+#pragma unroll
+        for (int u = 0; u < 8; ++u) frag_one(0, 0, u, 0);
+        int st = 0;                     // stage of the current K-step
+        for (int s = 0; s < steps; s += 2) {
+            // ---- even K-step s (stage st): no loads, no barrier: K-step s+1 was published
+            //      together with K-step s at the barrier of the previous pair
+            const int st1 = st + 1 >= NST ? st + 1 - NST : st + 1;
+            substep(0, st, 1, false, 0, 0);
+            substep(1, st1, 0, false, 0, 0);
+            // ---- odd K-step s+1 (stage st1) ----------------------------------------------
+            const int st2 = st1 + 1 >= NST ? st1 + 1 - NST : st1 + 1;
+            const int st3 = st2 + 2 >= NST ? st2 + 2 - NST : st2 + 2;  // (s+4) % 5
+            substep(0, st1, 1, false, 0, 0);
+            wait_vmcnt<0>();            // K-steps s+2, s+3 have landed (nothing else is in flight)
+            lds_barrier();              // ... and every wave is done with stages st and (s+4)%5
+            substep(1, st2, 0, true, st3, st);      // loads of K-steps s+4 -> st3, s+5 -> st
+            CF_ADVANCE_PAIR();
+            st = st2;
         }
+        wait_vmcnt<0>();
     }
-
 #undef CF_ADVANCE_KSTEP
+#undef CF_ADVANCE_PAIR
 
-    // ---- epilogue (same as the small-tile kernel) -----------------------------------------
+    // ---- epilogue: acc -> bf16 -> LDS C tile -> global with 16-byte stores -----------
     lds_barrier();
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -614,17 +649,17 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g) {
 }
 
 template <int MODE>
-static hipError_t launch_k64(const GemmArgs& g, hipStream_t st) {
-    constexpr int smem = 256 * (256 * 2 + 16);      // C tile staging > 2 operand stages of 64 KB
+static hipError_t launch_ring(const GemmArgs& g, hipStream_t st) {
+    constexpr int smem = 5 * 32768;                 // five operand stages; the C tile staging (132 KB) reuses them
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_k64_kernel<MODE>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_ring_kernel<MODE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int grid = ceil_div(g.M, 256) * ceil_div(g.N, 256);
-    gemm_bf16_k64_kernel<MODE><<<grid, 256, smem, st>>>(g);
+    gemm_bf16_ring_kernel<MODE><<<grid, 256, smem, st>>>(g);
     return hipGetLastError();
 }
 
@@ -675,7 +710,7 @@ hipError_t launch_gemm(int dtype, int mode, const GemmSeg* segs, int nseg, void*
     const int64_t big_tiles = (int64_t)ceil_div(M, 256) * ceil_div(N, 256);
     const bool big = big_tiles >= 200;
     // big: 256x256 block, 8 waves (2 per SIMD) of 128x64; small: 128x128 block, 4 waves of 64x64
-    if (big) return mode == 0 ? launch_k64<0>(g, st) : launch_k64<1>(g, st);
+    if (big) return mode == 0 ? launch_ring<0>(g, st) : launch_ring<1>(g, st);
     if (mode == 0) return big ? launch_bf16<0, 2, 4, 4, 2>(g, st) : launch_bf16<0, 2, 2, 2, 2>(g, st);
     return big ? launch_bf16<1, 2, 4, 4, 2>(g, st) : launch_bf16<1, 2, 2, 2, 2>(g, st);
 }

@@ -180,14 +180,23 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ 
     }
 }
 
+// out[c] = sum_b partial[b,c]: a block owns 32 columns, 8 row groups stride through the partials
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_finish_kernel(const float* __restrict__ partial,
                                                             int nblk, int H, T* __restrict__ out) {
-    const int c = blockIdx.x * 256 + threadIdx.x;
-    if (c >= H) return;
+    __shared__ float red[8][33];
+    const int c = blockIdx.x * 32 + (threadIdx.x & 31), rg = threadIdx.x >> 5;
     float s = 0.f;
-    for (int b = 0; b < nblk; ++b) s += partial[(int64_t)b * H + c];
-    out[c] = from_f32<T>(s);
+    if (c < H)
+        for (int b = rg; b < nblk; b += 8) s += partial[(int64_t)b * H + c];
+    red[rg][threadIdx.x & 31] = s;
+    __syncthreads();
+    if (rg == 0 && c < H) {
+        float t = 0.f;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) t += red[r][threadIdx.x];
+        out[c] = from_f32<T>(t);
+    }
 }
 
 // D[j,h] = sum_c da[j,h*d+c] * a[j,h*d+c]   (the FlashAttention-backward row term)
@@ -276,12 +285,12 @@ hipError_t launch_rmsnorm_bwd(int dtype, const void* dh, const void* x, const vo
         rmsnorm_bwd_kernel<float><<<nblk, 256, 0, st>>>((const float*)dh, (const float*)x,
                                                         (const float*)g, idx, (const float*)res,
                                                         n_rows, H, eps, (float*)dx_out, dg_partial);
-        colsum_finish_kernel<float><<<ceil_div(H, 256), 256, 0, st>>>(dg_partial, nblk, H, (float*)dg_out);
+        colsum_finish_kernel<float><<<ceil_div(H, 32), 256, 0, st>>>(dg_partial, nblk, H, (float*)dg_out);
     } else {
         rmsnorm_bwd_kernel<bf16_t><<<nblk, 256, 0, st>>>((const bf16_t*)dh, (const bf16_t*)x,
                                                          (const bf16_t*)g, idx, (const bf16_t*)res,
                                                          n_rows, H, eps, (bf16_t*)dx_out, dg_partial);
-        colsum_finish_kernel<bf16_t><<<ceil_div(H, 256), 256, 0, st>>>(dg_partial, nblk, H, (bf16_t*)dg_out);
+        colsum_finish_kernel<bf16_t><<<ceil_div(H, 32), 256, 0, st>>>(dg_partial, nblk, H, (bf16_t*)dg_out);
     }
     return hipGetLastError();
 }
