@@ -1,0 +1,69 @@
+"""GPU parity at the full sizes of the benchmark contract, in the launch
+configuration bench.py times (LayerBackward plan, bf16, filtered call), against
+the CPU oracle run in fp32 on the same bf16-rounded inputs.  Configs: 1
+(TinyLlama shape, top-k mask), 2 (3B shape at keep ratio 0.7: a kept count
+that is no tile multiple), 3 (8B shape, span mask: the bench workload) and 4
+(40B-class shape, ragged keep fractions)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import layer_oracle as O
+from paper_2502_00340_amd import binding as Bn
+from paper_2502_00340_amd import workloads as WL
+from tests import harness as Hn
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _run(index, rho=None):
+    shape = WL.CONFIGS[index]
+    print("[case] full size config %d %s rho=%s" % (index, shape.name, rho), flush=True)
+    p = Hn.Problem(shape, WL.config_seed(index), "independent", rho=rho, oracle_dtype=np.float32)
+    sv, W, dy, mask = p.device_tensors(DEV)
+    plan = Bn.LayerBackward(p.desc(), device=DEV)
+    n = plan.filtered(sv, W, dy, mask)
+    torch.cuda.synchronize()
+    ridx = np.flatnonzero(p.mask.reshape(-1))
+    assert n == len(ridx)
+    assert np.array_equal(plan.idx[:n].cpu().numpy(), ridx)
+    assert np.array_equal(plan.cu_kept.cpu().numpy(),
+                          np.concatenate([[0], np.cumsum(p.mask.sum(axis=1))]).astype(np.int32))
+    got = dict(plan.grads)
+    got["dx"] = got["dx"][:n]
+    print("[case]   GPU done (n_kept=%d), running the oracle" % n, flush=True)
+    ref = p.oracle()
+    errs = Hn.check_layer(p, got, ref, ridx, Hn.TOL["bf16"])
+    print("[case]   " + " ".join("%s=%.1e" % kv for kv in errs.items()), flush=True)
+    # second call on the same plan (warm workspace) gives bit-identical results
+    keep = {k: v.clone() for k, v in got.items()}
+    n2 = plan.filtered(sv, W, dy, mask)
+    torch.cuda.synchronize()
+    assert n2 == n
+    for k in keep:
+        cur = plan.grads[k][:n] if k == "dx" else plan.grads[k]
+        assert torch.equal(cur, keep[k]), k
+    return plan, p, sv, W, dy
+
+
+def test_config1_tinyllama_full():
+    _run(1)
+
+
+def test_config2_llama3b_ratio07():
+    _run(2, rho=0.7)
+
+
+def test_config3_llama8b_spans_and_dense():
+    plan, p, sv, W, dy = _run(3)
+    # the dense call of the same library at the same size (the speedup denominator)
+    plan.dense(sv, W, dy)
+    torch.cuda.synchronize()
+    print("[case]   dense GPU done, running the dense oracle", flush=True)
+    ref = p.oracle(dense=True)
+    Hn.check_layer(p, dict(plan.grads), ref, None, Hn.TOL["bf16"])
+
+
+def test_config4_40b_ragged():
+    _run(4)
