@@ -152,7 +152,7 @@ def roofline_leg(shape: WL.LayerShape, n_k: int, reps: int = 20):
             traffic = None
     return {"bound": "mfma", "achieved": round(ach, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
             "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
-            "kernel": "cf::gemm_bf16_ring_kernel<1> (TN): dW[F,H] = X_kept^T dY_kept",
+            "kernel": "cf::gemm_bf16_kernel<1> (TN): dW[F,H] = X_kept^T dY_kept",
             "flops_per_launch": flops, "avg_launch_ms": round(avg, 4), "launches": reps}
 
 
