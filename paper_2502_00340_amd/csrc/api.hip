@@ -94,7 +94,7 @@ struct Carver {
 struct LayerWs {
     void* index_ws;
     int32_t *idx, *cu_kept, *n_kept_dev;
-    void *dy_k, *bufF0, *bufF1, *bufHa, *bufHb, *dr, *a_k, *da, *q_k, *dq, *dk, *dv;
+    void *dy_k, *bufF0, *bufF1, *bufF2, *bufHa, *bufHb, *dr, *a_k, *da, *q_k, *dq, *dk, *dv;
     void* attn_ws;
     float* dg_partial;
     size_t total;
@@ -114,6 +114,7 @@ LayerWs carve_layer(const cf_layer_desc& L, int max_kept, void* ws) {
     w.dy_k = c.take(N * L.H * e);
     w.bufF0 = c.take(N * L.F * e);
     w.bufF1 = c.take(N * L.F * e);
+    w.bufF2 = c.take(N * L.F * e);
     w.bufHa = c.take(N * L.H * e);
     w.bufHb = c.take(N * L.H * e);
     w.dr = c.take(N * L.H * e);
@@ -174,20 +175,21 @@ cf_status layer_core(const cf_layer_desc& L, const cf_saved& sv, const cf_weight
     }
 
     // ---- SwiGLU FFN: y = r + act*Wd --------------------------------------------
-    void* act = w.bufF0;
+    // d_act = dy * Wd^T first; one pass over it then yields d_gate, d_up and act (the SwiGLU
+    // product, rebuilt for dWd), so gate and up are read once
     void* d_act = w.bufF1;
-    CF_HIP(launch_swiglu_fwd(dt, sv.gate, sv.up, idx, N, F, act, st));
-    {   // d_act = dy * Wd^T          [N,F] = [N,H] x [F,H]^T
+    {   // [N,F] = [N,H] x [F,H]^T
         GemmSeg s{dy_rows, W.wd, H};
         CF_HIP(launch_gemm(dt, 0, &s, 1, d_act, N, F, 0.f, st));
     }
+    void* d_gate = w.bufF1;   // in place over d_act
+    void* d_up = w.bufF0;
+    void* act = w.bufF2;
+    CF_HIP(launch_swiglu_bwd(dt, d_act, sv.gate, sv.up, idx, N, F, d_gate, d_up, act, st));
     {   // dWd = act^T * dy           [F,H]
         GemmSeg s{act, dy_rows, N};
         CF_HIP(launch_gemm(dt, 1, &s, 1, G.dwd, F, H, 0.f, st));
     }
-    void* d_gate = w.bufF1;   // in place over d_act
-    void* d_up = w.bufF0;     // act is dead after dWd
-    CF_HIP(launch_swiglu_bwd(dt, d_act, sv.gate, sv.up, idx, N, F, d_gate, d_up, st));
 
     void* h2 = w.bufHa;
     CF_HIP(launch_rmsnorm_fwd(dt, sv.r, W.g2, idx, N, H, L.rms_eps, h2, st));

@@ -92,11 +92,10 @@ hipError_t launch_gather(const void* src, int64_t cols_bytes, const int32_t* idx
                          void* dst, hipStream_t st);
 
 // rowlocal.hip
-hipError_t launch_swiglu_fwd(int dtype, const void* gate, const void* up, const int32_t* idx,
-                             int n_rows, int F, void* act, hipStream_t st);
+// act (nullable) also receives silu(gate)*up; d_gate may alias d_act
 hipError_t launch_swiglu_bwd(int dtype, const void* d_act, const void* gate, const void* up,
                              const int32_t* idx, int n_rows, int F, void* d_gate, void* d_up,
-                             hipStream_t st);
+                             void* act, hipStream_t st);
 hipError_t launch_rmsnorm_fwd(int dtype, const void* x, const void* g, const int32_t* idx,
                               int n_rows, int H, float eps, void* h, hipStream_t st);
 // dx_out = res + rmsnorm_bwd(dh; x, g); dg_partial is [rmsnorm_bwd_blocks(n_rows), H] fp32 scratch

@@ -9,36 +9,16 @@ namespace cf {
 
 __device__ __forceinline__ float sigmoidf_(float z) { return 1.0f / (1.0f + __expf(-z)); }
 
-// act[j,:] = silu(gate[row,:]) * up[row,:],   row = idx ? idx[j] : j
+// d_gate = d_act * up * s(1 + gate(1-s)), d_up = d_act * gate * s,  s = sigmoid(gate);
+// act (nullable) = gate * s * up, the SwiGLU product rebuilt in the same pass.
+// d_gate may alias d_act (every element is read before it is written, by the same thread).
 template <typename T>
-__global__ __launch_bounds__(256) void swiglu_fwd_kernel(const T* __restrict__ gate,
-                                                         const T* __restrict__ up,
-                                                         const int32_t* __restrict__ idx,
-                                                         int n_rows, int F, T* __restrict__ act) {
-    constexpr int VN = Vec<T>::N;
-    const int vpr = F / VN;
-    const int64_t total = (int64_t)n_rows * vpr;
-    for (int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x; v < total; v += (int64_t)gridDim.x * 256) {
-        const int j = (int)(v / vpr);
-        const int c = (int)(v % vpr) * VN;
-        const int64_t row = idx ? idx[j] : j;
-        float g[VN], u[VN], a[VN];
-        Vec<T>::load(gate + row * F + c, g);
-        Vec<T>::load(up + row * F + c, u);
-#pragma unroll
-        for (int e = 0; e < VN; ++e) a[e] = g[e] * sigmoidf_(g[e]) * u[e];
-        Vec<T>::store(act + (int64_t)j * F + c, a);
-    }
-}
-
-// d_gate = d_act * up * s(1 + gate(1-s)), d_up = d_act * gate * s,  s = sigmoid(gate)
-template <typename T>
-__global__ __launch_bounds__(256) void swiglu_bwd_kernel(const T* __restrict__ d_act,
+__global__ __launch_bounds__(256) void swiglu_bwd_kernel(const T* d_act,
                                                          const T* __restrict__ gate,
                                                          const T* __restrict__ up,
                                                          const int32_t* __restrict__ idx,
-                                                         int n_rows, int F, T* __restrict__ d_gate,
-                                                         T* __restrict__ d_up) {
+                                                         int n_rows, int F, T* d_gate,
+                                                         T* __restrict__ d_up, T* __restrict__ act) {
     constexpr int VN = Vec<T>::N;
     const int vpr = F / VN;
     const int64_t total = (int64_t)n_rows * vpr;
@@ -46,7 +26,7 @@ __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const T* __restrict__ d
         const int j = (int)(v / vpr);
         const int c = (int)(v % vpr) * VN;
         const int64_t row = idx ? idx[j] : j;
-        float g[VN], u[VN], da[VN], dg[VN], du[VN];
+        float g[VN], u[VN], da[VN], dg[VN], du[VN], a[VN];
         Vec<T>::load(gate + row * F + c, g);
         Vec<T>::load(up + row * F + c, u);
         Vec<T>::load(d_act + (int64_t)j * F + c, da);
@@ -55,9 +35,11 @@ __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const T* __restrict__ d
             const float s = sigmoidf_(g[e]);
             dg[e] = da[e] * u[e] * s * (1.0f + g[e] * (1.0f - s));
             du[e] = da[e] * g[e] * s;
+            a[e] = g[e] * s * u[e];
         }
         Vec<T>::store(d_gate + (int64_t)j * F + c, dg);
         Vec<T>::store(d_up + (int64_t)j * F + c, du);
+        if (act) Vec<T>::store(act + (int64_t)j * F + c, a);
     }
 }
 
@@ -115,7 +97,10 @@ __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const T* __restrict__ 
 
 // dx_out[j,:] = res[j,:] + rstd*(u - n*mean(u*n)),  n = x*rstd, u = dh*g
 // dg_partial[block,:] = sum over the block's rows of dh*n
-template <typename T>
+// A block owns one row at a time, NV 16-byte vectors per thread, and works on two rows per
+// iteration so that the loads of the second row overlap the reduction of the first; every
+// load of an iteration (x, dh, res of both rows) is issued before the first reduction.
+template <typename T, int NV>
 __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ dh,
                                                           const T* __restrict__ x,
                                                           const T* __restrict__ g,
@@ -124,54 +109,80 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ 
                                                           int H, float eps, T* __restrict__ dx_out,
                                                           float* __restrict__ dg_partial) {
     constexpr int VN = Vec<T>::N;
-    __shared__ float red[8];
+    __shared__ float red[16];
     const int vpr = H / VN;
-    float gv[RMS_MAX_VEC][VN], dgacc[RMS_MAX_VEC][VN];
+    float gv[NV][VN], dgacc[NV][VN];
 #pragma unroll
-    for (int i = 0; i < RMS_MAX_VEC; ++i) {
+    for (int i = 0; i < NV; ++i) {
         const int v = threadIdx.x + i * 256;
 #pragma unroll
         for (int e = 0; e < VN; ++e) { dgacc[i][e] = 0.f; gv[i][e] = 0.f; }
         if (v < vpr) Vec<T>::load(g + v * VN, gv[i]);
     }
-    for (int j = blockIdx.x; j < n_rows; j += gridDim.x) {
-        const int64_t row = idx ? idx[j] : j;
-        float xv[RMS_MAX_VEC][VN], dv[RMS_MAX_VEC][VN];
-        float ss = 0.f, sd = 0.f;
+    const int wave = threadIdx.x >> 6;
+    for (int j0 = blockIdx.x * 2; j0 < n_rows; j0 += gridDim.x * 2) {
+        float xv[2][NV][VN], dv[2][NV][VN], rv[2][NV][VN];
+        float ss[2] = {0.f, 0.f}, sd[2] = {0.f, 0.f};
 #pragma unroll
-        for (int i = 0; i < RMS_MAX_VEC; ++i) {
-            const int v = threadIdx.x + i * 256;
-            if (v < vpr) {
-                Vec<T>::load(x + row * H + v * VN, xv[i]);
-                Vec<T>::load(dh + (int64_t)j * H + v * VN, dv[i]);
+        for (int r = 0; r < 2; ++r) {
+            const int j = j0 + r;
+            const bool live = j < n_rows;
+            const int64_t row = live ? (idx ? idx[j] : j) : 0;
 #pragma unroll
-                for (int e = 0; e < VN; ++e) {
-                    ss += xv[i][e] * xv[i][e];
-                    sd += dv[i][e] * gv[i][e] * xv[i][e];
+            for (int i = 0; i < NV; ++i) {
+                const int v = threadIdx.x + i * 256;
+                if (live && v < vpr) {
+                    Vec<T>::load(x + row * H + v * VN, xv[r][i]);
+                    Vec<T>::load(dh + (int64_t)j * H + v * VN, dv[r][i]);
+                    Vec<T>::load(res + (int64_t)j * H + v * VN, rv[r][i]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < VN; ++e) { xv[r][i][e] = 0.f; dv[r][i][e] = 0.f; rv[r][i][e] = 0.f; }
                 }
             }
         }
-        block_sum2(ss, sd, red);
-        const float rstd = rsqrtf(ss / (float)H + eps);
-        const float c = sd * rstd / (float)H;          // mean(u*n)
 #pragma unroll
-        for (int i = 0; i < RMS_MAX_VEC; ++i) {
-            const int v = threadIdx.x + i * 256;
-            if (v < vpr) {
-                float rv[VN], o[VN];
-                Vec<T>::load(res + (int64_t)j * H + v * VN, rv);
+        for (int r = 0; r < 2; ++r)
+#pragma unroll
+            for (int i = 0; i < NV; ++i)
 #pragma unroll
                 for (int e = 0; e < VN; ++e) {
-                    const float n = xv[i][e] * rstd;
-                    o[e] = rv[e] + rstd * (dv[i][e] * gv[i][e] - n * c);
-                    dgacc[i][e] += dv[i][e] * n;
+                    ss[r] += xv[r][i][e] * xv[r][i][e];
+                    sd[r] += dv[r][i][e] * gv[i][e] * xv[r][i][e];
                 }
-                Vec<T>::store(dx_out + (int64_t)j * H + v * VN, o);
+#pragma unroll
+        for (int r = 0; r < 2; ++r) { ss[r] = wave_sum(ss[r]); sd[r] = wave_sum(sd[r]); }
+        __syncthreads();
+        if ((threadIdx.x & 63) == 0) {
+            red[wave] = ss[0]; red[4 + wave] = sd[0]; red[8 + wave] = ss[1]; red[12 + wave] = sd[1];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int j = j0 + r;
+            if (j >= n_rows) break;
+            const float ssr = red[8 * r] + red[8 * r + 1] + red[8 * r + 2] + red[8 * r + 3];
+            const float sdr = red[8 * r + 4] + red[8 * r + 5] + red[8 * r + 6] + red[8 * r + 7];
+            const float rstd = rsqrtf(ssr / (float)H + eps);
+            const float c = sdr * rstd / (float)H;          // mean(u*n)
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                const int v = threadIdx.x + i * 256;
+                if (v < vpr) {
+                    float o[VN];
+#pragma unroll
+                    for (int e = 0; e < VN; ++e) {
+                        const float n = xv[r][i][e] * rstd;
+                        o[e] = rv[r][i][e] + rstd * (dv[r][i][e] * gv[i][e] - n * c);
+                        dgacc[i][e] += dv[r][i][e] * n;
+                    }
+                    Vec<T>::store(dx_out + (int64_t)j * H + v * VN, o);
+                }
             }
         }
     }
 #pragma unroll
-    for (int i = 0; i < RMS_MAX_VEC; ++i) {
+    for (int i = 0; i < NV; ++i) {
         const int v = threadIdx.x + i * 256;
         if (v < vpr) {
 #pragma unroll
@@ -231,30 +242,18 @@ static int stream_grid(int64_t vec_total) {
     return (int)g;
 }
 
-hipError_t launch_swiglu_fwd(int dtype, const void* gate, const void* up, const int32_t* idx,
-                             int n_rows, int F, void* act, hipStream_t st) {
-    if (n_rows <= 0) return hipSuccess;
-    if (dtype == CF_F32)
-        swiglu_fwd_kernel<float><<<stream_grid((int64_t)n_rows * F / 4), 256, 0, st>>>(
-            (const float*)gate, (const float*)up, idx, n_rows, F, (float*)act);
-    else
-        swiglu_fwd_kernel<bf16_t><<<stream_grid((int64_t)n_rows * F / 8), 256, 0, st>>>(
-            (const bf16_t*)gate, (const bf16_t*)up, idx, n_rows, F, (bf16_t*)act);
-    return hipGetLastError();
-}
-
 hipError_t launch_swiglu_bwd(int dtype, const void* d_act, const void* gate, const void* up,
                              const int32_t* idx, int n_rows, int F, void* d_gate, void* d_up,
-                             hipStream_t st) {
+                             void* act, hipStream_t st) {
     if (n_rows <= 0) return hipSuccess;
     if (dtype == CF_F32)
         swiglu_bwd_kernel<float><<<stream_grid((int64_t)n_rows * F / 4), 256, 0, st>>>(
             (const float*)d_act, (const float*)gate, (const float*)up, idx, n_rows, F,
-            (float*)d_gate, (float*)d_up);
+            (float*)d_gate, (float*)d_up, (float*)act);
     else
         swiglu_bwd_kernel<bf16_t><<<stream_grid((int64_t)n_rows * F / 8), 256, 0, st>>>(
             (const bf16_t*)d_act, (const bf16_t*)gate, (const bf16_t*)up, idx, n_rows, F,
-            (bf16_t*)d_gate, (bf16_t*)d_up);
+            (bf16_t*)d_gate, (bf16_t*)d_up, (bf16_t*)act);
     return hipGetLastError();
 }
 
@@ -273,7 +272,22 @@ hipError_t launch_rmsnorm_fwd(int dtype, const void* x, const void* g, const int
 
 int rmsnorm_bwd_blocks(int n_rows) {
     if (n_rows < 1) return 1;
-    return n_rows < 512 ? n_rows : 512;
+    const int pairs = (n_rows + 1) / 2;             // a block takes two rows per iteration
+    return pairs < 512 ? pairs : 512;
+}
+
+template <typename T>
+static void rmsnorm_bwd_dispatch(int nv, int nblk, hipStream_t st, const void* dh, const void* x, const void* g,
+                                 const int32_t* idx, const void* res, int n_rows, int H, float eps,
+                                 void* dx_out, float* dg_partial) {
+#define CF_RMS_BWD(NV)                                                                               \
+    rmsnorm_bwd_kernel<T, NV><<<nblk, 256, 0, st>>>((const T*)dh, (const T*)x, (const T*)g, idx,      \
+                                                    (const T*)res, n_rows, H, eps, (T*)dx_out, dg_partial)
+    if (nv <= 1) CF_RMS_BWD(1);
+    else if (nv <= 2) CF_RMS_BWD(2);
+    else if (nv <= 4) CF_RMS_BWD(4);
+    else CF_RMS_BWD(8);
+#undef CF_RMS_BWD
 }
 
 hipError_t launch_rmsnorm_bwd(int dtype, const void* dh, const void* x, const void* g,
@@ -281,15 +295,13 @@ hipError_t launch_rmsnorm_bwd(int dtype, const void* dh, const void* x, const vo
                               void* dx_out, float* dg_partial, void* dg_out, hipStream_t st) {
     const int nblk = rmsnorm_bwd_blocks(n_rows);
     if (n_rows <= 0) return launch_fill_zero(dg_out, (size_t)H * dtype_size(dtype), st);
+    const int vn = dtype == CF_F32 ? 4 : 8;
+    const int nv = ceil_div(H / vn, 256);           // 16-byte vectors per thread (<= RMS_MAX_VEC, checked by the API)
     if (dtype == CF_F32) {
-        rmsnorm_bwd_kernel<float><<<nblk, 256, 0, st>>>((const float*)dh, (const float*)x,
-                                                        (const float*)g, idx, (const float*)res,
-                                                        n_rows, H, eps, (float*)dx_out, dg_partial);
+        rmsnorm_bwd_dispatch<float>(nv, nblk, st, dh, x, g, idx, res, n_rows, H, eps, dx_out, dg_partial);
         colsum_finish_kernel<float><<<ceil_div(H, 32), 256, 0, st>>>(dg_partial, nblk, H, (float*)dg_out);
     } else {
-        rmsnorm_bwd_kernel<bf16_t><<<nblk, 256, 0, st>>>((const bf16_t*)dh, (const bf16_t*)x,
-                                                         (const bf16_t*)g, idx, (const bf16_t*)res,
-                                                         n_rows, H, eps, (bf16_t*)dx_out, dg_partial);
+        rmsnorm_bwd_dispatch<bf16_t>(nv, nblk, st, dh, x, g, idx, res, n_rows, H, eps, dx_out, dg_partial);
         colsum_finish_kernel<bf16_t><<<ceil_div(H, 32), 256, 0, st>>>(dg_partial, nblk, H, (bf16_t*)dg_out);
     }
     return hipGetLastError();
