@@ -156,6 +156,65 @@ def roofline_leg(shape: WL.LayerShape, n_k: int, reps: int = 20):
             "flops_per_launch": flops, "avg_launch_ms": round(avg, 4), "launches": reps}
 
 
+def parts_leg(shape: WL.LayerShape, sv, W, dy, mask: np.ndarray, mask_dev, reps: int = 10):
+    """Per-part timings through the single-purpose entry points (HIP events, mean of `reps`
+    calls), plus scaled-up runs of the index build and the row gather: at T = 8192 those two
+    are launch-latency bound and say nothing about bandwidth."""
+    out = {}
+    n_k = int(mask.sum())
+    T, H, F, Nq, Nkv = shape.T, shape.H, shape.F, shape.Nq, shape.Nkv
+    mean = lambda fn: float(np.mean(event_times(fn, reps)))
+    # A1 keep index (no host copy: sync=False)
+    ms = mean(lambda: Bn.build_keep_index(mask_dev, sync=False))
+    out["A1_keep_index"] = {"ms": round(ms, 4), "tokens": T}
+    big = torch.from_numpy((np.random.default_rng(1).random((4096, 4096)) < 0.5).astype(np.uint8)).to(DEV)
+    ms = mean(lambda: Bn.build_keep_index(big, sync=False))
+    nb = int(big.sum().item())
+    out["A1_keep_index_16M_tokens"] = {"ms": round(ms, 4), "GBps": round((big.numel() + 4 * nb) / ms / 1e6, 1),
+                                       "bound": "hbm", "frac_of_8TBps": round((big.numel() + 4 * nb) / ms / 1e6 / 8000, 4)}
+    del big
+    # A2 gather
+    idx, cu, _, _ = Bn.build_keep_index(mask_dev)
+    dst = torch.empty((n_k, H), dtype=dy.dtype, device=DEV)
+    ms = mean(lambda: Bn.gather_rows(dy, idx, n_k, out=dst))
+    out["A2_gather_dy"] = {"ms": round(ms, 4), "GBps": round(2.0 * n_k * H * 2 / ms / 1e6, 1)}
+    src = torch.empty((131072, 4096), dtype=torch.bfloat16, device=DEV)      # 1 GiB
+    src.normal_()
+    bm = torch.from_numpy((np.random.default_rng(2).random((1, 131072)) < 0.5).astype(np.uint8)).to(DEV)
+    bidx, _, _, bn = Bn.build_keep_index(bm)
+    bdst = torch.empty((bn, 4096), dtype=torch.bfloat16, device=DEV)
+    ms = mean(lambda: Bn.gather_rows(src, bidx, bn, out=bdst))
+    gb = 2.0 * bn * 4096 * 2 / ms / 1e6
+    out["A2_gather_1GiB_source"] = {"ms": round(ms, 4), "GBps": round(gb, 1), "bound": "hbm",
+                                    "frac_of_8TBps": round(gb / 8000, 4)}
+    del src, bdst
+    # A3 reduced linear backward at the FFN shape
+    xk = torch.randn((n_k, F), device=DEV).to(dy.dtype)
+    dyk = torch.randn((n_k, H), device=DEV).to(dy.dtype)
+    lib = Bn.lib()
+    import ctypes as C
+    dxo = torch.empty((n_k, F), dtype=dy.dtype, device=DEV)
+    dwo = torch.empty((F, H), dtype=dy.dtype, device=DEV)
+    vp = lambda t: C.c_void_p(t.data_ptr())
+    st = lambda: C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    fl = 2.0 * n_k * F * H
+    ms = mean(lambda: lib.cf_linear_bwd_reduced(None, vp(dyk), vp(W["wd"]), n_k, F, H, Bn.CF_BF16, vp(dxo), None, 0.0, st()))
+    out["A3_dx_ffn"] = {"ms": round(ms, 4), "TFLOPs": round(fl / ms / 1e9, 1), "frac_of_peak": round(fl / ms / 1e9 / PEAK_BF16_TFLOPS, 4)}
+    ms = mean(lambda: lib.cf_linear_bwd_reduced(vp(xk), vp(dyk), None, n_k, F, H, Bn.CF_BF16, None, vp(dwo), 0.0, st()))
+    out["A3_dw_ffn"] = {"ms": round(ms, 4), "TFLOPs": round(fl / ms / 1e9, 1), "frac_of_peak": round(fl / ms / 1e9 / PEAK_BF16_TFLOPS, 4)}
+    del xk, dxo, dwo
+    # A5 filtered attention backward
+    desc = Bn.make_desc(shape.B, shape.S, H, shape.Hq, shape.Hkv, shape.d, F, shape.dtype)
+    qk = Bn.gather_rows(sv["q"], idx, n_k)
+    ok = Bn.gather_rows(sv["attn_out"], idx, n_k)
+    dok = torch.randn((n_k, Nq), device=DEV).to(dy.dtype)
+    ms = mean(lambda: Bn.attn_bwd_filtered(desc, qk, sv["k"], sv["v"], ok, sv["lse"], dok, idx, cu, n_k))
+    fa = attn_alg_flops(shape, mask)
+    out["A5_attn_bwd_filtered"] = {"ms": round(ms, 4), "algorithmic_TFLOPs": round(fa / ms / 1e9, 1),
+                                   "frac_of_peak": round(fa / ms / 1e9 / PEAK_BF16_TFLOPS, 4)}
+    return out
+
+
 def cpu_baseline_leg(shape: WL.LayerShape, W, sv, dy, mask):
     """The CPU oracle (fp32 arrays, numpy) on the same workload (the whole batch
     is a bounded sample already: about ten seconds of host time)."""
@@ -185,6 +244,7 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="index into the workload table (default: 8B shape)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the keep-ratio sweep")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--no-parts", action="store_true", help="skip the per-part timings")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU only (collectives and sharding are out of scope); "
@@ -231,6 +291,10 @@ def main():
     torch.cuda.synchronize()
     del calib, calib2
 
+    parts = None
+    if not a.no_parts:
+        log("per-part timings")
+        parts = parts_leg(shape, sv, W, dy, mask, mask_dev)
     log("roofline leg")
     roof = roofline_leg(shape, n_k)
     cpu = None
@@ -255,6 +319,7 @@ def main():
         "algorithmic_tflops": round(tfl, 1), "mfma_frac_of_peak_layer": round(tfl / PEAK_BF16_TFLOPS, 4),
         "dense_algorithmic_tflops": round(flops_d / t_d / 1e12, 1),
         "keep_ratio_sweep": sweep,
+        "parts": parts,
         "roofline": roof,
         "cpu_baseline": cpu,
     }

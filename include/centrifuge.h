@@ -162,13 +162,24 @@ cf_status cf_attn_bwd_filtered(const cf_layer_desc* desc, const void* q_kept, co
  * once, right after the index build, to size the remaining launches.
  * cf_layer_bwd_dense: the same kernels with every token kept and no index or
  * gather; dx is [T,H].
+ * cf_layer_bwd_compact: a layer BELOW the one whose call built the keep index
+ * (Sec. 3.2: once the first gradient is reduced, every later gradient is; Sec. 3.1:
+ * the sparsity is handed on to all front layers).  dy_kept [n_kept,H] is the compact
+ * dx of the layer above; idx [n_kept] and cu_kept [B+1] (device) are the index that
+ * call returned and n_kept its N_k.  Saved activations are still full length.
+ * Outputs as for the filtered call.  Nothing is copied to the host and the stream is
+ * not synchronised, so a stack of layers costs one synchronisation in total.
  * ws must hold cf_layer_workspace_bytes(desc, max_kept) bytes; max_kept = T is
- * always sufficient. */
+ * always sufficient (for the compact call: max_kept >= n_kept). */
 size_t cf_layer_workspace_bytes(const cf_layer_desc* desc, int32_t max_kept);
 cf_status cf_layer_bwd_filtered(const cf_layer_desc* desc, const cf_saved* saved,
                                 const cf_weights* w, const void* dy_full, const uint8_t* mask,
                                 cf_grads* grads, int32_t* idx_out, int32_t* cu_kept_out,
                                 int32_t* n_kept_host, void* ws, size_t ws_bytes, cf_stream stream);
+cf_status cf_layer_bwd_compact(const cf_layer_desc* desc, const cf_saved* saved,
+                               const cf_weights* w, const void* dy_kept, const int32_t* idx,
+                               const int32_t* cu_kept, int32_t n_kept, cf_grads* grads,
+                               void* ws, size_t ws_bytes, cf_stream stream);
 cf_status cf_layer_bwd_dense(const cf_layer_desc* desc, const cf_saved* saved,
                              const cf_weights* w, const void* dy_full, cf_grads* grads,
                              void* ws, size_t ws_bytes, cf_stream stream);

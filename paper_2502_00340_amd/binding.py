@@ -22,7 +22,7 @@ _STATUS = {0: "CF_OK", 1: "CF_ERR_NULL", 2: "CF_ERR_SHAPE", 3: "CF_ERR_DTYPE", 4
 EXPORTS = (
     "cf_status_str", "cf_version", "cf_index_workspace_bytes", "cf_build_keep_index", "cf_gather_rows",
     "cf_linear_bwd_reduced", "cf_attn_workspace_bytes", "cf_attn_bwd_filtered",
-    "cf_layer_workspace_bytes", "cf_layer_bwd_filtered", "cf_layer_bwd_dense",
+    "cf_layer_workspace_bytes", "cf_layer_bwd_filtered", "cf_layer_bwd_compact", "cf_layer_bwd_dense",
 )
 
 
@@ -84,6 +84,9 @@ def lib() -> C.CDLL:
     L.cf_layer_bwd_filtered.restype = C.c_int
     L.cf_layer_bwd_filtered.argtypes = [C.POINTER(LayerDesc), C.POINTER(Saved), C.POINTER(Weights), vp, vp,
                                         C.POINTER(Grads), vp, vp, C.POINTER(i32), vp, sz, vp]
+    L.cf_layer_bwd_compact.restype = C.c_int
+    L.cf_layer_bwd_compact.argtypes = [C.POINTER(LayerDesc), C.POINTER(Saved), C.POINTER(Weights), vp, vp, vp,
+                                       i32, C.POINTER(Grads), vp, sz, vp]
     L.cf_layer_bwd_dense.restype = C.c_int
     L.cf_layer_bwd_dense.argtypes = [C.POINTER(LayerDesc), C.POINTER(Saved), C.POINTER(Weights), vp,
                                      C.POINTER(Grads), vp, sz, vp]
@@ -241,6 +244,16 @@ class LayerBackward:
                                            C.byref(n_host), _ptr(self.ws), self.ws_bytes, _stream()),
                "cf_layer_bwd_filtered")
         return int(n_host.value)
+
+    def compact(self, saved: dict, weights: dict, dy_kept: torch.Tensor, idx: torch.Tensor,
+                cu_kept: torch.Tensor, n_kept: int) -> None:
+        """Runs cf_layer_bwd_compact for a layer below the one that built (idx, cu_kept); results
+        land in self.grads (dx: first n_kept rows).  No host synchronisation."""
+        sv, w = self._pack(saved, weights)
+        _check(lib().cf_layer_bwd_compact(C.byref(self.desc), C.byref(sv), C.byref(w), _ptr(dy_kept), _ptr(idx),
+                                          _ptr(cu_kept), n_kept, C.byref(self._g), _ptr(self.ws),
+                                          self.ws_bytes, _stream()),
+               "cf_layer_bwd_compact")
 
     def dense(self, saved: dict, weights: dict, dy: torch.Tensor) -> None:
         sv, w = self._pack(saved, weights)

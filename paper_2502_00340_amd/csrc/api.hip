@@ -401,6 +401,24 @@ cf_status cf_layer_bwd_filtered(const cf_layer_desc* desc, const cf_saved* saved
     return layer_core(*desc, *saved, *w, wk.dy_k, idx, cu, N, *grads, wk, st);
 }
 
+cf_status cf_layer_bwd_compact(const cf_layer_desc* desc, const cf_saved* saved, const cf_weights* w,
+                               const void* dy_kept, const int32_t* idx, const int32_t* cu_kept,
+                               int32_t n_kept, cf_grads* grads, void* ws, size_t ws_bytes,
+                               cf_stream stream) {
+    cf_status s = check_layer_desc(desc);
+    if (s != CF_OK) return s;
+    s = check_layer_ptrs(saved, w, dy_kept, grads);
+    if (s != CF_OK) return s;
+    if (!idx || !cu_kept) return CF_ERR_NULL;
+    if (misaligned(idx, 4) || misaligned(cu_kept, 4)) return CF_ERR_SHAPE;
+    const int T = desc->B * desc->S;
+    if (n_kept < 0 || n_kept > T) return CF_ERR_SHAPE;
+    if (!ws || misaligned(ws, 256)) return CF_ERR_WORKSPACE;
+    LayerWs wk = carve_layer(*desc, n_kept, ws);
+    if (ws_bytes < wk.total) return CF_ERR_WORKSPACE;
+    return layer_core(*desc, *saved, *w, dy_kept, idx, cu_kept, n_kept, *grads, wk, as_stream(stream));
+}
+
 cf_status cf_layer_bwd_dense(const cf_layer_desc* desc, const cf_saved* saved, const cf_weights* w,
                              const void* dy_full, cf_grads* grads, void* ws, size_t ws_bytes,
                              cf_stream stream) {

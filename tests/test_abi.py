@@ -118,6 +118,12 @@ def test_layer_argument_errors(L):
     assert f(C.byref(d), C.byref(sv_bad), C.byref(w), FAKE, FAKE, C.byref(g), None, None, C.byref(n), FAKE, ok_ws, None) == 1
     assert f(C.byref(d), C.byref(sv), C.byref(w), FAKE, FAKE, C.byref(g), None, None, C.byref(n), FAKE, 16, None) == 4
     assert f(C.byref(_desc(H=250)), C.byref(sv), C.byref(w), FAKE, FAKE, C.byref(g), None, None, C.byref(n), FAKE, ok_ws, None) == 2
+    fc = L.cf_layer_bwd_compact
+    assert fc(C.byref(d), C.byref(sv), C.byref(w), FAKE, None, FAKE, 4, C.byref(g), FAKE, ok_ws, None) == 1
+    assert fc(C.byref(d), C.byref(sv), C.byref(w), None, FAKE, FAKE, 4, C.byref(g), FAKE, ok_ws, None) == 1
+    assert fc(C.byref(d), C.byref(sv), C.byref(w), FAKE, FAKE, FAKE, 257, C.byref(g), FAKE, ok_ws, None) == 2   # n_kept > T
+    assert fc(C.byref(d), C.byref(sv), C.byref(w), FAKE, FAKE, FAKE, -1, C.byref(g), FAKE, ok_ws, None) == 2
+    assert fc(C.byref(d), C.byref(sv), C.byref(w), FAKE, FAKE, FAKE, 200, C.byref(g), FAKE, 4096, None) == 4
     fd = L.cf_layer_bwd_dense
     assert fd(C.byref(d), C.byref(sv), C.byref(w), None, C.byref(g), FAKE, ok_ws, None) == 1
     assert fd(C.byref(d), C.byref(sv), C.byref(w), FAKE, C.byref(g), FAKE, ok_ws - 256, None) == 4

@@ -307,3 +307,36 @@ def test_layer_ragged_batch_with_empty_sequence():
     p = Hn.Problem(shape, 9, "independent", mask=mask)
     got, ridx, n = _run_layer(p)
     Hn.check_layer(p, got, p.oracle(), ridx, Hn.TOL["bf16"])
+
+
+def test_layer_stack_of_two_shares_one_index():
+    """Two layers chained: the compact dx of the upper layer is the compact upstream
+    gradient of the lower one, which reuses the index and is not synchronised.  The
+    oracle runs the same chain on full-length tensors (its dx is zero on filtered rows)."""
+    shape = WL.LayerShape("stack", B=2, S=288, H=256, Hq=4, Hkv=2, d=64, F=640, dtype="bf16")
+    say("layer stack of two")
+    top = Hn.Problem(shape, 21, "independent", rho=0.5)
+    low = Hn.Problem(shape, 22, "independent", mask=top.mask)
+    sv2, W2, dy, mask = top.device_tensors(DEV)
+    sv1, W1, _, _ = low.device_tensors(DEV)
+    plan2 = Bn.LayerBackward(top.desc(), device=DEV)
+    plan1 = Bn.LayerBackward(low.desc(), device=DEV)
+    n = plan2.filtered(sv2, W2, dy, mask)
+    plan1.compact(sv1, W1, plan2.grads["dx"][:n], plan2.idx, plan2.cu_kept, n)
+    torch.cuda.synchronize()
+    ref2 = top.oracle()
+    low.dy = np.asarray(ref2["dx"], dtype=np.float64)      # full length, zero on filtered rows
+    ref1 = low.oracle()
+    ridx = np.flatnonzero(top.mask.reshape(-1))
+    got = dict(plan1.grads)
+    got["dx"] = got["dx"][:n]
+    errs = Hn.check_layer(low, got, ref1, ridx, Hn.TOL["bf16"])
+    say("  " + " ".join("%s=%.1e" % kv for kv in errs.items()))
+    # the compact call on the upper layer's own inputs reproduces the filtered call bit for bit
+    keep = {k: v.clone() for k, v in plan2.grads.items()}
+    dyk = Bn.gather_rows(dy, plan2.idx, n)
+    plan2.compact(sv2, W2, dyk, plan2.idx, plan2.cu_kept, n)
+    torch.cuda.synchronize()
+    for k in keep:
+        a, b = (plan2.grads[k][:n], keep[k][:n]) if k == "dx" else (plan2.grads[k], keep[k])
+        assert torch.equal(a, b), k
