@@ -28,7 +28,10 @@
 //   * One LDS barrier per 64 K (four 16-wide sub-steps); the fragments of the next
 //     sub-step are read ahead of the MFMAs of the current one, and the instruction
 //     stream is laid out by hand so that no burst of memory instructions stands
-//     between two MFMAs.
+//     between two MFMAs.  With one wave per SIMD every instruction between two MFMAs
+//     costs MFMA issue time, so the stream is kept lean: a load takes its per-lane
+//     offset from a register that is fixed for the whole K segment, the K position
+//     being the instruction's scalar offset.
 //   * NT stage: [rows][32 k], 64-byte rows, 16-byte chunk index XOR (row/4)%4, which
 //     makes the 16 lanes of a ds_read_b128 hit distinct banks; a lane of the loading
 //     wave picks the global chunk that belongs in its (fixed) LDS slot.
@@ -42,6 +45,8 @@
 //     bf16, stages the whole C tile in LDS (the operand stages are dead by then)
 //     and writes full rows with 16-byte stores.
 // fp32 path (check mode): plain LDS-tiled FMA kernel.
+#include <type_traits>
+
 #include "common.h"
 #include "mfma_util.h"
 
@@ -93,7 +98,6 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
     constexpr int A_BYTES = BM * KB * 2;                // B tile follows the A tile inside a stage
     constexpr int NU = TM + TN;                         // 1 KB wave-loads per wave per K-step: TM for A, TN for B
     constexpr int NQ = TM * TN, NF = TM + TN;           // MFMAs and fragment reads per 16-wide sub-step
-    constexpr unsigned OOB = 0xFFFFFFFFu;
     constexpr int C_PITCH = BN * 2 + 16;
     static_assert(A_BYTES + BN * KB * 2 <= STAGE, "tile shape");
 
@@ -116,6 +120,15 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
     int seg = 0, k0 = 0, Kseg = 0;
     i32x4_t rsA, rsB;
     unsigned ldA = 0, ldB = 0;
+    // Per-lane byte offset of wave-load u at k = 0 of the current segment (out of range for rows /
+    // columns beyond the matrix edge); the K position of a K-step is added as the load's scalar
+    // offset, so the steady-state loop spends no vector instruction on addresses.  v0 / v1 are the
+    // offsets used for the first / second K-step of the pair at (seg, k0): equal to vbase while the
+    // pair lies inside the segment, out of range for the lanes whose k falls past its end.
+    constexpr unsigned OOB_FAST = 0x80000000u;          // stays out of range when the scalar offset is added
+    unsigned vbase[NU], v0[NU], v1[NU];
+    bool pair_inside = false;
+    const unsigned nt_lc = (unsigned)((lane & 3) ^ ((lane >> 4) & 3));
     auto open_segment = [&](int s) __attribute__((always_inline)) {
         const bool live = s < g.nseg;
         const bf16_t* A = static_cast<const bf16_t*>(s == 1 ? g.A[1] : (s == 2 ? g.A[2] : g.A[0]));
@@ -133,6 +146,52 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
             ldA = (unsigned)g.M * 2u;
             ldB = (unsigned)g.N * 2u;
         }
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+            const bool isA = u < TM;
+            const int i = isA ? u : u - TM;
+            if (MODE == 0) {
+                const unsigned row = (4 * i + wave) * 16 + (lane >> 2);
+                vbase[u] = row * (isA ? ldA : ldB) + nt_lc * 16u;
+            } else {
+                const int cpr = (isA ? BM : BN) / 8;
+                const int qq = (4 * i + wave) * 64 + lane;
+                const int kr = qq / cpr;
+                const int c = (qq % cpr) ^ ((kr & 3) << 2);
+                const bool ok = (isA ? m0 : n0) + c * 8 < (isA ? g.M : g.N);
+                vbase[u] = ok ? (unsigned)kr * (isA ? ldA : ldB) + c * 16u : OOB_FAST;
+            }
+        }
+        pair_inside = false;
+    };
+    // offsets and scalar K offsets of the pair at (seg, k0); cheap when this pair and the previous one
+    // lie inside the segment
+    unsigned ka0 = 0, kb0 = 0, ka1 = 0, kb1 = 0;
+    auto prepare_pair = [&]() __attribute__((always_inline)) {
+        const bool inside = k0 + 2 * KB <= Kseg;
+        if (!(inside && pair_inside)) {
+#pragma unroll
+            for (int u = 0; u < NU; ++u) {
+                int kpos;                       // first k of the lane's chunk within a K-step
+                if (MODE == 0) {
+                    kpos = (int)nt_lc * 8;
+                } else {
+                    const bool isA = u < TM;
+                    const int i = isA ? u : u - TM;
+                    kpos = ((4 * i + wave) * 64 + lane) / ((isA ? BM : BN) / 8);
+                }
+                v0[u] = (k0 + kpos < Kseg) ? vbase[u] : OOB_FAST;
+                v1[u] = (k0 + KB + kpos < Kseg) ? vbase[u] : OOB_FAST;
+            }
+        }
+        pair_inside = inside;
+        if (MODE == 0) {
+            ka0 = kb0 = (unsigned)k0 * 2u;
+            ka1 = kb1 = (unsigned)(k0 + KB) * 2u;
+        } else {
+            ka0 = (unsigned)k0 * ldA; kb0 = (unsigned)k0 * ldB;
+            ka1 = (unsigned)(k0 + KB) * ldA; kb1 = (unsigned)(k0 + KB) * ldB;
+        }
     };
     // A pair of K-steps never straddles a segment boundary: a segment with an odd number of
     // K-steps gets one all-zero K-step appended (its loads fall past Kseg).
@@ -146,30 +205,15 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
     };
 
     const unsigned lds0 = __builtin_amdgcn_readfirstlane(lds_addr_of(smem) + wave * 1024);
-    // wave-load u of the K-step at (seg, k0): u < TM -> A tile, else B tile; tile bytes [(4*i + wave) KB, +1 KB)
-    //   NT: 16 rows x 4 chunks; the chunk a lane fetches undoes the XOR swizzle of its LDS slot
-    //   TN: 1024 / (2*rows) k-rows of the tile
-    const unsigned nt_lc = (unsigned)((lane & 3) ^ ((lane >> 4) & 3));
-    auto dma_one = [&](int stage, int u, int kk0) __attribute__((always_inline)) {
+    // wave-load u of K-step `second` (0 / 1) of the pair at (seg, k0): u < TM -> A tile, else B tile; tile
+    // bytes [(4*i + wave) KB, +1 KB).  NT: 16 rows x 4 chunks, the chunk a lane fetches undoes the XOR
+    // swizzle of its LDS slot.  TN: 1024 / (2*rows) k-rows of the tile.
+    auto dma_one = [&](int stage, int u, int second) __attribute__((always_inline)) {
         const bool isA = u < TM;
         const int i = isA ? u : u - TM;
         const unsigned dst = lds0 + stage * STAGE + (isA ? 0 : A_BYTES) + i * 4096;
-        unsigned off;
-        if (MODE == 0) {
-            const unsigned row = (4 * i + wave) * 16 + (lane >> 2);
-            const int kk = kk0 + (int)nt_lc * 8;
-            off = (kk < Kseg) ? row * (isA ? ldA : ldB) + (unsigned)kk * 2u : OOB;
-        } else {
-            constexpr int CPR_A = BM / 8, CPR_B = BN / 8;       // 16-byte chunks per k-row
-            const int cpr = isA ? CPR_A : CPR_B;
-            const int qq = (4 * i + wave) * 64 + lane;
-            const int kr = qq / cpr;
-            const int c = (qq % cpr) ^ ((kr & 3) << 2);
-            const bool ok = ((isA ? m0 : n0) + c * 8 < (isA ? g.M : g.N)) && (kk0 + kr < Kseg);
-            off = ok ? (unsigned)(kk0 + kr) * (isA ? ldA : ldB) + c * 16u : OOB;
-        }
-        if (isA) dma16(dst, rsA, off);
-        else dma16(dst, rsB, off);
+        if (isA) dma16s(dst, rsA, second ? v1[u] : v0[u], second ? ka1 : ka0);
+        else dma16s(dst, rsB, second ? v1[u] : v0[u], second ? kb1 : kb0);
     };
 
     // ---- LDS -> fragments: fragment u < TM is 32-row block u of the wave's A rows, else of its B rows
@@ -206,7 +250,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
     };
     // One 16-wide sub-step: NQ MFMAs on fragment buffer `buf`; spread evenly between them, the NF
     // fragments of (stage ns, sub-step nks) go into the other buffer.  with_dma: also the 2*NU
-    // wave-loads of the next two K-steps (into stages d0, d1), the two halves of each 128-byte
+    // wave-loads of the pair at (seg, k0) (into stages d0, d1), the two halves of each 128-byte
     // line of an NT operand row in adjacent instructions.
     auto substep = [&](int buf, int ns, int nks, bool with_dma, int d0, int d1) __attribute__((always_inline)) {
 #pragma unroll
@@ -214,10 +258,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
             if (with_dma) {
 #pragma unroll
                 for (int e = 0; e < 2 * NU; ++e)
-                    if ((e * NQ) / (2 * NU) == q) {
-                        if ((e & 1) == 0) dma_one(d0, e >> 1, k0);
-                        else dma_one(d1, e >> 1, k0 + KB);
-                    }
+                    if ((e * NQ) / (2 * NU) == q) dma_one((e & 1) ? d1 : d0, e >> 1, e & 1);
             }
 #pragma unroll
             for (int f = 0; f < NF; ++f)
@@ -227,13 +268,31 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
             CF_SCHED_FENCE();
         }
     };
-    // loads of two consecutive K-steps outside the MFMA stream (prologue)
+    // loads of the pair at (seg, k0) outside the MFMA stream (prologue)
     auto issue_pair = [&](int d0, int d1) __attribute__((always_inline)) {
+        prepare_pair();
 #pragma unroll
         for (int u = 0; u < NU; ++u) {
-            dma_one(d0, u, k0);
-            dma_one(d1, u, k0 + KB);
+            dma_one(d0, u, 0);
+            dma_one(d1, u, 1);
         }
+    };
+    // One pair of K-steps s, s+1 in stages st, st+1 (mod 5)
+    auto pair_body = [&](int st) __attribute__((always_inline)) {
+        const int st1 = st + 1 >= NST ? st + 1 - NST : st + 1;
+        const int st2 = st1 + 1 >= NST ? st1 + 1 - NST : st1 + 1;
+        const int st3 = st2 + 2 >= NST ? st2 + 2 - NST : st2 + 2;      // (s+4) % 5
+        // K-step s (stage st): no loads, no barrier: K-step s+1 was published together with
+        // K-step s at the barrier of the previous pair
+        substep(0, st, 1, false, 0, 0);
+        substep(1, st1, 0, false, 0, 0);
+        // K-step s+1 (stage st1)
+        substep(0, st1, 1, false, 0, 0);
+        prepare_pair();
+        wait_vmcnt<0>();            // K-steps s+2, s+3 have landed (nothing else is in flight)
+        lds_barrier();              // ... and every wave is done with stages st and (s+4)%5
+        substep(1, st2, 0, true, st3, st);      // loads of K-steps s+4 -> st3, s+5 -> st
+        advance_pair();
     };
 
     // K-steps of 32 including the zero K-step that pads a segment with an odd count
@@ -251,20 +310,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
         for (int u = 0; u < NF; ++u) frag_one(0, 0, u, 0);
         int st = 0;                     // stage of K-step s
         for (int s = 0; s < steps; s += 2) {
-            // K-step s (stage st): no loads, no barrier: K-step s+1 was published together
-            // with K-step s at the barrier of the previous pair
-            const int st1 = st + 1 >= NST ? st + 1 - NST : st + 1;
-            substep(0, st, 1, false, 0, 0);
-            substep(1, st1, 0, false, 0, 0);
-            // K-step s+1 (stage st1)
-            const int st2 = st1 + 1 >= NST ? st1 + 1 - NST : st1 + 1;
-            const int st3 = st2 + 2 >= NST ? st2 + 2 - NST : st2 + 2;  // (s+4) % 5
-            substep(0, st1, 1, false, 0, 0);
-            wait_vmcnt<0>();            // K-steps s+2, s+3 have landed (nothing else is in flight)
-            lds_barrier();              // ... and every wave is done with stages st and (s+4)%5
-            substep(1, st2, 0, true, st3, st);      // loads of K-steps s+4 -> st3, s+5 -> st
-            advance_pair();
-            st = st2;
+            pair_body(st);
+            st = st + 2 >= NST ? st + 2 - NST : st + 2;
         }
         wait_vmcnt<0>();
     }
@@ -319,24 +366,23 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tiles_m = (g.M + 255) / 256, tiles_n = (g.N + 255) / 256;
     const int pid = blockIdx.x;
-    int bm, bn;
+    int bm, bn, m0, n0, cut = 1;
     if (pid < g.n_full) {
         tile_coords(xcd_order(pid, g.n_full), tiles_m, tiles_n, bm, bn);
-        gemm_tile<MODE, 4, 4>(g, bm * 256, bn * 256, smem);
-        return;
-    }
-    const int j = xcd_order(pid - g.n_full, (int)gridDim.x - g.n_full);
-    const int part = j % g.sub;
-    tile_coords(g.n_full + j / g.sub, tiles_m, tiles_n, bm, bn);
-    if (g.sub == 1) {
-        gemm_tile<MODE, 4, 4>(g, bm * 256, bn * 256, smem);
-    } else if (g.sub == 2) {
-        const int n0 = bn * 256 + part * 128;
-        if (n0 < g.N) gemm_tile<MODE, 4, 2>(g, bm * 256, n0, smem);
+        m0 = bm * 256;
+        n0 = bn * 256;
     } else {
-        const int m0 = bm * 256 + (part >> 1) * 128, n0 = bn * 256 + (part & 1) * 128;
-        if (m0 < g.M && n0 < g.N) gemm_tile<MODE, 2, 2>(g, m0, n0, smem);
+        cut = g.sub;
+        const int j = xcd_order(pid - g.n_full, (int)gridDim.x - g.n_full);
+        const int part = j % cut;
+        tile_coords(g.n_full + j / cut, tiles_m, tiles_n, bm, bn);
+        m0 = bm * 256 + (cut == 4 ? (part >> 1) * 128 : 0);
+        n0 = bn * 256 + (cut == 4 ? (part & 1) * 128 : (cut == 2 ? part * 128 : 0));
+        if (m0 >= g.M || n0 >= g.N) return;
     }
+    if (cut == 1) gemm_tile<MODE, 4, 4>(g, m0, n0, smem);
+    else if (cut == 2) gemm_tile<MODE, 4, 2>(g, m0, n0, smem);
+    else gemm_tile<MODE, 2, 2>(g, m0, n0, smem);
 }
 
 // ---------------------------------------------------------------------------
@@ -467,6 +513,12 @@ hipError_t launch_gemm(int dtype, int mode, const GemmSeg* segs, int nseg, void*
         // empty contraction: C = beta*C; only beta in {0,1} is supported by the API
         if (beta == 0.f) return launch_fill_zero(C, (size_t)M * N * dtype_size(dtype), st);
         return hipSuccess;
+    }
+    if (dtype == CF_BF16) {
+        // per-lane load offsets are 32-bit with the upper half reserved for "out of range"
+        for (int s = 0; s < g.nseg; ++s)
+            if ((int64_t)M * g.K[s] * 2 >= ((int64_t)1 << 31) || (int64_t)N * g.K[s] * 2 >= ((int64_t)1 << 31))
+                return hipErrorInvalidValue;
     }
     if (dtype == CF_F32) {
         const int grid = ceil_div(M, 64) * ceil_div(N, 64);

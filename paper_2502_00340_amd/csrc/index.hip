@@ -60,8 +60,34 @@ __global__ __launch_bounds__(IDX_THREADS) void mask_count_kernel(const uint8_t* 
     if (threadIdx.x == 0) block_count[blockIdx.x] = total;
 }
 
+// Exclusive prefix sum of the per-block counts, in place: one block, each thread owns a
+// contiguous run of the array.
+__global__ __launch_bounds__(1024) void block_scan_kernel(int32_t* __restrict__ block_count, int nblk) {
+    __shared__ int part[1024];
+    const int tid = threadIdx.x;
+    const int per = (nblk + 1023) / 1024;
+    const int lo = min(tid * per, nblk), hi = min(lo + per, nblk);
+    int s = 0;
+    for (int i = lo; i < hi; ++i) s += block_count[i];
+    part[tid] = s;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {        // Hillis-Steele inclusive scan of the 1024 run totals
+        const int v = tid >= o ? part[tid - o] : 0;
+        __syncthreads();
+        part[tid] += v;
+        __syncthreads();
+    }
+    int run = part[tid] - s;                    // exclusive
+    for (int i = lo; i < hi; ++i) {
+        const int c = block_count[i];
+        block_count[i] = run;
+        run += c;
+    }
+}
+
 // block_count == nullptr: every block counts the mask bytes before its chunk itself
-// (only used for a handful of blocks).
+// (only used for a handful of blocks); otherwise block_count[b] holds the number of kept
+// tokens before chunk b.
 __global__ __launch_bounds__(IDX_THREADS) void mask_scatter_kernel(
     const uint8_t* __restrict__ mask, int64_t T, int S, int B, int aligned,
     const int32_t* __restrict__ block_count, int32_t* __restrict__ idx,
@@ -71,17 +97,18 @@ __global__ __launch_bounds__(IDX_THREADS) void mask_scatter_kernel(
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
 
-    int before = 0;
+    int base;
     if (block_count != nullptr) {
-        for (int i = tid; i < (int)blockIdx.x; i += IDX_THREADS) before += block_count[i];
+        base = block_count[blockIdx.x];
     } else {
+        int before = 0;
         unsigned w[4];
         for (int c = 0; c < (int)blockIdx.x; ++c) {
             load_flags(mask, (int64_t)c * IDX_CHUNK + (int64_t)tid * IDX_PER_THREAD, T, aligned != 0, w);
             before += count_flags(w);
         }
+        base = block_sum_256(before, red);
     }
-    const int base = block_sum_256(before, red);
 
     unsigned w[4];
     const int64_t t0 = (int64_t)blockIdx.x * IDX_CHUNK + (int64_t)tid * IDX_PER_THREAD;
@@ -137,6 +164,7 @@ hipError_t launch_keep_index(const uint8_t* mask, int B, int S, int32_t* idx, in
     } else {
         int32_t* block_count = static_cast<int32_t*>(ws);
         mask_count_kernel<<<nblk, IDX_THREADS, 0, st>>>(mask, T, aligned, block_count);
+        block_scan_kernel<<<1, 1024, 0, st>>>(block_count, nblk);
         mask_scatter_kernel<<<nblk, IDX_THREADS, 0, st>>>(mask, T, S, B, aligned, block_count, idx,
                                                           cu_kept, n_kept_dev);
     }

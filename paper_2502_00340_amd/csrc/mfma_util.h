@@ -60,6 +60,23 @@ __device__ __forceinline__ void dma16(unsigned lds_base /*wave-uniform*/, i32x4_
                  : "memory");
 }
 
+// The same with a wave-uniform byte offset added to every lane's address (the instruction's
+// scalar offset operand): a loop that walks along a matrix keeps the per-lane offsets fixed
+// and advances one scalar.
+__device__ __forceinline__ void dma16s(unsigned lds_base /*wave-uniform*/, i32x4_t rsrc, unsigned voffset,
+                                       unsigned soffset /*wave-uniform*/) {
+    lds_base = __builtin_amdgcn_readfirstlane(lds_base);
+    soffset = __builtin_amdgcn_readfirstlane(soffset);
+    rsrc.x = __builtin_amdgcn_readfirstlane(rsrc.x);
+    rsrc.y = __builtin_amdgcn_readfirstlane(rsrc.y);
+    rsrc.z = __builtin_amdgcn_readfirstlane(rsrc.z);
+    rsrc.w = __builtin_amdgcn_readfirstlane(rsrc.w);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_base), "v"(voffset), "s"(rsrc), "s"(soffset)
+                 : "memory");
+}
+
 __device__ __forceinline__ unsigned lds_addr_of(const void* p) {
     return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
 }

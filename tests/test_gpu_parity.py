@@ -30,6 +30,7 @@ def say(msg):
     (5, 1000, 0.7), (2, 333, 0.0), (2, 333, 1.0), (1, 8192, 0.5),
     (3, 40961, 0.5),          # above 8 blocks: two-kernel path, ragged tail
     (1, (1 << 20) + 17, 0.5),
+    (8, 1 << 21, 0.5),        # 4096 blocks: every thread of the block-count scan owns several entries
 ])
 def test_keep_index_bit_exact(B, S, p):
     say("keep_index B=%d S=%d p=%g" % (B, S, p))
