@@ -158,7 +158,8 @@ cf_status cf_attn_bwd_filtered(const cf_layer_desc* desc, const void* q_kept, co
  * (rows of filtered tokens are ignored).  Outputs: grads->dx compact [N_k,H] (the
  * row-sparse gradient for the layer below), all parameter gradients; idx_out
  * [T] / cu_kept_out [B+1] (device, nullable) receive the keep index;
- * n_kept_host (host, required) receives N_k.  The call synchronises the stream
+ * n_kept_host (host, required; page-locked memory makes the copy cheaper) receives N_k.
+ * The call synchronises the stream
  * once, right after the index build, to size the remaining launches.
  * cf_layer_bwd_dense: the same kernels with every token kept and no index or
  * gather; dx is [T,H].

@@ -228,6 +228,8 @@ class LayerBackward:
             raise CfError(2, "cf_layer_workspace_bytes")
         self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=self.device)
         self._g = Grads(*[self.grads[n].data_ptr() for n, _ in Grads._fields_])
+        # N_k comes back through page-locked host memory: the copy needs no staging buffer
+        self._n_host = torch.empty(1, dtype=torch.int32).pin_memory()
 
     def _pack(self, saved: dict, weights: dict):
         sv = Saved(*[saved[n].data_ptr() for n in _SAVED])
@@ -238,12 +240,13 @@ class LayerBackward:
         """Runs cf_layer_bwd_filtered; results land in self.grads (dx: first N_k rows), self.idx,
         self.cu_kept.  Returns N_k."""
         sv, w = self._pack(saved, weights)
-        n_host = C.c_int32(-1)
+        self._n_host[0] = -1
         _check(lib().cf_layer_bwd_filtered(C.byref(self.desc), C.byref(sv), C.byref(w), _ptr(dy), _ptr(mask),
                                            C.byref(self._g), _ptr(self.idx), _ptr(self.cu_kept),
-                                           C.byref(n_host), _ptr(self.ws), self.ws_bytes, _stream()),
+                                           C.cast(self._n_host.data_ptr(), C.POINTER(C.c_int32)), _ptr(self.ws),
+                                           self.ws_bytes, _stream()),
                "cf_layer_bwd_filtered")
-        return int(n_host.value)
+        return int(self._n_host[0])
 
     def compact(self, saved: dict, weights: dict, dy_kept: torch.Tensor, idx: torch.Tensor,
                 cu_kept: torch.Tensor, n_kept: int) -> None:

@@ -191,22 +191,31 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ 
     }
 }
 
-// out[c] = sum_b partial[b,c]: a block owns 32 columns, 8 row groups stride through the partials
+// out[c] = sum_b partial[b,c]: a block owns 32 columns (8 lanes x 4 columns), 32 row groups
+// stride through the partials with 16-byte loads, many in flight; H is a multiple of 4.
+// The order of the additions is fixed, so the result is reproducible.
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_finish_kernel(const float* __restrict__ partial,
                                                             int nblk, int H, T* __restrict__ out) {
-    __shared__ float red[8][33];
-    const int c = blockIdx.x * 32 + (threadIdx.x & 31), rg = threadIdx.x >> 5;
-    float s = 0.f;
-    if (c < H)
-        for (int b = rg; b < nblk; b += 8) s += partial[(int64_t)b * H + c];
-    red[rg][threadIdx.x & 31] = s;
+    __shared__ float red[32][33];
+    const int cq = threadIdx.x & 7, rg = threadIdx.x >> 3;
+    const int c = blockIdx.x * 32 + cq * 4;
+    float s[4] = {0.f, 0.f, 0.f, 0.f};
+    if (c < H) {
+#pragma unroll 8
+        for (int b = rg; b < nblk; b += 32) {
+            const float4 v = *reinterpret_cast<const float4*>(partial + (int64_t)b * H + c);
+            s[0] += v.x; s[1] += v.y; s[2] += v.z; s[3] += v.w;
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) red[rg][cq * 4 + e] = s[e];
     __syncthreads();
-    if (rg == 0 && c < H) {
+    if (threadIdx.x < 32 && blockIdx.x * 32 + threadIdx.x < H) {
         float t = 0.f;
 #pragma unroll
-        for (int r = 0; r < 8; ++r) t += red[r][threadIdx.x];
-        out[c] = from_f32<T>(t);
+        for (int r = 0; r < 32; ++r) t += red[r][threadIdx.x];
+        out[blockIdx.x * 32 + threadIdx.x] = from_f32<T>(t);
     }
 }
 
