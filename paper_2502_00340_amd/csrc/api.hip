@@ -13,10 +13,10 @@ hipError_t launch_attn_bwd_ref(const cf_layer_desc& L, float scale, const void* 
 bool attn_mfma_supported(const cf_layer_desc& L);
 size_t attn_mfma_partial_bytes(const cf_layer_desc& L, int n_kept);
 hipError_t launch_attn_bwd_mfma(const cf_layer_desc& L, float scale, const void* q_kept,
-                                const void* k_full, const void* v_full, const float* lse_full,
-                                const void* do_kept, const float* Drow, const int32_t* idx,
-                                const int32_t* cu_kept, int n_kept, void* dq_kept, void* dk_kept,
-                                void* dv_kept, float* partials, hipStream_t st);
+                                const void* k_full, const void* v_full, const void* o_kept,
+                                const float* lse_full, const void* do_kept, float* stat,
+                                const int32_t* idx, const int32_t* cu_kept, int n_kept, void* dq_kept,
+                                void* dk_kept, void* dv_kept, float* partials, hipStream_t st);
 }  // namespace cf
 
 using namespace cf;
@@ -70,8 +70,9 @@ float eff_scale(const cf_layer_desc& L) {
     return L.softmax_scale > 0.f ? L.softmax_scale : 1.0f / sqrtf((float)L.d);
 }
 
+// row statistics: D per (row, head), and for the matrix-core path also the scaled LSE
 size_t attn_drow_bytes(const cf_layer_desc& L, int n_kept) {
-    return align_up((size_t)(n_kept > 0 ? n_kept : 1) * L.Hq * sizeof(float), 256);
+    return align_up((size_t)2 * (size_t)(n_kept > 0 ? n_kept : 1) * L.Hq * sizeof(float), 256);
 }
 
 // D row statistics followed by the per-head dK/dV partials of the matrix-core path
@@ -138,13 +139,14 @@ cf_status attn_dispatch(const cf_layer_desc& L, const void* q_kept, const void* 
     const float scale = eff_scale(L);
     float* Drow = static_cast<float*>(attn_ws);
     float* partials = reinterpret_cast<float*>(static_cast<unsigned char*>(attn_ws) + attn_drow_bytes(L, n_kept));
-    CF_HIP(launch_attn_rowdot(L.dtype, do_kept, o_kept, n_kept, L.Hq, L.d, Drow, st));
-    if (attn_mfma_supported(L))
-        CF_HIP(launch_attn_bwd_mfma(L, scale, q_kept, k_full, v_full, lse_full, do_kept, Drow, idx,
+    if (attn_mfma_supported(L)) {
+        CF_HIP(launch_attn_bwd_mfma(L, scale, q_kept, k_full, v_full, o_kept, lse_full, do_kept, Drow, idx,
                                     cu_kept, n_kept, dq_kept, dk_kept, dv_kept, partials, st));
-    else
+    } else {
+        CF_HIP(launch_attn_rowdot(L.dtype, do_kept, o_kept, n_kept, L.Hq, L.d, Drow, st));
         CF_HIP(launch_attn_bwd_ref(L, scale, q_kept, k_full, v_full, lse_full, do_kept, Drow, idx,
                                    cu_kept, n_kept, dq_kept, dk_kept, dv_kept, st));
+    }
     return CF_OK;
 }
 

@@ -46,7 +46,7 @@ static constexpr float LOG2E = 1.4426950408889634f;
 
 struct AttnParams {
     const bf16_t *q_kept, *k_full, *v_full, *do_kept;
-    const float *lse_full, *Drow;
+    const float* stat;             // [2][Hq][n_kept]: log2(e)*LSE and D = rowsum(dO*O) of every kept row and head
     const int32_t *idx, *cu_kept;
     bf16_t *dq_kept, *dk_kept, *dv_kept;
     float *dk_part, *dv_part;      // [G][n_kept][Hkv*d] fp32 per-query-head partials (G > 1 only)
@@ -153,8 +153,8 @@ __global__ __launch_bounds__(256, 2) void attn_dq_kernel(AttnParams p) {
     const int jq = j0 + wave * 32 + slot;
     const bool qvalid = wave * 32 + slot < rows_in_tile;
     const int pos = qvalid ? (p.idx ? p.idx[jq] : jq) - b * p.S : -1;
-    const float lse2 = qvalid ? p.lse_full[((int64_t)b * p.Hq + h) * p.S + pos] * LOG2E : 0.f;
-    const float Dq = qvalid ? p.Drow[(int64_t)jq * p.Hq + h] : 0.f;
+    const float lse2 = qvalid ? p.stat[(int64_t)h * p.n_kept + jq] : 0.f;
+    const float Dq = qvalid ? p.stat[(int64_t)(p.Hq + h) * p.n_kept + jq] : 0.f;
     bf16x8_t qf[KS], dof[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
@@ -305,6 +305,8 @@ __global__ __launch_bounds__(256, D == 128 ? 1 : 2) void attn_dkv_kernel(AttnPar
     // Q and dO rows of this sequence from its first key on, this head's columns
     const i32x4_t rsQ = make_rsrc(p.q_kept + (int64_t)c0 * Nq + h * D, ((int64_t)(seq_end - c0) * Nq - h * D) * 2);
     const i32x4_t rsO = make_rsrc(p.do_kept + (int64_t)c0 * Nq + h * D, ((int64_t)(seq_end - c0) * Nq - h * D) * 2);
+    const i32x4_t rsL = make_rsrc(p.stat + (int64_t)h * p.n_kept + c0, (int64_t)(seq_end - c0) * 4);
+    const i32x4_t rsD = make_rsrc(p.stat + (int64_t)(p.Hq + h) * p.n_kept + c0, (int64_t)(seq_end - c0) * 4);
     const unsigned lds0 = __builtin_amdgcn_readfirstlane(lds_addr_of(smem));
     auto issue_q = [&](int step, int stage) {
         const unsigned sq = lds0 + stage * STAGE;
@@ -312,17 +314,12 @@ __global__ __launch_bounds__(256, D == 128 ? 1 : 2) void attn_dkv_kernel(AttnPar
         const int valid = seq_end - c0 - step * 64;
         dma_tile<D>(sq, rsQ, base, Nq * 2, valid, wave, lane);
         dma_tile<D>(sq + TILE, rsO, base, Nq * 2, valid, wave, lane);
-        if (tid < 64) {
-            float* sl = reinterpret_cast<float*>(smem + stage * STAGE + 2 * TILE);
-            const int row = c0 + step * 64 + tid;
-            float rl = __builtin_inff(), rd = 0.f;          // exp2(x - inf) = 0 past the sequence end
-            if (row < seq_end) {
-                const int pos = (p.idx ? p.idx[row] : row) - b * p.S;
-                rl = p.lse_full[((int64_t)b * p.Hq + h) * p.S + pos] * LOG2E;
-                rd = p.Drow[(int64_t)row * p.Hq + h];
-            }
-            sl[tid] = rl;
-            sl[64 + tid] = rd;
+        if (wave == 0) {
+            // row statistics of the 64 queries: rows past the sequence end read zeros, which is
+            // harmless because their Q and dO rows are zero as well
+            const unsigned off = (unsigned)(step * 64 + lane) * 4u;
+            dma4(sq + 2 * TILE, rsL, off);
+            dma4(sq + 2 * TILE + 256, rsD, off);
         }
     };
 
@@ -440,6 +437,37 @@ __global__ __launch_bounds__(256) void attn_dkv_reduce_kernel(const float* __res
     Vec<bf16_t>::store(dv + i, sv);
 }
 
+// stat[0][h][j] = log2(e) * LSE(b, h, position of kept row j); stat[1][h][j] = D = sum_c dO*O of
+// (row j, head h): the row terms of the FlashAttention backward, laid out so that the 64 rows a
+// dK/dV block needs per step are contiguous.  d/8 lanes share one (row, head).
+__global__ __launch_bounds__(256) void attn_stats_kernel(const bf16_t* __restrict__ do_kept,
+                                                         const bf16_t* __restrict__ o_kept,
+                                                         const float* __restrict__ lse_full,
+                                                         const int32_t* __restrict__ idx, int n_kept,
+                                                         int Hq, int d, int S, float* __restrict__ stat) {
+    const int lanes = d / 8;
+    const int64_t total = (int64_t)n_kept * Hq * lanes;
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    float s = 0.f;
+    const int64_t pair = gid / lanes;
+    if (gid < total) {
+        const int part = (int)(gid % lanes);
+        float a[8], b[8];
+        Vec<bf16_t>::load(do_kept + pair * d + part * 8, a);
+        Vec<bf16_t>::load(o_kept + pair * d + part * 8, b);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s += a[e] * b[e];
+    }
+    for (int o = lanes >> 1; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+    if (gid < total && (gid % lanes) == 0) {
+        const int j = (int)(pair / Hq), h = (int)(pair % Hq);
+        const int64_t tok = idx ? idx[j] : j;
+        const int64_t bb = tok / S, pos = tok - bb * S;
+        stat[(int64_t)h * n_kept + j] = lse_full[(bb * Hq + h) * S + pos] * LOG2E;
+        stat[(int64_t)(Hq + h) * n_kept + j] = s;
+    }
+}
+
 bool attn_mfma_supported(const cf_layer_desc& L) {
     return L.dtype == CF_BF16 && (L.d == 64 || L.d == 128);
 }
@@ -451,7 +479,8 @@ size_t attn_mfma_partial_bytes(const cf_layer_desc& L, int n_kept) {
 }
 
 template <int D>
-static hipError_t launch_t(const AttnParams& p, int n_kept, hipStream_t st) {
+static hipError_t launch_t(const AttnParams& p, const bf16_t* o_kept, const float* lse_full, float* stat,
+                           int n_kept, hipStream_t st) {
     constexpr int smem_dq = 2 * 2 * 64 * D * 2;
     constexpr int smem_dkv = 2 * (2 * 64 * D * 2 + 512);
     static bool attr_set = false;
@@ -463,6 +492,11 @@ static hipError_t launch_t(const AttnParams& p, int n_kept, hipStream_t st) {
                                 hipFuncAttributeMaxDynamicSharedMemorySize, smem_dkv);
         if (e != hipSuccess) return e;
         attr_set = true;
+    }
+    {
+        const int64_t total = (int64_t)n_kept * p.Hq * (D / 8);
+        attn_stats_kernel<<<(int)((total + 255) / 256), 256, 0, st>>>(p.do_kept, o_kept, lse_full, p.idx, n_kept,
+                                                                     p.Hq, D, p.S, stat);
     }
     const int max_per_seq = n_kept < p.S ? n_kept : p.S;
     const int tiles = ceil_div(max_per_seq, 128);
@@ -477,20 +511,20 @@ static hipError_t launch_t(const AttnParams& p, int n_kept, hipStream_t st) {
 }
 
 hipError_t launch_attn_bwd_mfma(const cf_layer_desc& L, float scale, const void* q_kept,
-                                const void* k_full, const void* v_full, const float* lse_full,
-                                const void* do_kept, const float* Drow, const int32_t* idx,
-                                const int32_t* cu_kept, int n_kept, void* dq_kept, void* dk_kept,
-                                void* dv_kept, float* partials, hipStream_t st) {
+                                const void* k_full, const void* v_full, const void* o_kept,
+                                const float* lse_full, const void* do_kept, float* stat,
+                                const int32_t* idx, const int32_t* cu_kept, int n_kept, void* dq_kept,
+                                void* dk_kept, void* dv_kept, float* partials, hipStream_t st) {
     AttnParams p;
     p.q_kept = (const bf16_t*)q_kept; p.k_full = (const bf16_t*)k_full; p.v_full = (const bf16_t*)v_full;
-    p.do_kept = (const bf16_t*)do_kept; p.lse_full = lse_full; p.Drow = Drow; p.idx = idx;
+    p.do_kept = (const bf16_t*)do_kept; p.stat = stat; p.idx = idx;
     p.cu_kept = cu_kept; p.dq_kept = (bf16_t*)dq_kept; p.dk_kept = (bf16_t*)dk_kept;
     p.dv_kept = (bf16_t*)dv_kept; p.B = L.B; p.S = L.S; p.Hq = L.Hq; p.Hkv = L.Hkv; p.scale = scale;
     p.n_kept = n_kept;
     p.dk_part = partials;
     p.dv_part = partials ? partials + (size_t)n_kept * L.Hq * L.d : nullptr;
-    if (L.d == 64) return launch_t<64>(p, n_kept, st);
-    return launch_t<128>(p, n_kept, st);
+    if (L.d == 64) return launch_t<64>(p, (const bf16_t*)o_kept, lse_full, stat, n_kept, st);
+    return launch_t<128>(p, (const bf16_t*)o_kept, lse_full, stat, n_kept, st);
 }
 
 }  // namespace cf

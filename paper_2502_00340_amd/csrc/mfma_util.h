@@ -60,6 +60,19 @@ __device__ __forceinline__ void dma16(unsigned lds_base /*wave-uniform*/, i32x4_
                  : "memory");
 }
 
+// 4 bytes per lane: lane l of the wave writes LDS bytes [lds_base + 4*l, +4).
+__device__ __forceinline__ void dma4(unsigned lds_base /*wave-uniform*/, i32x4_t rsrc, unsigned voffset) {
+    lds_base = __builtin_amdgcn_readfirstlane(lds_base);
+    rsrc.x = __builtin_amdgcn_readfirstlane(rsrc.x);
+    rsrc.y = __builtin_amdgcn_readfirstlane(rsrc.y);
+    rsrc.z = __builtin_amdgcn_readfirstlane(rsrc.z);
+    rsrc.w = __builtin_amdgcn_readfirstlane(rsrc.w);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_base), "v"(voffset), "s"(rsrc)
+                 : "memory");
+}
+
 // The same with a wave-uniform byte offset added to every lane's address (the instruction's
 // scalar offset operand): a loop that walks along a matrix keeps the per-lane offsets fixed
 // and advances one scalar.
