@@ -256,7 +256,7 @@ __global__ __launch_bounds__(256, 2) void attn_dq_kernel(AttnParams p) {
 // dK/dV kernel: one (key tile, query head) per block
 // ---------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(256, D == 128 ? 1 : 2) void attn_dkv_kernel(AttnParams p) {
+__global__ __launch_bounds__(256, 1) void attn_dkv_kernel(AttnParams p) {
     constexpr int KS = D / 16, NT = D / 32;
     constexpr int TILE = 64 * D * 2;
     constexpr int STAGE = 2 * TILE + 512;       // Q tile, dO tile, lse2[64], D[64]
@@ -294,7 +294,6 @@ __global__ __launch_bounds__(256, D == 128 ? 1 : 2) void attn_dkv_kernel(AttnPar
     }
     const float scale2 = p.scale * LOG2E;
     const int steps = (seq_end - c0 + 63) / 64;     // query tiles from the first key to the sequence end
-    const int wave_first_key = c0 + wave * 32;
 
     f32x16_t dk[NT], dv[NT];
 #pragma unroll
@@ -314,73 +313,137 @@ __global__ __launch_bounds__(256, D == 128 ? 1 : 2) void attn_dkv_kernel(AttnPar
         const int valid = seq_end - c0 - step * 64;
         dma_tile<D>(sq, rsQ, base, Nq * 2, valid, wave, lane);
         dma_tile<D>(sq + TILE, rsO, base, Nq * 2, valid, wave, lane);
-        if (wave == 0) {
-            // row statistics of the 64 queries: rows past the sequence end read zeros, which is
-            // harmless because their Q and dO rows are zero as well
+        {
+            // row statistics of the 64 queries (every wave issues the same two loads, which keeps the
+            // number of loads per wave and step equal); rows past the sequence end read zeros, which
+            // is harmless because their Q and dO rows are zero as well
             const unsigned off = (unsigned)(step * 64 + lane) * 4u;
             dma4(sq + 2 * TILE, rsL, off);
             dma4(sq + 2 * TILE + 256, rsD, off);
         }
     };
 
+    // Ring of four stages: the loads of step s+3 are issued at the top of step s, into the stage that
+    // step s-1 used.  Steps past the end are issued as well (every row out of range: zero fill), so
+    // the number of loads in flight is the same in every iteration.
+    constexpr int LPS = 2 * (D / 32) + 2;           // loads per wave and step
     issue_q(0, 0);
-    wait_vmcnt<0>();
+    issue_q(1, 1);
+    issue_q(2, 2);
+    wait_vmcnt<2 * LPS>();
     lds_barrier();
     for (int step = 0; step < steps; ++step) {
-        const int cur = step & 1;
-        if (step + 1 < steps) issue_q(step + 1, cur ^ 1);
+        const int cur = step & 3;
+        issue_q(step + 3, (step + 3) & 3);
         const int qbase = c0 + step * 64;
-        if (qbase + 63 >= wave_first_key && wave * 32 < keys_in_tile) {
+        // every wave works on every step: a wave whose keys all lie after the step's queries (first
+        // step of a tile) or past the sequence end multiplies zeros, which costs less than keeping
+        // the accumulators live across a branch
+        {
             const unsigned char* sq = smem + cur * STAGE;
             const unsigned char* sdo = sq + TILE;
             const float* sl = reinterpret_cast<const float*>(sq + 2 * TILE);
-            // one 32-query half of the tile at a time keeps the score registers at 2 x 16
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt) {
-                f32x16_t st, dpt;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) { st[v] = 0.f; dpt[v] = 0.f; }
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sq, mt * 32 + slot, ks, hh), kf[ks],
-                                                                 st, 0, 0, 0);
-                    dpt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sdo, mt * 32 + slot, ks, hh), vf[ks],
-                                                                  dpt, 0, 0, 0);
-                }
-                // P and dS: lane = key, register = query
+            // The tile is two halves of 32 queries (h = 0, 1).  Per half: A(h) = S and dP (2*KS MFMAs),
+            // B(h) = P and dS from them (vector ALU: exp2, masks, products), C(h) = dV and dK (4*NT
+            // MFMAs).  A wave runs alone on its SIMD, so the three kinds of work are software-pipelined
+            // by hand:   A(0) | A(1) + B(0) | C(0) + B(1) | C(1)
+            // with a few vector instructions and the LDS reads of the next MFMA pair placed between two
+            // MFMA pairs, which keeps the matrix core fed while the exponentials are computed.
+            constexpr int VPP = 16 / KS;                    // softmax values per MFMA pair
+            f32x16_t st[2], dpt[2];
+            bf16x8_t fa[2][2], fc[2][2];                    // [buffer][Q / dO]: row and token fragments
+            float4 lq[4], dq4[4];                           // log2(e)*LSE and D of the current half's queries, in groups of 4
+            bf16x8_t ap[2][2], ads[2][2];                   // packed P and dS, [half][16-query block]
+            auto load_a = [&](int h, int ks, int buf) __attribute__((always_inline)) {
+                fa[buf][0] = frag_rows<D>(sq, h * 32 + slot, ks, hh);
+                fa[buf][1] = frag_rows<D>(sdo, h * 32 + slot, ks, hh);
+            };
+            auto load_c = [&](int h, int c, int buf) __attribute__((always_inline)) {
+                const int j = c / NT, nt = c % NT;
+                fc[buf][0] = frag_tokens<D>(sq, h * 32 + 16 * j, nt, lane);
+                fc[buf][1] = frag_tokens<D>(sdo, h * 32 + 16 * j, nt, lane);
+            };
+            auto load_stats = [&](int h) __attribute__((always_inline)) {
 #pragma unroll
                 for (int v4 = 0; v4 < 4; ++v4) {
-                    const int ql = mt * 32 + 8 * v4 + 4 * hh;
-                    const float4 l4 = *reinterpret_cast<const float4*>(sl + ql);
-                    const float4 d4 = *reinterpret_cast<const float4*>(sl + 64 + ql);
-                    const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
-                    const float dd[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int v = 4 * v4 + e;
-                        const bool ok = kvalid && (qbase + ql + e >= jk);
-                        const float pr = ok ? __builtin_amdgcn_exp2f(st[v] * scale2 - lv[e]) : 0.f;
-                        st[v] = pr;
-                        dpt[v] = pr * (dpt[v] - dd[e]);
-                    }
+                    lq[v4] = *reinterpret_cast<const float4*>(sl + h * 32 + 8 * v4 + 4 * hh);
+                    dq4[v4] = *reinterpret_cast<const float4*>(sl + 64 + h * 32 + 8 * v4 + 4 * hh);
                 }
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    const bf16x8_t ap = pack8(st, j);
-                    const bf16x8_t ads = pack8(dpt, j);
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) {
-                        dv[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            ap, frag_tokens<D>(sdo, mt * 32 + 16 * j, nt, lane), dv[nt], 0, 0, 0);
-                        dk[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            ads, frag_tokens<D>(sq, mt * 32 + 16 * j, nt, lane), dk[nt], 0, 0, 0);
-                    }
+            };
+            auto mma_a = [&](int h, int ks, int buf) __attribute__((always_inline)) {
+                st[h] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][0], kf[ks], st[h], 0, 0, 0);
+                dpt[h] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][1], vf[ks], dpt[h], 0, 0, 0);
+            };
+            auto mma_c = [&](int h, int c, int buf) __attribute__((always_inline)) {
+                const int j = c / NT, nt = c % NT;
+                dk[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ads[h][j], fc[buf][0], dk[nt], 0, 0, 0);
+                dv[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[h][j], fc[buf][1], dv[nt], 0, 0, 0);
+            };
+            // P and dS of value v (query 8*(v/4) + 4*hh + v%4 of the half): lane = key, register = query
+            auto soft = [&](int h, int v) __attribute__((always_inline)) {
+                const int v4 = v >> 2, e = v & 3;
+                const float lv = e == 0 ? lq[v4].x : (e == 1 ? lq[v4].y : (e == 2 ? lq[v4].z : lq[v4].w));
+                const float dd = e == 0 ? dq4[v4].x : (e == 1 ? dq4[v4].y : (e == 2 ? dq4[v4].z : dq4[v4].w));
+                const bool ok = kvalid && (qbase + h * 32 + 8 * v4 + 4 * hh + e >= jk);
+                const float pr = ok ? __builtin_amdgcn_exp2f(st[h][v] * scale2 - lv) : 0.f;
+                st[h][v] = pr;
+                dpt[h][v] = pr * (dpt[h][v] - dd);
+                if ((v & 7) == 7) {                          // a 16-query block (8 registers) is complete
+                    ap[h][v >> 3] = pack8(st[h], v >> 3);
+                    ads[h][v >> 3] = pack8(dpt[h], v >> 3);
                 }
+            };
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) { st[h][v] = 0.f; dpt[h][v] = 0.f; }
+            // ---- A(0)
+            load_a(0, 0, 0);
+            load_stats(0);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                if (ks + 1 < KS) load_a(0, ks + 1, (ks + 1) & 1);
+                else load_a(1, 0, (ks + 1) & 1);
+                CF_SCHED_FENCE();
+                mma_a(0, ks, ks & 1);
+                CF_SCHED_FENCE();
+            }
+            // ---- A(1) + B(0)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                if (ks + 1 < KS) load_a(1, ks + 1, (KS + ks + 1) & 1);
+                else load_c(0, 0, 0);
+#pragma unroll
+                for (int e = 0; e < VPP; ++e) soft(0, ks * VPP + e);
+                CF_SCHED_FENCE();
+                mma_a(1, ks, (KS + ks) & 1);
+                CF_SCHED_FENCE();
+            }
+            // ---- C(0) + B(1)
+            load_stats(1);
+#pragma unroll
+            for (int c = 0; c < 2 * NT; ++c) {
+                if (c + 1 < 2 * NT) load_c(0, c + 1, (c + 1) & 1);
+                else load_c(1, 0, (c + 1) & 1);
+#pragma unroll
+                for (int e = 0; e < VPP; ++e) soft(1, c * VPP + e);
+                CF_SCHED_FENCE();
+                mma_c(0, c, c & 1);
+                CF_SCHED_FENCE();
+            }
+            // ---- C(1)
+#pragma unroll
+            for (int c = 0; c < 2 * NT; ++c) {
+                if (c + 1 < 2 * NT) load_c(1, c + 1, (2 * NT + c + 1) & 1);
+                CF_SCHED_FENCE();
+                mma_c(1, c, (2 * NT + c) & 1);
+                CF_SCHED_FENCE();
             }
         }
-        wait_vmcnt<0>();
+        wait_vmcnt<2 * LPS>();          // step + 1 has landed; steps + 2 and + 3 may be in flight
         lds_barrier();
     }
+    wait_vmcnt<0>();
 
     if (G == 1) {
 #pragma unroll
@@ -482,7 +545,7 @@ template <int D>
 static hipError_t launch_t(const AttnParams& p, const bf16_t* o_kept, const float* lse_full, float* stat,
                            int n_kept, hipStream_t st) {
     constexpr int smem_dq = 2 * 2 * 64 * D * 2;
-    constexpr int smem_dkv = 2 * (2 * 64 * D * 2 + 512);
+    constexpr int smem_dkv = 4 * (2 * 64 * D * 2 + 512);
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_dq_kernel<D>),
