@@ -206,7 +206,17 @@ __global__ __launch_bounds__(256, 2) void attn_dq_kernel(AttnParams p) {
         if (kt * 64 <= wave_maxpos) {
             const unsigned char* sk = smem + cur * 2 * TILE;
             const unsigned char* sv = sk + TILE;
-            // one 32-key half of the tile at a time keeps the score registers at 2 x 16
+            // One 32-key half of the tile at a time keeps the score registers at 2 x 16.  The LDS
+            // fragments of an MFMA are read while the previous MFMAs run (one step ahead).
+            bf16x8_t fa[2][2], fc[2];
+            auto load_a = [&](int mt, int ks, int buf) __attribute__((always_inline)) {
+                fa[buf][0] = frag_rows<D>(sk, mt * 32 + slot, ks, hh);
+                fa[buf][1] = frag_rows<D>(sv, mt * 32 + slot, ks, hh);
+            };
+            auto load_c = [&](int mt, int c, int buf) __attribute__((always_inline)) {
+                fc[buf] = frag_tokens<D>(sk, mt * 32 + 16 * (c / NT), c % NT, lane);
+            };
+            load_a(0, 0, 0);
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt) {
                 f32x16_t st, dpt;
@@ -214,10 +224,12 @@ __global__ __launch_bounds__(256, 2) void attn_dq_kernel(AttnParams p) {
                 for (int v = 0; v < 16; ++v) { st[v] = 0.f; dpt[v] = 0.f; }
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sk, mt * 32 + slot, ks, hh), qf[ks],
-                                                                 st, 0, 0, 0);
-                    dpt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sv, mt * 32 + slot, ks, hh), dof[ks],
-                                                                  dpt, 0, 0, 0);
+                    if (ks + 1 < KS) load_a(mt, ks + 1, (ks + 1) & 1);
+                    else load_c(mt, 0, 0);
+                    CF_SCHED_FENCE();
+                    st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][0], qf[ks], st, 0, 0, 0);
+                    dpt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][1], dof[ks], dpt, 0, 0, 0);
+                    CF_SCHED_FENCE();
                 }
                 // dS^T = P^T o (dP^T - D): lane = query, register = key
 #pragma unroll
@@ -226,13 +238,14 @@ __global__ __launch_bounds__(256, 2) void attn_dq_kernel(AttnParams p) {
                     const float pr = key <= pos ? __builtin_amdgcn_exp2f(st[v] * scale2 - lse2) : 0.f;
                     st[v] = pr * (dpt[v] - Dq);
                 }
+                const bf16x8_t a0 = pack8(st, 0), a1 = pack8(st, 1);
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    const bf16x8_t a = pack8(st, j);
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt)
-                        acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            a, frag_tokens<D>(sk, mt * 32 + 16 * j, nt, lane), acc[nt], 0, 0, 0);
+                for (int c = 0; c < 2 * NT; ++c) {
+                    if (c + 1 < 2 * NT) load_c(mt, c + 1, (c + 1) & 1);
+                    else if (mt == 0) load_a(1, 0, 0);
+                    CF_SCHED_FENCE();
+                    acc[c % NT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c < NT ? a0 : a1, fc[c & 1], acc[c % NT], 0, 0, 0);
+                    CF_SCHED_FENCE();
                 }
             }
         }
