@@ -143,13 +143,13 @@ def roofline_leg(shape: WL.LayerShape, n_k: int, reps: int = 20):
     avg = sum(ms) / len(ms)
     flops = 2.0 * n_k * shape.F * shape.H
     ach = flops / (avg * 1e-3) / 1e12
+    # HBM bytes per launch of this kernel, from the two counter runs summarised under profiles/
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get("gemm_tn_dwd_bytes_per_launch")
-        except Exception:
-            traffic = None
+    tpath = os.path.join(ROOT, "profiles", "gemm_tn_dw_8b_hbm_traffic.txt")
+    if os.path.exists(tpath) and (n_k, shape.F, shape.H) == (4096, 14336, 4096):
+        for line in open(tpath):
+            if line.strip().startswith("traffic_bytes_per_launch:"):
+                traffic = int(line.split(":")[1])
     return {"bound": "mfma", "achieved": round(ach, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
             "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
             "kernel": "cf::gemm_bf16_kernel<1> (TN): dW[F,H] = X_kept^T dY_kept",
