@@ -78,6 +78,14 @@ typedef struct {
     const void* r;         /* [T,H]     x + attn_out*Wo (input of the 2nd norm)  */
     const void* gate;      /* [T,F]     rmsnorm2(r)*Wg                           */
     const void* up;        /* [T,F]     rmsnorm2(r)*Wu                           */
+    /* Rotary position embedding of q and k (optional; both NULL = none).  The paper does not
+     * mention it; the evaluated model families use it.  Tables [S, d/2] fp32 for position s and
+     * frequency i; the forward rotated each head of the projected q and k as
+     *   out[i] = x[i]*cos - x[i+d/2]*sin,  out[i+d/2] = x[i+d/2]*cos + x[i]*sin   (i < d/2),
+     * q and k above are the rotated tensors, and the layer calls apply the transposed rotation
+     * to dq and dk, at the ORIGINAL position of each kept row, before the projections' backward. */
+    const float* rope_cos;
+    const float* rope_sin;
 } cf_saved;
 
 typedef struct {

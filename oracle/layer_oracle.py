@@ -109,14 +109,53 @@ def attn_fwd(q, k, v, B, S, Hq, Hkv, d, scale):
     return out, lse
 
 
-def layer_fwd(x, W, B, S, Hq, Hkv, d, eps=1e-5, scale=None):
+def rope_fwd(x, cos, sin, B, S, heads, d):
+    """Rotary position embedding of every head of x [T, heads*d]: the pair
+    (i, i + d/2) of a head is rotated by the angle of (position, frequency i);
+    cos, sin: [S, d/2].  (Not in the paper; the model families it evaluates use
+    it, in this half-split pairing.)"""
+    T = B * S
+    out = np.empty_like(x)
+    half = d // 2
+    for t in range(T):
+        c = cos[t % S].astype(x.dtype)
+        s = sin[t % S].astype(x.dtype)
+        for h in range(heads):
+            lo = x[t, h * d:h * d + half]
+            hi = x[t, h * d + half:(h + 1) * d]
+            out[t, h * d:h * d + half] = lo * c - hi * s
+            out[t, h * d + half:(h + 1) * d] = hi * c + lo * s
+    return out
+
+
+def rope_bwd(dy, cos, sin, B, S, heads, d):
+    """Gradient of rope_fwd with respect to its input: the transposed rotation."""
+    T = B * S
+    out = np.empty_like(dy)
+    half = d // 2
+    for t in range(T):
+        c = cos[t % S].astype(dy.dtype)
+        s = sin[t % S].astype(dy.dtype)
+        for h in range(heads):
+            lo = dy[t, h * d:h * d + half]
+            hi = dy[t, h * d + half:(h + 1) * d]
+            out[t, h * d:h * d + half] = lo * c + hi * s
+            out[t, h * d + half:(h + 1) * d] = hi * c - lo * s
+    return out
+
+
+def layer_fwd(x, W, B, S, Hq, Hkv, d, eps=1e-5, scale=None, rope=None):
     """Decoder-layer forward.  Returns (y, saved) where saved holds exactly the
-    tensors the backward is given: x, q, k, v, attn_out, lse, r, gate, up."""
+    tensors the backward is given: x, q, k, v, attn_out, lse, r, gate, up.
+    rope: None or (cos, sin) tables [S, d/2]; q and k in `saved` are rotated."""
     scale = (1.0 / np.sqrt(d)) if scale is None else scale
     h1, _ = rmsnorm_fwd(x, W["g1"], eps)
     q = h1 @ W["wq"]
     k = h1 @ W["wk"]
     v = h1 @ W["wv"]
+    if rope is not None:
+        q = rope_fwd(q, rope[0], rope[1], B, S, Hq, d)
+        k = rope_fwd(k, rope[0], rope[1], B, S, Hkv, d)
     a, lse = attn_fwd(q, k, v, B, S, Hq, Hkv, d, scale)
     r = x + a @ W["wo"]
     h2, _ = rmsnorm_fwd(r, W["g2"], eps)
@@ -201,7 +240,7 @@ def attn_bwd(q, k, v, attn_out, lse, da, B, S, Hq, Hkv, d, scale, keep=None):
 # whole layer
 # ---------------------------------------------------------------------------
 
-def layer_bwd(saved, W, dy, mask, B, S, Hq, Hkv, d, eps=1e-5, scale=None):
+def layer_bwd(saved, W, dy, mask, B, S, Hq, Hkv, d, eps=1e-5, scale=None, rope=None):
     """Token-filtered backward of one decoder layer.
 
     saved: dict from layer_fwd (x, q, k, v, attn_out, lse, r, gate, up), or
@@ -210,7 +249,7 @@ def layer_bwd(saved, W, dy, mask, B, S, Hq, Hkv, d, eps=1e-5, scale=None):
     the dense backward.  Returns a dict: dx [T,H] (zero on filtered rows),
     dwq, dwk, dwv, dwo, dwg, dwu, dwd, dg1, dg2.  Normalised activations and
     the SwiGLU product are rebuilt from the saved tensors, as the HIP path has
-    to do as well."""
+    to do as well.  rope: None or (cos, sin) [S, d/2] when saved q, k are rotated."""
     scale = (1.0 / np.sqrt(d)) if scale is None else scale
     x, r, gate, up = saved["x"], saved["r"], saved["gate"], saved["up"]
     a = saved["attn_out"]
@@ -236,6 +275,9 @@ def layer_bwd(saved, W, dy, mask, B, S, Hq, Hkv, d, eps=1e-5, scale=None):
     da, dwo = linear_bwd(a, dr, W["wo"])
     dq, dk, dv = attn_bwd(saved["q"], saved["k"], saved["v"], a, saved["lse"], da,
                           B, S, Hq, Hkv, d, scale, keep=keep)       # masking point (2)
+    if rope is not None:        # saved q, k are the rotated tensors: undo the rotation on their gradients
+        dq = rope_bwd(dq, rope[0], rope[1], B, S, Hq, d)
+        dk = rope_bwd(dk, rope[0], rope[1], B, S, Hkv, d)
     h1, _ = rmsnorm_fwd(x, W["g1"], eps)
     dh1_q, dwq = linear_bwd(h1, dq, W["wq"])
     dh1_k, dwk = linear_bwd(h1, dk, W["wk"])

@@ -39,7 +39,8 @@ class LayerDesc(C.Structure):
 
 
 class Saved(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("x", "q", "k", "v", "attn_out", "lse", "r", "gate", "up")]
+    _fields_ = [(n, C.c_void_p) for n in ("x", "q", "k", "v", "attn_out", "lse", "r", "gate", "up",
+                                           "rope_cos", "rope_sin")]
 
 
 class Weights(C.Structure):
@@ -232,7 +233,8 @@ class LayerBackward:
         self._n_host = torch.empty(1, dtype=torch.int32).pin_memory()
 
     def _pack(self, saved: dict, weights: dict):
-        sv = Saved(*[saved[n].data_ptr() for n in _SAVED])
+        rope = [saved[n].data_ptr() if saved.get(n) is not None else None for n in ("rope_cos", "rope_sin")]
+        sv = Saved(*([saved[n].data_ptr() for n in _SAVED] + rope))
         w = Weights(*[weights[n].data_ptr() for n in _WEIGHTS])
         return sv, w
 

@@ -221,6 +221,10 @@ cf_status layer_core(const cf_layer_desc& L, const cf_saved& sv, const cf_weight
                                  w.dk, w.dv, w.attn_ws, st);
     if (as != CF_OK) return as;
 
+    if (sv.rope_cos) {      // transposed rotation of dq and dk at the original positions of the kept rows
+        CF_HIP(launch_rope_bwd(dt, w.dq, idx, N, L.Hq, L.d, L.S, sv.rope_cos, sv.rope_sin, st));
+        CF_HIP(launch_rope_bwd(dt, w.dk, idx, N, L.Hkv, L.d, L.S, sv.rope_cos, sv.rope_sin, st));
+    }
     void* h1 = w.bufHa;
     CF_HIP(launch_rmsnorm_fwd(dt, sv.x, W.g1, idx, N, H, L.rms_eps, h1, st));
     {
@@ -254,7 +258,15 @@ cf_status check_layer_ptrs(const cf_saved* sv, const cf_weights* W, const void* 
     for (const void* p : req) {
         if (misaligned(p)) return CF_ERR_SHAPE;
     }
+    if ((sv->rope_cos == nullptr) != (sv->rope_sin == nullptr)) return CF_ERR_NULL;
+    if (sv->rope_cos && (misaligned(sv->rope_cos) || misaligned(sv->rope_sin))) return CF_ERR_SHAPE;
     return CF_OK;
+}
+
+cf_status check_rope(const cf_layer_desc* L, const cf_saved* sv) {
+    if (!sv->rope_cos) return CF_OK;
+    const int vn = L->dtype == CF_BF16 ? 8 : 4;
+    return (L->d % 2 == 0 && (L->d / 2) % vn == 0) ? CF_OK : CF_ERR_SHAPE;
 }
 
 }  // namespace
@@ -379,6 +391,8 @@ cf_status cf_layer_bwd_filtered(const cf_layer_desc* desc, const cf_saved* saved
     if (s != CF_OK) return s;
     s = check_layer_ptrs(saved, w, dy_full, grads);
     if (s != CF_OK) return s;
+    s = check_rope(desc, saved);
+    if (s != CF_OK) return s;
     if (!mask || !n_kept_host) return CF_ERR_NULL;
     if ((idx_out && misaligned(idx_out, 4)) || (cu_kept_out && misaligned(cu_kept_out, 4)))
         return CF_ERR_SHAPE;
@@ -411,6 +425,8 @@ cf_status cf_layer_bwd_compact(const cf_layer_desc* desc, const cf_saved* saved,
     if (s != CF_OK) return s;
     s = check_layer_ptrs(saved, w, dy_kept, grads);
     if (s != CF_OK) return s;
+    s = check_rope(desc, saved);
+    if (s != CF_OK) return s;
     if (!idx || !cu_kept) return CF_ERR_NULL;
     if (misaligned(idx, 4) || misaligned(cu_kept, 4)) return CF_ERR_SHAPE;
     const int T = desc->B * desc->S;
@@ -427,6 +443,8 @@ cf_status cf_layer_bwd_dense(const cf_layer_desc* desc, const cf_saved* saved, c
     cf_status s = check_layer_desc(desc);
     if (s != CF_OK) return s;
     s = check_layer_ptrs(saved, w, dy_full, grads);
+    if (s != CF_OK) return s;
+    s = check_rope(desc, saved);
     if (s != CF_OK) return s;
     const int T = desc->B * desc->S;
     if (!ws || misaligned(ws, 256)) return CF_ERR_WORKSPACE;

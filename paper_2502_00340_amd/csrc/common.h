@@ -103,6 +103,10 @@ int rmsnorm_bwd_blocks(int n_rows);
 hipError_t launch_rmsnorm_bwd(int dtype, const void* dh, const void* x, const void* g,
                               const int32_t* idx, const void* res, int n_rows, int H, float eps,
                               void* dx_out, float* dg_partial, void* dg_out, hipStream_t st);
+// g[j, h*d + i] (in place, [n_rows, heads*d]): transposed rotary rotation at position idx[j] % S
+// (idx null: j % S); cos, sin are [S, d/2] fp32
+hipError_t launch_rope_bwd(int dtype, void* g, const int32_t* idx, int n_rows, int heads, int d, int S,
+                           const float* cos, const float* sin, hipStream_t st);
 hipError_t launch_attn_rowdot(int dtype, const void* da, const void* a, int n_rows, int Hq, int d,
                               float* D, hipStream_t st);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st);

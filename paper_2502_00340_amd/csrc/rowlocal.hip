@@ -242,6 +242,38 @@ __global__ __launch_bounds__(256) void attn_rowdot_kernel(const T* __restrict__ 
     if (gid < total && (gid % lanes) == 0) D[pair] = s;
 }
 
+// Transposed rotary rotation, in place: for i < d/2 and c = cos[pos,i], s = sin[pos,i]
+//   dx[i] = dy[i]*c + dy[i+d/2]*s,   dx[i+d/2] = dy[i+d/2]*c - dy[i]*s
+// One thread per vector of VN frequencies of one (row, head); d/2 is a multiple of VN.
+template <typename T>
+__global__ __launch_bounds__(256) void rope_bwd_kernel(T* __restrict__ g, const int32_t* __restrict__ idx,
+                                                       int n_rows, int heads, int d, int S,
+                                                       const float* __restrict__ cs,
+                                                       const float* __restrict__ sn) {
+    constexpr int VN = Vec<T>::N;
+    const int half = d / 2, vph = half / VN;            // vectors per head half
+    const int64_t total = (int64_t)n_rows * heads * vph;
+    for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
+        const int iv = (int)(t % vph);
+        const int64_t rh = t / vph;
+        const int h = (int)(rh % heads);
+        const int64_t j = rh / heads;
+        const int pos = (int)((idx ? (int64_t)idx[j] : j) % S);
+        T* p = g + (j * heads + h) * d + iv * VN;
+        float lo[VN], hi[VN], olo[VN], ohi[VN];
+        Vec<T>::load(p, lo);
+        Vec<T>::load(p + half, hi);
+#pragma unroll
+        for (int e = 0; e < VN; ++e) {
+            const float c = cs[(int64_t)pos * half + iv * VN + e], s = sn[(int64_t)pos * half + iv * VN + e];
+            olo[e] = lo[e] * c + hi[e] * s;
+            ohi[e] = hi[e] * c - lo[e] * s;
+        }
+        Vec<T>::store(p, olo);
+        Vec<T>::store(p + half, ohi);
+    }
+}
+
 // ---------------------------------------------------------------------------
 
 static int stream_grid(int64_t vec_total) {
@@ -313,6 +345,19 @@ hipError_t launch_rmsnorm_bwd(int dtype, const void* dh, const void* x, const vo
         rmsnorm_bwd_dispatch<bf16_t>(nv, nblk, st, dh, x, g, idx, res, n_rows, H, eps, dx_out, dg_partial);
         colsum_finish_kernel<bf16_t><<<ceil_div(H, 32), 256, 0, st>>>(dg_partial, nblk, H, (bf16_t*)dg_out);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_rope_bwd(int dtype, void* g, const int32_t* idx, int n_rows, int heads, int d, int S,
+                           const float* cos, const float* sin, hipStream_t st) {
+    if (n_rows <= 0) return hipSuccess;
+    const int vn = dtype == CF_F32 ? 4 : 8;
+    if ((d / 2) % vn != 0) return hipErrorInvalidValue;
+    const int64_t total = (int64_t)n_rows * heads * (d / 2 / vn);
+    if (dtype == CF_F32)
+        rope_bwd_kernel<float><<<stream_grid(total), 256, 0, st>>>((float*)g, idx, n_rows, heads, d, S, cos, sin);
+    else
+        rope_bwd_kernel<bf16_t><<<stream_grid(total), 256, 0, st>>>((bf16_t*)g, idx, n_rows, heads, d, S, cos, sin);
     return hipGetLastError();
 }
 

@@ -208,3 +208,11 @@ def make_independent_activations(shape: LayerShape, rng: np.random.Generator) ->
         "gate": make_normal(rng, shape.T, shape.F),
         "up": make_normal(rng, shape.T, shape.F),
     }
+
+
+def rope_tables(S: int, d: int, base: float = 10000.0):
+    """cos / sin tables [S, d/2] fp32 of the rotary position embedding: angle of
+    position s and frequency i is s * base^(-2i/d)."""
+    inv = base ** (-np.arange(0, d, 2, dtype=np.float64) / d)
+    ang = np.outer(np.arange(S, dtype=np.float64), inv)
+    return np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)

@@ -53,7 +53,7 @@ class Problem:
     storage dtype) plus the oracle's keyword arguments."""
 
     def __init__(self, shape: WL.LayerShape, seed: int, mode: str, mask: np.ndarray | None = None,
-                 rho: float | None = None, oracle_dtype=np.float64):
+                 rho: float | None = None, oracle_dtype=np.float64, rope: bool = False):
         self.shape = shape
         self.dtype = shape.dtype
         rng = np.random.default_rng(seed)
@@ -61,10 +61,13 @@ class Problem:
         self.W = {k: q(v) for k, v in WL.make_weights(shape, rng).items()}
         self.kw = dict(B=shape.B, S=shape.S, Hq=shape.Hq, Hkv=shape.Hkv, d=shape.d)
         scale = 1.0 / math.sqrt(shape.d)
+        # rotary tables (fp32 on both sides); in "independent" mode q and k are drawn directly, which
+        # stands for already rotated tensors
+        self.rope = WL.rope_tables(shape.S, shape.d) if rope else None
         if mode == "consistent":
             x = q(WL.make_normal(rng, shape.T, shape.H))
             _, sv = O.layer_fwd(x.astype(oracle_dtype), {k: v.astype(oracle_dtype) for k, v in self.W.items()},
-                                **self.kw)
+                                rope=self.rope, **self.kw)
             self.saved = {k: (np.asarray(v, dtype=np.float32) if k == "lse" else q(v)) for k, v in sv.items()}
         elif mode == "independent":
             sv = {k: q(v) for k, v in WL.make_independent_activations(shape, rng).items()}
@@ -83,11 +86,14 @@ class Problem:
         dt = self.oracle_dtype
         sv = {k: v.astype(dt) for k, v in self.saved.items()}
         W = {k: v.astype(dt) for k, v in self.W.items()}
-        return O.layer_bwd(sv, W, self.dy.astype(dt), None if dense else self.mask, **self.kw)
+        return O.layer_bwd(sv, W, self.dy.astype(dt), None if dense else self.mask, rope=self.rope, **self.kw)
 
     def device_tensors(self, device="cuda:0"):
         sv = {k: (torch.from_numpy(v).to(device) if k == "lse" else to_dev(v, self.dtype, device))
               for k, v in self.saved.items()}
+        if self.rope is not None:
+            sv["rope_cos"] = torch.from_numpy(self.rope[0]).to(device)
+            sv["rope_sin"] = torch.from_numpy(self.rope[1]).to(device)
         W = {k: to_dev(v, self.dtype, device) for k, v in self.W.items()}
         dy = to_dev(self.dy, self.dtype, device)
         mask = torch.from_numpy(self.mask).to(device)

@@ -105,7 +105,7 @@ def test_attention_argument_errors(L):
 
 def test_layer_argument_errors(L):
     d = _desc()
-    sv = Bn.Saved(*([0x10000] * 9))
+    sv = Bn.Saved(*([0x10000] * 9 + [None, None]))
     w = Bn.Weights(*([0x10000] * 9))
     g = Bn.Grads(*([0x10000] * 10))
     n = C.c_int32(0)
@@ -114,10 +114,12 @@ def test_layer_argument_errors(L):
     assert f(None, C.byref(sv), C.byref(w), FAKE, FAKE, C.byref(g), None, None, C.byref(n), FAKE, ok_ws, None) == 1
     assert f(C.byref(d), C.byref(sv), C.byref(w), FAKE, None, C.byref(g), None, None, C.byref(n), FAKE, ok_ws, None) == 1
     assert f(C.byref(d), C.byref(sv), C.byref(w), FAKE, FAKE, C.byref(g), None, None, None, FAKE, ok_ws, None) == 1
-    sv_bad = Bn.Saved(*([0x10000] * 8 + [0]))
+    sv_bad = Bn.Saved(*([0x10000] * 8 + [0, None, None]))
     assert f(C.byref(d), C.byref(sv_bad), C.byref(w), FAKE, FAKE, C.byref(g), None, None, C.byref(n), FAKE, ok_ws, None) == 1
     assert f(C.byref(d), C.byref(sv), C.byref(w), FAKE, FAKE, C.byref(g), None, None, C.byref(n), FAKE, 16, None) == 4
     assert f(C.byref(_desc(H=250)), C.byref(sv), C.byref(w), FAKE, FAKE, C.byref(g), None, None, C.byref(n), FAKE, ok_ws, None) == 2
+    sv_rope = Bn.Saved(*([0x10000] * 9 + [0x10000, None]))      # one rotary table without the other
+    assert f(C.byref(d), C.byref(sv_rope), C.byref(w), FAKE, FAKE, C.byref(g), None, None, C.byref(n), FAKE, ok_ws, None) == 1
     fc = L.cf_layer_bwd_compact
     assert fc(C.byref(d), C.byref(sv), C.byref(w), FAKE, None, FAKE, 4, C.byref(g), FAKE, ok_ws, None) == 1
     assert fc(C.byref(d), C.byref(sv), C.byref(w), None, FAKE, FAKE, 4, C.byref(g), FAKE, ok_ws, None) == 1

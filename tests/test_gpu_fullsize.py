@@ -17,10 +17,10 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def _run(index, rho=None):
-    shape = WL.CONFIGS[index]
+def _run(index, rho=None, shape=None, rope=False):
+    shape = WL.CONFIGS[index] if shape is None else shape
     print("[case] full size config %d %s rho=%s" % (index, shape.name, rho), flush=True)
-    p = Hn.Problem(shape, WL.config_seed(index), "independent", rho=rho, oracle_dtype=np.float32)
+    p = Hn.Problem(shape, WL.config_seed(index), "independent", rho=rho, oracle_dtype=np.float32, rope=rope)
     sv, W, dy, mask = p.device_tensors(DEV)
     plan = Bn.LayerBackward(p.desc(), device=DEV)
     n = plan.filtered(sv, W, dy, mask)
@@ -67,3 +67,12 @@ def test_config3_llama8b_spans_and_dense():
 
 def test_config4_40b_ragged():
     _run(4)
+
+
+def test_tensor_parallel_share_of_the_8b_layer_with_rotary():
+    """The per-GPU share of the 8B layer under 8-way tensor parallelism (the setting the
+    paper timed that model in): 4 query heads, 1 KV head, F/8 = 1792, full hidden size;
+    skinny projections, and q/k are rotated tensors."""
+    shape = WL.LayerShape("llama31_8b_tp8_share", B=2, S=4096, H=4096, Hq=4, Hkv=1, d=128, F=1792,
+                          dtype="bf16", mask_kind="spans")
+    _run(5, shape=shape, rope=True)

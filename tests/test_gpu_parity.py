@@ -341,3 +341,23 @@ def test_layer_stack_of_two_shares_one_index():
     for k in keep:
         a, b = (plan2.grads[k][:n], keep[k][:n]) if k == "dx" else (plan2.grads[k], keep[k])
         assert torch.equal(a, b), k
+
+
+@pytest.mark.parametrize("dtype,mode", [("f32", "consistent"), ("bf16", "independent")])
+def test_layer_with_rotary_embedding(dtype, mode):
+    """q and k are rotated tensors: the layer applies the transposed rotation to dq and dk at
+    the original positions of the kept rows (filtered and dense calls)."""
+    shape = WL.LayerShape("rope", B=2, S=160, H=256, Hq=4, Hkv=2, d=64, F=384, dtype=dtype)
+    say("layer rotary %s" % dtype)
+    p = Hn.Problem(shape, 31, mode, rho=0.5, rope=True)
+    got, ridx, n = _run_layer(p)
+    ref = p.oracle()
+    errs = Hn.check_layer(p, got, ref, ridx, Hn.TOL[dtype])
+    say("  " + " ".join("%s=%.1e" % kv for kv in errs.items()))
+    gotd, _, _ = _run_layer(p, dense=True)
+    Hn.check_layer(p, gotd, p.oracle(dense=True), None, Hn.TOL[dtype])
+    # the rotation matters: without it dWq is far from the reference
+    p.rope, keep = None, p.rope
+    got0, _, _ = _run_layer(p)
+    p.rope = keep
+    assert Hn.rel_fro(Hn.to_np(got0["dwq"]), ref["dwq"]) > 10 * Hn.TOL[dtype]

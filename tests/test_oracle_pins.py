@@ -83,6 +83,45 @@ def test_dense_backward_matches_finite_differences():
         assert _relerr(got["d" + name], fd) < 1e-6, name
 
 
+def test_rotary_dense_backward_matches_finite_differences():
+    """With rotated q and k the whole-layer backward is still the gradient of the
+    forward (pins the pairing (i, i+d/2), the sign of the transposed rotation and
+    that positions restart at every sequence)."""
+    c, W, x, dy, _ = _tiny_problem(7)
+    kw = _kw(c)
+    rope = tuple(t.astype(np.float64) for t in WL.rope_tables(c["S"], c["d"]))
+    _, saved = O.layer_fwd(x, W, rope=rope, **kw)
+    got = O.layer_bwd(saved, W, dy, None, rope=rope, **kw)
+
+    def loss():
+        yy, _ = O.layer_fwd(x, W, rope=rope, **kw)
+        return float(np.sum(yy * dy))
+
+    assert _relerr(got["dx"], _fd(loss, x)) < 1e-6
+    for name in ("wq", "wk", "wv"):
+        assert _relerr(got["d" + name], _fd(loss, W[name])) < 1e-6, name
+    # without the transposed rotation the projections' gradients are wrong
+    plain = O.layer_bwd(saved, W, dy, None, **kw)
+    assert _relerr(plain["dwq"], got["dwq"]) > 1e-2
+
+
+def test_rotary_rotation_closed_forms():
+    """The rotation is orthogonal (its transpose undoes it), position 0 is the
+    identity, and a single pair at angle a is the 2x2 rotation matrix."""
+    B, S, heads, d = 2, 5, 3, 8
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal((B * S, heads * d))
+    cos, sin = (t.astype(np.float64) for t in WL.rope_tables(S, d))
+    y = O.rope_fwd(x, cos, sin, B, S, heads, d)
+    assert np.allclose(O.rope_bwd(y, cos, sin, B, S, heads, d), x, atol=1e-6)
+    assert np.allclose(y[0], x[0]) and np.allclose(y[S], x[S])         # position 0 of both sequences
+    a = np.arctan2(sin[3, 1], cos[3, 1])
+    got = y[3, [1, 1 + d // 2]]
+    want = np.array([[np.cos(a), -np.sin(a)], [np.sin(a), np.cos(a)]]) @ x[3, [1, 1 + d // 2]]
+    assert np.allclose(got, want, atol=1e-6)
+    assert np.isclose(a, 3.0 * 10000.0 ** (-2.0 / d), atol=1e-6)
+
+
 def test_float32_oracle_agrees_with_float64():
     c, W, x, dy, mask = _tiny_problem(2)
     kw = _kw(c)
