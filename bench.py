@@ -215,6 +215,35 @@ def parts_leg(shape: WL.LayerShape, sv, W, dy, mask: np.ndarray, mask_dev, reps:
     return out
 
 
+def context_sweep_leg(base: WL.LayerShape, steps: int, warmup: int):
+    """Filtered vs dense layer backward at a fixed token count T and keep ratio 0.5 for context
+    lengths from 1K to 8K (the paper's context-length experiment, Sec. 5.3, at layer level), and a
+    fine keep-ratio sweep at the base context length."""
+    import dataclasses
+    out = {"by_context": {}, "by_ratio": {}}
+    T = base.T
+    for S in (1024, 2048, 4096, 8192):
+        shape = dataclasses.replace(base, B=T // S, S=S, mask_kind="topk")
+        W, sv, dy, mask, rng = make_inputs(shape, 7)
+        md = torch.from_numpy(mask).to(DEV)
+        desc = Bn.make_desc(shape.B, shape.S, shape.H, shape.Hq, shape.Hkv, shape.d, shape.F, shape.dtype)
+        plan = Bn.LayerBackward(desc, device=DEV)
+        t_f = time_steps(lambda: plan.filtered(sv, W, dy, md), steps, warmup)
+        t_d = time_steps(lambda: plan.dense(sv, W, dy), steps, warmup)
+        out["by_context"][str(S)] = {"B": shape.B, "filtered_ms": round(t_f * 1e3, 4), "dense_ms": round(t_d * 1e3, 4),
+                                     "speedup": round(t_d / t_f, 4)}
+        log("context %d: filtered %.3f ms dense %.3f ms speedup %.3f" % (S, t_f * 1e3, t_d * 1e3, t_d / t_f))
+        if S == base.S:
+            for rho in (0.1, 0.2, 0.3, 0.4, 0.5, 0.6, 0.7, 0.8, 0.9, 1.0):
+                m = WL.mask_topk(rng, shape.B, shape.S, rho)
+                mdd = torch.from_numpy(m).to(DEV)
+                t = time_steps(lambda: plan.filtered(sv, W, dy, mdd), steps, warmup)
+                out["by_ratio"]["%.1f" % rho] = {"ms": round(t * 1e3, 4), "speedup": round(t_d / t, 4)}
+        del plan, W, sv, dy
+        torch.cuda.empty_cache()
+    return out
+
+
 def cpu_baseline_leg(shape: WL.LayerShape, W, sv, dy, mask):
     """The CPU oracle (fp32 arrays, numpy) on the same workload (the whole batch
     is a bounded sample already: about ten seconds of host time)."""
@@ -245,6 +274,8 @@ def main():
     ap.add_argument("--no-sweep", action="store_true", help="skip the keep-ratio sweep")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-parts", action="store_true", help="skip the per-part timings")
+    ap.add_argument("--context-sweep", action="store_true",
+                    help="also time context lengths 1K..8K at fixed token count and keep ratios 0.1..1.0 (slow)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU only (collectives and sharding are out of scope); "
@@ -295,6 +326,10 @@ def main():
     if not a.no_parts:
         log("per-part timings")
         parts = parts_leg(shape, sv, W, dy, mask, mask_dev)
+    ctx = None
+    if a.context_sweep:
+        log("context-length and keep-ratio sweeps")
+        ctx = context_sweep_leg(shape, a.steps, a.warmup)
     log("roofline leg")
     roof = roofline_leg(shape, n_k)
     cpu = None
@@ -320,6 +355,7 @@ def main():
         "dense_algorithmic_tflops": round(flops_d / t_d / 1e12, 1),
         "keep_ratio_sweep": sweep,
         "parts": parts,
+        "context_sweep": ctx,
         "roofline": roof,
         "cpu_baseline": cpu,
     }
