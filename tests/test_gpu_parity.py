@@ -361,3 +361,37 @@ def test_layer_with_rotary_embedding(dtype, mode):
     got0, _, _ = _run_layer(p)
     p.rope = keep
     assert Hn.rel_fro(Hn.to_np(got0["dwq"]), ref["dwq"]) > 10 * Hn.TOL[dtype]
+
+
+def test_no_write_outside_the_outputs_and_the_workspace():
+    """Every output tensor and the workspace sit inside a larger allocation filled with a
+    sentinel; after filtered, compact and dense calls on a ragged shape (no dimension a tile
+    multiple) the guard bands are untouched."""
+    shape = WL.LayerShape("guard", B=3, S=200, H=264, Hq=6, Hkv=2, d=64, F=520, dtype="bf16")
+    say("guard bands")
+    p = Hn.Problem(shape, 41, "independent", rho=0.37)
+    sv, W, dy, mask = p.device_tensors(DEV)
+    desc = p.desc()
+    plan = Bn.LayerBackward(desc, device=DEV)
+    PAD = 4096                                      # bytes on each side
+    raw = {}
+
+    def guarded(t):
+        nbytes = t.numel() * t.element_size()
+        buf = torch.full((nbytes + 2 * PAD,), 0xA5, dtype=torch.uint8, device=DEV)
+        view = buf[PAD:PAD + nbytes].view(t.dtype).view(t.shape)
+        return buf, view
+
+    for name in list(plan.grads):
+        raw[name], plan.grads[name] = guarded(plan.grads[name])
+    raw["idx"], plan.idx = guarded(plan.idx)
+    raw["cu"], plan.cu_kept = guarded(plan.cu_kept)
+    raw["ws"], plan.ws = guarded(plan.ws)
+    plan._g = Bn.Grads(*[plan.grads[n].data_ptr() for n, _ in Bn.Grads._fields_])
+    n = plan.filtered(sv, W, dy, mask)
+    dyk = Bn.gather_rows(dy, plan.idx, n)
+    plan.compact(sv, W, dyk, plan.idx, plan.cu_kept, n)
+    plan.dense(sv, W, dy)
+    torch.cuda.synchronize()
+    for name, buf in raw.items():
+        assert bool((buf[:PAD] == 0xA5).all()) and bool((buf[-PAD:] == 0xA5).all()), name
