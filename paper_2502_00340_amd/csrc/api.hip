@@ -227,13 +227,20 @@ cf_status layer_core(const cf_layer_desc& L, const cf_saved& sv, const cf_weight
     }
     void* h1 = w.bufHa;
     CF_HIP(launch_rmsnorm_fwd(dt, sv.x, W.g1, idx, N, H, L.rms_eps, h1, st));
-    {
-        GemmSeg s{h1, w.dq, N};
-        CF_HIP(launch_gemm(dt, 1, &s, 1, G.dwq, H, Nq, 0.f, st));
-        GemmSeg s2{h1, w.dk, N};
-        CF_HIP(launch_gemm(dt, 1, &s2, 1, G.dwk, H, Nkv, 0.f, st));
-        GemmSeg s3{h1, w.dv, N};
-        CF_HIP(launch_gemm(dt, 1, &s3, 1, G.dwv, H, Nkv, 0.f, st));
+    {   // dWq, dWk, dWv = h1^T * dq, dk, dv: one launch when the column groups fall on tile boundaries
+        const int Ng[3] = {Nq, Nkv, Nkv};
+        if (N > 0 && gemm_tn_groups_supported(dt, N, 3, Ng)) {
+            const void* Bg[3] = {w.dq, w.dk, w.dv};
+            void* Cg[3] = {G.dwq, G.dwk, G.dwv};
+            CF_HIP(launch_gemm_tn_groups(h1, N, H, 3, Bg, Cg, Ng, st));
+        } else {
+            GemmSeg s{h1, w.dq, N};
+            CF_HIP(launch_gemm(dt, 1, &s, 1, G.dwq, H, Nq, 0.f, st));
+            GemmSeg s2{h1, w.dk, N};
+            CF_HIP(launch_gemm(dt, 1, &s2, 1, G.dwk, H, Nkv, 0.f, st));
+            GemmSeg s3{h1, w.dv, N};
+            CF_HIP(launch_gemm(dt, 1, &s3, 1, G.dwv, H, Nkv, 0.f, st));
+        }
     }
     void* dh1 = w.bufHb;
     {   // dh1 = dq*Wq^T + dk*Wk^T + dv*Wv^T

@@ -123,4 +123,10 @@ struct GemmSeg {
 hipError_t launch_gemm(int dtype, int mode, const GemmSeg* segs, int nseg, void* C, int M, int N,
                        float beta, hipStream_t st);
 
+// One TN launch for up to three products that share A [K,M]: C_j [M,Ng[j]] = A^T * B_j [K,Ng[j]].
+// bf16 only, every Ng[j] a multiple of 256 (gemm_tn_groups_supported says whether it applies).
+bool gemm_tn_groups_supported(int dtype, int K, int ngroups, const int* Ng);
+hipError_t launch_gemm_tn_groups(const void* A, int K, int M, int ngroups, const void* const* Bg,
+                                 void* const* Cg, const int* Ng, hipStream_t st);
+
 }  // namespace cf

@@ -62,6 +62,14 @@ struct GemmArgs {
     float beta;
     int n_full;     // leading blocks that own a whole 256x256 tile
     int sub;        // the remaining tiles are cut into `sub` (1, 2 or 4) sub-tiles, one block each
+    // Column groups (ngroups > 1, one K segment): output columns [off_j, off_j + Ng[j]) belong to a
+    // matrix of their own, C = Cg[j] [M, Ng[j]] with B operand Bg[j]; every Ng[j] is a multiple of
+    // 256, so a tile lies in one group.  N is the sum of the Ng.  One launch then covers several
+    // products that share their A operand (the dW of the q, k and v projections).
+    int ngroups;
+    const void* Bg[3];
+    void* Cg[3];
+    int Ng[3];
 };
 
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4_t;
@@ -380,6 +388,15 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
         n0 = bn * 256 + (cut == 4 ? (part & 1) * 128 : (cut == 2 ? part * 128 : 0));
         if (m0 >= g.M || n0 >= g.N) return;
     }
+    if (g.ngroups > 1) {
+        // the tile's column group: rebase the B operand, the output and the column range on it
+        const int j = n0 < g.Ng[0] ? 0 : (n0 < g.Ng[0] + g.Ng[1] ? 1 : 2);
+        const int off = j == 0 ? 0 : (j == 1 ? g.Ng[0] : g.Ng[0] + g.Ng[1]);
+        g.B[0] = j == 0 ? g.Bg[0] : (j == 1 ? g.Bg[1] : g.Bg[2]);
+        g.C = j == 0 ? g.Cg[0] : (j == 1 ? g.Cg[1] : g.Cg[2]);
+        g.N = j == 0 ? g.Ng[0] : (j == 1 ? g.Ng[1] : g.Ng[2]);
+        n0 -= off;
+    }
     if (cut == 1) gemm_tile<MODE, 4, 4>(g, m0, n0, smem);
     else if (cut == 2) gemm_tile<MODE, 4, 2>(g, m0, n0, smem);
     else gemm_tile<MODE, 2, 2>(g, m0, n0, smem);
@@ -509,6 +526,8 @@ hipError_t launch_gemm(int dtype, int mode, const GemmSeg* segs, int nseg, void*
     }
     for (int s = g.nseg; s < 3; ++s) { g.A[s] = nullptr; g.B[s] = nullptr; g.K[s] = 0; }
     g.C = C; g.M = M; g.N = N; g.beta = beta; g.n_full = 0; g.sub = 1;
+    g.ngroups = 1;
+    for (int j = 0; j < 3; ++j) { g.Bg[j] = nullptr; g.Cg[j] = nullptr; g.Ng[j] = 0; }
     if (g.nseg == 0) {
         // empty contraction: C = beta*C; only beta in {0,1} is supported by the API
         if (beta == 0.f) return launch_fill_zero(C, (size_t)M * N * dtype_size(dtype), st);
@@ -527,6 +546,33 @@ hipError_t launch_gemm(int dtype, int mode, const GemmSeg* segs, int nseg, void*
         return hipGetLastError();
     }
     return mode == 0 ? launch_bf16<0>(g, st) : launch_bf16<1>(g, st);
+}
+
+bool gemm_tn_groups_supported(int dtype, int K, int ngroups, const int* Ng) {
+    if (dtype != CF_BF16 || K <= 0 || ngroups < 2 || ngroups > 3) return false;
+    for (int j = 0; j < ngroups; ++j)
+        if (Ng[j] <= 0 || Ng[j] % 256 != 0) return false;
+    return true;
+}
+
+hipError_t launch_gemm_tn_groups(const void* A, int K, int M, int ngroups, const void* const* Bg,
+                                 void* const* Cg, const int* Ng, hipStream_t st) {
+    if (M <= 0) return hipSuccess;
+    GemmArgs g;
+    int N = 0;
+    for (int j = 0; j < 3; ++j) {
+        g.Bg[j] = j < ngroups ? Bg[j] : nullptr;
+        g.Cg[j] = j < ngroups ? Cg[j] : nullptr;
+        g.Ng[j] = j < ngroups ? Ng[j] : 0;
+        N += g.Ng[j];
+        if ((int64_t)g.Ng[j] * K * 2 >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
+    }
+    if ((int64_t)M * K * 2 >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
+    g.ngroups = ngroups;
+    g.A[0] = A; g.B[0] = Bg[0]; g.K[0] = K; g.nseg = 1;
+    for (int s = 1; s < 3; ++s) { g.A[s] = nullptr; g.B[s] = nullptr; g.K[s] = 0; }
+    g.C = Cg[0]; g.M = M; g.N = N; g.beta = 0.f; g.n_full = 0; g.sub = 1;
+    return launch_bf16<1>(g, st);
 }
 
 }  // namespace cf

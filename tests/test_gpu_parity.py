@@ -254,7 +254,11 @@ def test_layer_config0_tiny_fp32(mode):
     Hn.check_layer(p, gotd, p.oracle(dense=True), None, Hn.TOL["f32"])
 
 
-@pytest.mark.parametrize("shape", [SMALL_BF16, SMALL_BF16_D128], ids=lambda s: s.name)
+# Hq*d and Hkv*d multiples of 256: the three projection dW run as one grouped launch
+SMALL_BF16_GROUPED = WL.LayerShape("small_bf16_grouped", B=2, S=192, H=320, Hq=8, Hkv=4, d=64, F=384, dtype="bf16")
+
+
+@pytest.mark.parametrize("shape", [SMALL_BF16, SMALL_BF16_D128, SMALL_BF16_GROUPED], ids=lambda s: s.name)
 @pytest.mark.parametrize("rho", [0.5, 0.3])
 def test_layer_small_bf16(shape, rho):
     say("layer %s rho=%g" % (shape.name, rho))
