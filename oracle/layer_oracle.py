@@ -144,20 +144,32 @@ def rope_bwd(dy, cos, sin, B, S, heads, d):
     return out
 
 
-def layer_fwd(x, W, B, S, Hq, Hkv, d, eps=1e-5, scale=None, rope=None):
+def lora_linear(x, w, lora, p):
+    """Y = X W, plus the low-rank adapter s * (X a_p) b_p when `lora` is given
+    (Sec. 5.3: rank-64 adapters on the q, k, v and o projections; the paper gives
+    no formula, this is the standard LoRA form).  lora: dict with a<p> [in,r],
+    b<p> [r,out] and "scale"."""
+    y = x @ w
+    if lora is not None:
+        y = y + (x @ lora["a" + p]) @ lora["b" + p] * x.dtype.type(lora["scale"])
+    return y
+
+
+def layer_fwd(x, W, B, S, Hq, Hkv, d, eps=1e-5, scale=None, rope=None, lora=None):
     """Decoder-layer forward.  Returns (y, saved) where saved holds exactly the
     tensors the backward is given: x, q, k, v, attn_out, lse, r, gate, up.
-    rope: None or (cos, sin) tables [S, d/2]; q and k in `saved` are rotated."""
+    rope: None or (cos, sin) tables [S, d/2]; q and k in `saved` are rotated.
+    lora: None or the adapters of the q, k, v, o projections (see lora_linear)."""
     scale = (1.0 / np.sqrt(d)) if scale is None else scale
     h1, _ = rmsnorm_fwd(x, W["g1"], eps)
-    q = h1 @ W["wq"]
-    k = h1 @ W["wk"]
-    v = h1 @ W["wv"]
+    q = lora_linear(h1, W["wq"], lora, "q")
+    k = lora_linear(h1, W["wk"], lora, "k")
+    v = lora_linear(h1, W["wv"], lora, "v")
     if rope is not None:
         q = rope_fwd(q, rope[0], rope[1], B, S, Hq, d)
         k = rope_fwd(k, rope[0], rope[1], B, S, Hkv, d)
     a, lse = attn_fwd(q, k, v, B, S, Hq, Hkv, d, scale)
-    r = x + a @ W["wo"]
+    r = x + lora_linear(a, W["wo"], lora, "o")
     h2, _ = rmsnorm_fwd(r, W["g2"], eps)
     gate = h2 @ W["wg"]
     up = h2 @ W["wu"]
@@ -240,7 +252,20 @@ def attn_bwd(q, k, v, attn_out, lse, da, B, S, Hq, Hkv, d, scale, keep=None):
 # whole layer
 # ---------------------------------------------------------------------------
 
-def layer_bwd(saved, W, dy, mask, B, S, Hq, Hkv, d, eps=1e-5, scale=None, rope=None):
+def lora_linear_bwd(x, dy, w, lora, p):
+    """Backward of lora_linear: returns (dX, dW, da, db); da, db are None without
+    an adapter.  dX = dY W^T + s (dY b^T) a^T, da = s X^T (dY b^T), db = s (X a)^T dY."""
+    dx, dw = linear_bwd(x, dy, w)
+    if lora is None:
+        return dx, dw, None, None
+    a, b = lora["a" + p], lora["b" + p]
+    sc = x.dtype.type(lora["scale"])
+    t = dy @ b.T
+    dx = dx + (t @ a.T) * sc
+    return dx, dw, (x.T @ t) * sc, ((x @ a).T @ dy) * sc
+
+
+def layer_bwd(saved, W, dy, mask, B, S, Hq, Hkv, d, eps=1e-5, scale=None, rope=None, lora=None):
     """Token-filtered backward of one decoder layer.
 
     saved: dict from layer_fwd (x, q, k, v, attn_out, lse, r, gate, up), or
@@ -249,7 +274,10 @@ def layer_bwd(saved, W, dy, mask, B, S, Hq, Hkv, d, eps=1e-5, scale=None, rope=N
     the dense backward.  Returns a dict: dx [T,H] (zero on filtered rows),
     dwq, dwk, dwv, dwo, dwg, dwu, dwd, dg1, dg2.  Normalised activations and
     the SwiGLU product are rebuilt from the saved tensors, as the HIP path has
-    to do as well.  rope: None or (cos, sin) [S, d/2] when saved q, k are rotated."""
+    to do as well.  rope: None or (cos, sin) [S, d/2] when saved q, k are rotated.
+    lora: None or the adapters of the q, k, v, o projections; then the result also
+    holds daq, dbq, ..., dao, dbo and dx includes the adapter paths (the base
+    weight gradients are still returned; a LoRA trainer ignores them)."""
     scale = (1.0 / np.sqrt(d)) if scale is None else scale
     x, r, gate, up = saved["x"], saved["r"], saved["gate"], saved["up"]
     a = saved["attn_out"]
@@ -272,20 +300,21 @@ def layer_bwd(saved, W, dy, mask, B, S, Hq, Hkv, d, eps=1e-5, scale=None, rope=N
     dr = dy + dr_n
 
     # attention block:  r = x + attn_out @ Wo
-    da, dwo = linear_bwd(a, dr, W["wo"])
+    da, dwo, dao, dbo = lora_linear_bwd(a, dr, W["wo"], lora, "o")
     dq, dk, dv = attn_bwd(saved["q"], saved["k"], saved["v"], a, saved["lse"], da,
                           B, S, Hq, Hkv, d, scale, keep=keep)       # masking point (2)
     if rope is not None:        # saved q, k are the rotated tensors: undo the rotation on their gradients
         dq = rope_bwd(dq, rope[0], rope[1], B, S, Hq, d)
         dk = rope_bwd(dk, rope[0], rope[1], B, S, Hkv, d)
     h1, _ = rmsnorm_fwd(x, W["g1"], eps)
-    dh1_q, dwq = linear_bwd(h1, dq, W["wq"])
-    dh1_k, dwk = linear_bwd(h1, dk, W["wk"])
-    dh1_v, dwv = linear_bwd(h1, dv, W["wv"])
+    dh1_q, dwq, daq, dbq = lora_linear_bwd(h1, dq, W["wq"], lora, "q")
+    dh1_k, dwk, dak, dbk = lora_linear_bwd(h1, dk, W["wk"], lora, "k")
+    dh1_v, dwv, dav, dbv = lora_linear_bwd(h1, dv, W["wv"], lora, "v")
     dx_n, dg1 = rmsnorm_bwd(dh1_q + dh1_k + dh1_v, x, W["g1"], eps)
     dx = dr + dx_n
+    extra = {} if lora is None else dict(daq=daq, dbq=dbq, dak=dak, dbk=dbk, dav=dav, dbv=dbv, dao=dao, dbo=dbo)
     return dict(dx=dx, dwq=dwq, dwk=dwk, dwv=dwv, dwo=dwo, dwg=dwg, dwu=dwu, dwd=dwd,
-                dg1=dg1, dg2=dg2,
+                dg1=dg1, dg2=dg2, **extra,
                 # intermediates, exposed for the per-entry-point parity tests
                 _dr=dr, _da=da, _dq=dq, _dk=dk, _dv=dv)
 

@@ -216,3 +216,16 @@ def rope_tables(S: int, d: int, base: float = 10000.0):
     inv = base ** (-np.arange(0, d, 2, dtype=np.float64) / d)
     ang = np.outer(np.arange(S, dtype=np.float64), inv)
     return np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
+
+
+def make_lora(shape: LayerShape, rng: np.random.Generator, rank: int = 64, alpha: float = 128.0) -> dict:
+    """Low-rank adapters of the q, k, v, o projections (the paper's LoRA setting:
+    rank 64 on the attention projections): a_p [in, rank], b_p [rank, out],
+    both N(0, 0.02^2) so that every gradient path carries signal (a trained
+    adapter has a non-zero b), scale = alpha / rank."""
+    dims = {"q": (shape.H, shape.Nq), "k": (shape.H, shape.Nkv), "v": (shape.H, shape.Nkv), "o": (shape.Nq, shape.H)}
+    out = {"scale": float(alpha) / rank, "rank": rank}
+    for p, (i, o) in dims.items():
+        out["a" + p] = rng.standard_normal((i, rank), dtype=np.float32) * np.float32(0.02)
+        out["b" + p] = rng.standard_normal((rank, o), dtype=np.float32) * np.float32(0.02)
+    return out

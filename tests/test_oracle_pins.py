@@ -122,6 +122,42 @@ def test_rotary_rotation_closed_forms():
     assert np.isclose(a, 3.0 * 10000.0 ** (-2.0 / d), atol=1e-6)
 
 
+def test_lora_backward_matches_finite_differences():
+    """Adapters on q, k, v, o: the adapter gradients and dx are the gradient of
+    the forward with adapters (dense mode), and they change when rows are filtered."""
+    c, W, x, dy, mask = _tiny_problem(11)
+    kw = _kw(c)
+    rng = np.random.default_rng(5)
+    shape = WL.LayerShape("t", B=c["B"], S=c["S"], H=c["H"], Hq=c["Hq"], Hkv=c["Hkv"], d=c["d"], F=c["F"], dtype="f32")
+    lora = {k: (np.asarray(v, dtype=np.float64) * 10.0 if isinstance(v, np.ndarray) else v)
+            for k, v in WL.make_lora(shape, rng, rank=4, alpha=6.0).items()}
+    _, saved = O.layer_fwd(x, W, lora=lora, **kw)
+    got = O.layer_bwd(saved, W, dy, None, lora=lora, **kw)
+
+    def loss():
+        yy, _ = O.layer_fwd(x, W, lora=lora, **kw)
+        return float(np.sum(yy * dy))
+
+    assert _relerr(got["dx"], _fd(loss, x)) < 1e-6
+    for p in "qkvo":
+        assert _relerr(got["da" + p], _fd(loss, lora["a" + p])) < 1e-6, "a" + p
+        assert _relerr(got["db" + p], _fd(loss, lora["b" + p])) < 1e-6, "b" + p
+    assert _relerr(got["dwq"], _fd(loss, W["wq"])) < 1e-6
+    # a zero b makes the adapter a no-op for dx and da, but db is still live
+    zero_b = dict(lora, bq=np.zeros_like(lora["bq"]), bk=np.zeros_like(lora["bk"]),
+                  bv=np.zeros_like(lora["bv"]), bo=np.zeros_like(lora["bo"]))
+    _, saved0 = O.layer_fwd(x, W, lora=zero_b, **kw)
+    g0 = O.layer_bwd(saved0, W, dy, None, lora=zero_b, **kw)
+    plain = O.layer_bwd(saved0, W, dy, None, **kw)
+    assert np.array_equal(g0["dx"], plain["dx"]) and not np.any(g0["daq"]) and np.any(g0["dbq"])
+    # filtered: rows of filtered tokens contribute nothing to the adapter gradients
+    gf = O.layer_bwd(saved, W, dy, mask, lora=lora, **kw)
+    keep = mask.reshape(-1).astype(np.float64)[:, None]
+    h1, _ = O.rmsnorm_fwd(x, W["g1"], 1e-5)
+    assert np.allclose(gf["dbq"], ((h1 @ lora["aq"]).T @ (gf["_dq"] * keep)) * lora["scale"], atol=1e-12)
+    assert _relerr(gf["dbq"], got["dbq"]) > 1e-2
+
+
 def test_float32_oracle_agrees_with_float64():
     c, W, x, dy, mask = _tiny_problem(2)
     kw = _kw(c)
