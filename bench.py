@@ -244,6 +244,19 @@ def context_sweep_leg(base: WL.LayerShape, steps: int, warmup: int):
     return out
 
 
+def lora_leg(shape: WL.LayerShape, sv, W, dy, mask_dev, rng, steps: int, warmup: int, rank: int = 64):
+    """The LoRA regime of the paper (rank-64 adapters on q, k, v, o; base weights frozen): filtered
+    vs dense cf_layer_bwd_lora on the same layer."""
+    lo = {k: (to_dev(v, shape.dtype) if isinstance(v, np.ndarray) else v)
+          for k, v in WL.make_lora(shape, rng, rank=rank, alpha=2.0 * rank).items()}
+    desc = Bn.make_desc(shape.B, shape.S, shape.H, shape.Hq, shape.Hkv, shape.d, shape.F, shape.dtype)
+    plan = Bn.LoraBackward(desc, rank, device=DEV)
+    t_f = time_steps(lambda: plan.run(sv, W, lo, dy, mask_dev), steps, warmup)
+    t_d = time_steps(lambda: plan.run(sv, W, lo, dy, None), steps, warmup)
+    return {"rank": rank, "filtered_ms": round(t_f * 1e3, 4), "dense_ms": round(t_d * 1e3, 4),
+            "speedup": round(t_d / t_f, 4)}
+
+
 def cpu_baseline_leg(shape: WL.LayerShape, W, sv, dy, mask):
     """The CPU oracle (fp32 arrays, numpy) on the same workload (the whole batch
     is a bounded sample already: about ten seconds of host time)."""
@@ -274,6 +287,7 @@ def main():
     ap.add_argument("--no-sweep", action="store_true", help="skip the keep-ratio sweep")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-parts", action="store_true", help="skip the per-part timings")
+    ap.add_argument("--lora", action="store_true", help="also time the LoRA-adapted layer backward (rank 64)")
     ap.add_argument("--context-sweep", action="store_true",
                     help="also time context lengths 1K..8K at fixed token count and keep ratios 0.1..1.0 (slow)")
     a = ap.parse_args()
@@ -330,6 +344,11 @@ def main():
     if a.context_sweep:
         log("context-length and keep-ratio sweeps")
         ctx = context_sweep_leg(shape, a.steps, a.warmup)
+    lora = None
+    if a.lora:
+        log("LoRA leg")
+        lora = lora_leg(shape, sv, W, dy, mask_dev, rng, a.steps, a.warmup)
+        log("LoRA: filtered %.3f ms dense %.3f ms speedup %.3f" % (lora["filtered_ms"], lora["dense_ms"], lora["speedup"]))
     log("roofline leg")
     roof = roofline_leg(shape, n_k)
     cpu = None
@@ -356,6 +375,7 @@ def main():
         "keep_ratio_sweep": sweep,
         "parts": parts,
         "context_sweep": ctx,
+        "lora": lora,
         "roofline": roof,
         "cpu_baseline": cpu,
     }

@@ -193,6 +193,39 @@ cf_status cf_layer_bwd_dense(const cf_layer_desc* desc, const cf_saved* saved,
                              const cf_weights* w, const void* dy_full, cf_grads* grads,
                              void* ws, size_t ws_bytes, cf_stream stream);
 
+/* ---- low-rank adapters (Sec. 5.3: LoRA, rank 64, on the q, k, v and o projections) --------
+ * The adapted projection is Y = X*W + scale * (X*a)*b with a [in, rank], b [rank, out]; the base
+ * weights and the RMSNorm gains are frozen, so the call produces no gradient for them: every
+ * linear layer only hands its input gradient on (reduced GEMM dX), and the adapters get
+ *   da = scale * X_kept^T * (dY_kept * b^T),   db = scale * (X_kept * a)^T * dY_kept,
+ * with dX_kept = dY_kept*W^T + scale * (dY_kept*b^T)*a^T.  Saved q, k, v, attn_out, r are the
+ * tensors of the adapted forward.  rank must be a multiple of 8 (CF_BF16) or 4 (CF_F32). */
+typedef struct {
+    const void *aq, *bq;   /* [H,rank],    [rank,Hq*d]  */
+    const void *ak, *bk;   /* [H,rank],    [rank,Hkv*d] */
+    const void *av, *bv;   /* [H,rank],    [rank,Hkv*d] */
+    const void *ao, *bo;   /* [Hq*d,rank], [rank,H]     */
+    int32_t rank;
+    float scale;           /* usually lora_alpha / rank */
+} cf_lora;
+
+/* Adapter gradients have the shapes of the adapters and are overwritten; dx is compact
+ * [N_k,H] (or [T,H] when every token is kept because mask is NULL). */
+typedef struct {
+    void *daq, *dbq, *dak, *dbk, *dav, *dbv, *dao, *dbo;
+    void *dx;
+} cf_lora_grads;
+
+/* cf_layer_bwd_lora: the filtered layer backward of a LoRA-adapted layer.  Arguments as for
+ * cf_layer_bwd_filtered; mask == NULL means "every token kept" (no index, no gather, no host
+ * synchronisation: the dense LoRA backward of the same library, and n_kept_host may be NULL).
+ * ws must hold cf_lora_workspace_bytes(desc, rank, max_kept) bytes. */
+size_t cf_lora_workspace_bytes(const cf_layer_desc* desc, int32_t rank, int32_t max_kept);
+cf_status cf_layer_bwd_lora(const cf_layer_desc* desc, const cf_saved* saved, const cf_weights* w,
+                            const cf_lora* lora, const void* dy_full, const uint8_t* mask,
+                            cf_lora_grads* grads, int32_t* idx_out, int32_t* cu_kept_out,
+                            int32_t* n_kept_host, void* ws, size_t ws_bytes, cf_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

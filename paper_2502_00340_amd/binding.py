@@ -23,6 +23,7 @@ EXPORTS = (
     "cf_status_str", "cf_version", "cf_index_workspace_bytes", "cf_build_keep_index", "cf_gather_rows",
     "cf_linear_bwd_reduced", "cf_attn_workspace_bytes", "cf_attn_bwd_filtered",
     "cf_layer_workspace_bytes", "cf_layer_bwd_filtered", "cf_layer_bwd_compact", "cf_layer_bwd_dense",
+    "cf_lora_workspace_bytes", "cf_layer_bwd_lora",
 )
 
 
@@ -49,6 +50,17 @@ class Weights(C.Structure):
 
 class Grads(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("dwq", "dwk", "dwv", "dwo", "dwg", "dwu", "dwd", "dg1", "dg2", "dx")]
+
+
+_LORA_T = ("aq", "bq", "ak", "bk", "av", "bv", "ao", "bo")
+
+
+class Lora(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _LORA_T] + [("rank", C.c_int32), ("scale", C.c_float)]
+
+
+class LoraGrads(C.Structure):
+    _fields_ = [("d" + n, C.c_void_p) for n in _LORA_T] + [("dx", C.c_void_p)]
 
 
 _lib = None
@@ -91,6 +103,11 @@ def lib() -> C.CDLL:
     L.cf_layer_bwd_dense.restype = C.c_int
     L.cf_layer_bwd_dense.argtypes = [C.POINTER(LayerDesc), C.POINTER(Saved), C.POINTER(Weights), vp,
                                      C.POINTER(Grads), vp, sz, vp]
+    L.cf_lora_workspace_bytes.restype = sz
+    L.cf_lora_workspace_bytes.argtypes = [C.POINTER(LayerDesc), i32, i32]
+    L.cf_layer_bwd_lora.restype = C.c_int
+    L.cf_layer_bwd_lora.argtypes = [C.POINTER(LayerDesc), C.POINTER(Saved), C.POINTER(Weights), C.POINTER(Lora), vp,
+                                    vp, C.POINTER(LoraGrads), vp, vp, C.POINTER(i32), vp, sz, vp]
     _lib = L
     return L
 
@@ -279,3 +296,38 @@ def layer_bwd_dense(desc, saved, weights, dy):
     plan = LayerBackward(desc, device=dy.device)
     plan.dense(saved, weights, dy)
     return dict(plan.grads)
+
+
+class LoraBackward(LayerBackward):
+    """Pre-allocated adapter gradients + workspace for cf_layer_bwd_lora (base weights frozen)."""
+
+    def __init__(self, desc: LayerDesc, rank: int, device="cuda:0"):
+        self.desc = desc
+        self.device = torch.device(device)
+        self.rank = rank
+        dt = torch_dtype(desc)
+        T = desc.B * desc.S
+        H, Nq, Nkv = desc.H, desc.Hq * desc.d, desc.Hkv * desc.d
+        e = lambda *s: torch.empty(s, dtype=dt, device=self.device)
+        self.grads = dict(daq=e(H, rank), dbq=e(rank, Nq), dak=e(H, rank), dbk=e(rank, Nkv), dav=e(H, rank),
+                          dbv=e(rank, Nkv), dao=e(Nq, rank), dbo=e(rank, H), dx=e(T, H))
+        self.idx = torch.empty(T, dtype=torch.int32, device=self.device)
+        self.cu_kept = torch.empty(desc.B + 1, dtype=torch.int32, device=self.device)
+        self.ws_bytes = lib().cf_lora_workspace_bytes(C.byref(desc), rank, T)
+        if self.ws_bytes == 0:
+            raise CfError(2, "cf_lora_workspace_bytes")
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=self.device)
+        self._g = LoraGrads(*[self.grads[n].data_ptr() for n, _ in LoraGrads._fields_])
+        self._n_host = torch.empty(1, dtype=torch.int32).pin_memory()
+
+    def run(self, saved: dict, weights: dict, lora: dict, dy: torch.Tensor, mask: torch.Tensor | None) -> int:
+        """mask None: every token kept (the dense LoRA backward).  Returns N_k."""
+        sv, w = self._pack(saved, weights)
+        lo = Lora(*([lora[n].data_ptr() for n in _LORA_T] + [self.rank, float(lora["scale"])]))
+        self._n_host[0] = -1
+        _check(lib().cf_layer_bwd_lora(C.byref(self.desc), C.byref(sv), C.byref(w), C.byref(lo), _ptr(dy),
+                                       _ptr(mask), C.byref(self._g), _ptr(self.idx), _ptr(self.cu_kept),
+                                       C.cast(self._n_host.data_ptr(), C.POINTER(C.c_int32)), _ptr(self.ws),
+                                       self.ws_bytes, _stream()),
+               "cf_layer_bwd_lora")
+        return int(self._n_host[0])

@@ -253,6 +253,134 @@ cf_status layer_core(const cf_layer_desc& L, const cf_saved& sv, const cf_weight
     return CF_OK;
 }
 
+// ---- LoRA-adapted layer: base weights and gains frozen, adapters on q, k, v, o ---------------
+struct LoraWs {
+    LayerWs base;
+    void *a_t;                  // [rank, max(H, Nq)]  transposed adapter
+    void *u;                    // [N, rank]           scale * X * a
+    void *tq, *tk, *tv, *to;    // [N, rank]           scale * dY * b^T
+    void *dg_scratch;           // [H]
+    size_t total;
+};
+
+LoraWs carve_lora(const cf_layer_desc& L, int rank, int max_kept, void* ws) {
+    LoraWs w;
+    w.base = carve_layer(L, max_kept, ws);
+    const size_t e = dtype_size(L.dtype);
+    const size_t N = (size_t)(max_kept > 0 ? max_kept : 1);
+    const size_t Nq = (size_t)L.Hq * L.d;
+    Carver c(ws);
+    c.off = w.base.total;
+    w.a_t = c.take((size_t)rank * (Nq > (size_t)L.H ? Nq : (size_t)L.H) * e);
+    w.u = c.take(N * rank * e);
+    w.tq = c.take(N * rank * e);
+    w.tk = c.take(N * rank * e);
+    w.tv = c.take(N * rank * e);
+    w.to = c.take(N * rank * e);
+    w.dg_scratch = c.take((size_t)L.H * e);
+    w.total = c.off;
+    return w;
+}
+
+// One adapted projection with input rows x [N,in] and output gradient dy [N,out]:
+// t = scale*dy*b^T (kept for the caller's dX GEMM), db = (scale*x*a)^T*dy, da = x^T*t.
+cf_status lora_proj(int dt, const void* x, const void* dy, const void* a, const void* b, int N, int in,
+                    int out, int rank, float scale, void* t, void* da, void* db, const LoraWs& w,
+                    hipStream_t st) {
+    {   // t [N,rank] = scale * dy [N,out] * b [rank,out]^T
+        GemmSeg s{dy, b, out};
+        CF_HIP(launch_gemm(dt, 0, &s, 1, t, N, rank, 0.f, st, scale));
+    }
+    CF_HIP(launch_transpose(dt, a, in, rank, w.a_t, st));
+    {   // u [N,rank] = scale * x [N,in] * a_t [rank,in]^T
+        GemmSeg s{x, w.a_t, in};
+        CF_HIP(launch_gemm(dt, 0, &s, 1, w.u, N, rank, 0.f, st, scale));
+    }
+    {   // db [rank,out] = u^T * dy
+        GemmSeg s{w.u, dy, N};
+        CF_HIP(launch_gemm(dt, 1, &s, 1, db, rank, out, 0.f, st));
+    }
+    {   // da [in,rank] = x^T * t
+        GemmSeg s{x, t, N};
+        CF_HIP(launch_gemm(dt, 1, &s, 1, da, in, rank, 0.f, st));
+    }
+    return CF_OK;
+}
+
+cf_status layer_core_lora(const cf_layer_desc& L, const cf_saved& sv, const cf_weights& W,
+                          const cf_lora& A, const void* dy_rows, const int32_t* idx,
+                          const int32_t* cu_kept, int N, cf_lora_grads& G, const LoraWs& lw,
+                          hipStream_t st) {
+    const LayerWs& w = lw.base;
+    const int dt = L.dtype;
+    const size_t e = dtype_size(dt);
+    const int H = L.H, F = L.F, Nq = L.Hq * L.d, Nkv = L.Hkv * L.d, R = A.rank;
+    if (N == 0) {
+        void* outs[8] = {G.daq, G.dbq, G.dak, G.dbk, G.dav, G.dbv, G.dao, G.dbo};
+        size_t sz[8] = {(size_t)H * R, (size_t)R * Nq, (size_t)H * R, (size_t)R * Nkv,
+                        (size_t)H * R, (size_t)R * Nkv, (size_t)Nq * R, (size_t)R * H};
+        for (int i = 0; i < 8; ++i) CF_HIP(launch_fill_zero(outs[i], sz[i] * e, st));
+        return CF_OK;
+    }
+    const void* a_rows = sv.attn_out;
+    const void* q_rows = sv.q;
+    if (idx) {
+        CF_HIP(launch_gather(sv.attn_out, (int64_t)Nq * e, idx, N, w.a_k, st));
+        CF_HIP(launch_gather(sv.q, (int64_t)Nq * e, idx, N, w.q_k, st));
+        a_rows = w.a_k;
+        q_rows = w.q_k;
+    }
+    // ---- frozen SwiGLU FFN: only the input gradient
+    void* d_act = w.bufF1;
+    {
+        GemmSeg s{dy_rows, W.wd, H};
+        CF_HIP(launch_gemm(dt, 0, &s, 1, d_act, N, F, 0.f, st));
+    }
+    void* d_gate = w.bufF1;
+    void* d_up = w.bufF0;
+    CF_HIP(launch_swiglu_bwd(dt, d_act, sv.gate, sv.up, idx, N, F, d_gate, d_up, nullptr, st));
+    void* dh2 = w.bufHb;
+    {
+        GemmSeg s[2] = {{d_gate, W.wg, F}, {d_up, W.wu, F}};
+        CF_HIP(launch_gemm(dt, 0, s, 2, dh2, N, H, 0.f, st));
+    }
+    CF_HIP(launch_rmsnorm_bwd(dt, dh2, sv.r, W.g2, idx, dy_rows, N, H, L.rms_eps, w.dr, w.dg_partial,
+                              lw.dg_scratch, st));
+    // ---- adapted O projection: input a [N,Nq], output gradient dr [N,H]
+    cf_status ps = lora_proj(dt, a_rows, w.dr, A.ao, A.bo, N, Nq, H, R, A.scale, lw.to, G.dao, G.dbo, lw, st);
+    if (ps != CF_OK) return ps;
+    {   // da = dr*Wo^T + t_o*a_o^T
+        GemmSeg s[2] = {{w.dr, W.wo, H}, {lw.to, A.ao, R}};
+        CF_HIP(launch_gemm(dt, 0, s, 2, w.da, N, Nq, 0.f, st));
+    }
+    cf_status as = attn_dispatch(L, q_rows, sv.k, sv.v, a_rows, sv.lse, w.da, idx, cu_kept, N, w.dq,
+                                 w.dk, w.dv, w.attn_ws, st);
+    if (as != CF_OK) return as;
+    if (sv.rope_cos) {
+        CF_HIP(launch_rope_bwd(dt, w.dq, idx, N, L.Hq, L.d, L.S, sv.rope_cos, sv.rope_sin, st));
+        CF_HIP(launch_rope_bwd(dt, w.dk, idx, N, L.Hkv, L.d, L.S, sv.rope_cos, sv.rope_sin, st));
+    }
+    // ---- adapted Q, K, V projections: input h1 [N,H]
+    void* h1 = w.bufHa;
+    CF_HIP(launch_rmsnorm_fwd(dt, sv.x, W.g1, idx, N, H, L.rms_eps, h1, st));
+    ps = lora_proj(dt, h1, w.dq, A.aq, A.bq, N, H, Nq, R, A.scale, lw.tq, G.daq, G.dbq, lw, st);
+    if (ps != CF_OK) return ps;
+    ps = lora_proj(dt, h1, w.dk, A.ak, A.bk, N, H, Nkv, R, A.scale, lw.tk, G.dak, G.dbk, lw, st);
+    if (ps != CF_OK) return ps;
+    ps = lora_proj(dt, h1, w.dv, A.av, A.bv, N, H, Nkv, R, A.scale, lw.tv, G.dav, G.dbv, lw, st);
+    if (ps != CF_OK) return ps;
+    void* dh1 = w.bufHb;
+    {   // dh1 = dq*Wq^T + dk*Wk^T + dv*Wv^T, then += t_q*a_q^T + t_k*a_k^T + t_v*a_v^T
+        GemmSeg s[3] = {{w.dq, W.wq, Nq}, {w.dk, W.wk, Nkv}, {w.dv, W.wv, Nkv}};
+        CF_HIP(launch_gemm(dt, 0, s, 3, dh1, N, H, 0.f, st));
+        GemmSeg s2[3] = {{lw.tq, A.aq, R}, {lw.tk, A.ak, R}, {lw.tv, A.av, R}};
+        CF_HIP(launch_gemm(dt, 0, s2, 3, dh1, N, H, 1.f, st));
+    }
+    CF_HIP(launch_rmsnorm_bwd(dt, dh1, sv.x, W.g1, idx, w.dr, N, H, L.rms_eps, G.dx, w.dg_partial,
+                              lw.dg_scratch, st));
+    return CF_OK;
+}
+
 cf_status check_layer_ptrs(const cf_saved* sv, const cf_weights* W, const void* dy, const cf_grads* G) {
     if (!sv || !W || !dy || !G) return CF_ERR_NULL;
     const void* req[] = {sv->x, sv->q, sv->k, sv->v, sv->attn_out, sv->lse, sv->r, sv->gate, sv->up,
@@ -458,6 +586,62 @@ cf_status cf_layer_bwd_dense(const cf_layer_desc* desc, const cf_saved* saved, c
     LayerWs wk = carve_layer(*desc, T, ws);
     if (ws_bytes < wk.total) return CF_ERR_WORKSPACE;
     return layer_core(*desc, *saved, *w, dy_full, nullptr, nullptr, T, *grads, wk, as_stream(stream));
+}
+
+size_t cf_lora_workspace_bytes(const cf_layer_desc* desc, int32_t rank, int32_t max_kept) {
+    if (check_layer_desc(desc) != CF_OK || max_kept < 0 || rank <= 0) return 0;
+    return carve_lora(*desc, rank, max_kept, nullptr).total;
+}
+
+cf_status cf_layer_bwd_lora(const cf_layer_desc* desc, const cf_saved* saved, const cf_weights* w,
+                            const cf_lora* lora, const void* dy_full, const uint8_t* mask,
+                            cf_lora_grads* grads, int32_t* idx_out, int32_t* cu_kept_out,
+                            int32_t* n_kept_host, void* ws, size_t ws_bytes, cf_stream stream) {
+    cf_status s = check_layer_desc(desc);
+    if (s != CF_OK) return s;
+    if (!saved || !w || !lora || !dy_full || !grads) return CF_ERR_NULL;
+    {
+        const void* req[] = {saved->x, saved->q, saved->k, saved->v, saved->attn_out, saved->lse, saved->r,
+                             saved->gate, saved->up, w->wq, w->wk, w->wv, w->wo, w->wg, w->wu, w->wd, w->g1,
+                             w->g2, lora->aq, lora->bq, lora->ak, lora->bk, lora->av, lora->bv, lora->ao,
+                             lora->bo, grads->daq, grads->dbq, grads->dak, grads->dbk, grads->dav,
+                             grads->dbv, grads->dao, grads->dbo, grads->dx, dy_full};
+        for (const void* p : req)
+            if (!p) return CF_ERR_NULL;
+        for (const void* p : req)
+            if (misaligned(p)) return CF_ERR_SHAPE;
+    }
+    if ((saved->rope_cos == nullptr) != (saved->rope_sin == nullptr)) return CF_ERR_NULL;
+    s = check_rope(desc, saved);
+    if (s != CF_OK) return s;
+    const int mult = desc->dtype == CF_BF16 ? 8 : 4;
+    if (lora->rank <= 0 || lora->rank % mult || lora->rank > 1024) return CF_ERR_SHAPE;
+    if (!(lora->scale == lora->scale)) return CF_ERR_SHAPE;
+    if (mask && !n_kept_host) return CF_ERR_NULL;
+    if ((idx_out && misaligned(idx_out, 4)) || (cu_kept_out && misaligned(cu_kept_out, 4))) return CF_ERR_SHAPE;
+    if (!ws || misaligned(ws, 256)) return CF_ERR_WORKSPACE;
+    const int T = desc->B * desc->S;
+    hipStream_t st = as_stream(stream);
+    if (!mask) {
+        LoraWs lw = carve_lora(*desc, lora->rank, T, ws);
+        if (ws_bytes < lw.total) return CF_ERR_WORKSPACE;
+        if (n_kept_host) *n_kept_host = T;
+        return layer_core_lora(*desc, *saved, *w, *lora, dy_full, nullptr, nullptr, T, *grads, lw, st);
+    }
+    LoraWs w0 = carve_lora(*desc, lora->rank, 0, ws);
+    if (ws_bytes < w0.total) return CF_ERR_WORKSPACE;
+    int32_t* idx = idx_out ? idx_out : w0.base.idx;
+    int32_t* cu = cu_kept_out ? cu_kept_out : w0.base.cu_kept;
+    CF_HIP(launch_keep_index(mask, desc->B, desc->S, idx, cu, w0.base.n_kept_dev, w0.base.index_ws, st));
+    CF_HIP(hipMemcpyAsync(n_kept_host, w0.base.n_kept_dev, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    CF_HIP(hipStreamSynchronize(st));
+    const int N = *n_kept_host;
+    if (N < 0 || N > T) return CF_ERR_HIP;
+    LoraWs lw = carve_lora(*desc, lora->rank, N, ws);
+    if (ws_bytes < lw.total) return CF_ERR_WORKSPACE;
+    if (N > 0)
+        CF_HIP(launch_gather(dy_full, (int64_t)desc->H * dtype_size(desc->dtype), idx, N, lw.base.dy_k, st));
+    return layer_core_lora(*desc, *saved, *w, *lora, lw.base.dy_k, idx, cu, N, *grads, lw, st);
 }
 
 }  // extern "C"

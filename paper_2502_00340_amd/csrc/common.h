@@ -110,6 +110,8 @@ hipError_t launch_rope_bwd(int dtype, void* g, const int32_t* idx, int n_rows, i
 hipError_t launch_attn_rowdot(int dtype, const void* da, const void* a, int n_rows, int Hq, int d,
                               float* D, hipStream_t st);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st);
+// dst [cols, rows] = src [rows, cols]^T  (small matrices: the low-rank adapters)
+hipError_t launch_transpose(int dtype, const void* src, int rows, int cols, void* dst, hipStream_t st);
 
 // gemm.hip
 struct GemmSeg {
@@ -117,11 +119,11 @@ struct GemmSeg {
     const void* B;
     int K;
 };
-// C[M,N] = beta*C + sum_seg op(A_seg)*op(B_seg); all matrices dense row-major.
+// C[M,N] = beta*C + alpha * sum_seg op(A_seg)*op(B_seg); all matrices dense row-major.
 //   mode 0 ("NT"): A_seg [M,K], B_seg [N,K]      (C = A * B^T)
 //   mode 1 ("TN"): A_seg [K,M], B_seg [K,N]      (C = A^T * B)
 hipError_t launch_gemm(int dtype, int mode, const GemmSeg* segs, int nseg, void* C, int M, int N,
-                       float beta, hipStream_t st);
+                       float beta, hipStream_t st, float alpha = 1.0f);
 
 // One TN launch for up to three products that share A [K,M]: C_j [M,Ng[j]] = A^T * B_j [K,Ng[j]].
 // bf16 only, every Ng[j] a multiple of 256 (gemm_tn_groups_supported says whether it applies).

@@ -60,6 +60,7 @@ struct GemmArgs {
     void* C;
     int M, N;
     float beta;
+    float alpha;    // the product is scaled by alpha before beta*C is added
     int n_full;     // leading blocks that own a whole 256x256 tile
     int sub;        // the remaining tiles are cut into `sub` (1, 2 or 4) sub-tiles, one block each
     // Column groups (ngroups > 1, one K segment): output columns [off_j, off_j + Ng[j]) belong to a
@@ -325,6 +326,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
     }
 
     // ---- epilogue: acc -> bf16 -> LDS C tile -> global with 16-byte stores -----------
+    const float alpha = g.alpha;
     lds_barrier();
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -335,8 +337,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
                 const int r = wm * (32 * TM) + i * 32 + slot;
                 const int c = wn * (32 * TN) + j * 32 + 8 * v4 + 4 * hh;
                 uint2 o;
-                o.x = pack_bf16x2(acc[i][j][4 * v4 + 0], acc[i][j][4 * v4 + 1]);
-                o.y = pack_bf16x2(acc[i][j][4 * v4 + 2], acc[i][j][4 * v4 + 3]);
+                o.x = pack_bf16x2(acc[i][j][4 * v4 + 0] * alpha, acc[i][j][4 * v4 + 1] * alpha);
+                o.y = pack_bf16x2(acc[i][j][4 * v4 + 2] * alpha, acc[i][j][4 * v4 + 3] * alpha);
                 *reinterpret_cast<uint2*>(smem + r * C_PITCH + c * 2) = o;
             }
     lds_barrier();
@@ -457,7 +459,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g) {
             const int n = n0 + tx * 4 + j;
             if (n >= g.N) continue;
             float* p = C + (int64_t)m * g.N + n;
-            *p = (g.beta != 0.f) ? acc[i][j] + g.beta * *p : acc[i][j];
+            *p = (g.beta != 0.f) ? g.alpha * acc[i][j] + g.beta * *p : g.alpha * acc[i][j];
         }
     }
 }
@@ -513,7 +515,7 @@ static hipError_t launch_bf16(GemmArgs& g, hipStream_t st) {
 }
 
 hipError_t launch_gemm(int dtype, int mode, const GemmSeg* segs, int nseg, void* C, int M, int N,
-                       float beta, hipStream_t st) {
+                       float beta, hipStream_t st, float alpha) {
     if (M <= 0 || N <= 0) return hipSuccess;
     GemmArgs g;
     g.nseg = 0;
@@ -525,7 +527,7 @@ hipError_t launch_gemm(int dtype, int mode, const GemmSeg* segs, int nseg, void*
         ++g.nseg;
     }
     for (int s = g.nseg; s < 3; ++s) { g.A[s] = nullptr; g.B[s] = nullptr; g.K[s] = 0; }
-    g.C = C; g.M = M; g.N = N; g.beta = beta; g.n_full = 0; g.sub = 1;
+    g.C = C; g.M = M; g.N = N; g.beta = beta; g.alpha = alpha; g.n_full = 0; g.sub = 1;
     g.ngroups = 1;
     for (int j = 0; j < 3; ++j) { g.Bg[j] = nullptr; g.Cg[j] = nullptr; g.Ng[j] = 0; }
     if (g.nseg == 0) {
@@ -571,7 +573,7 @@ hipError_t launch_gemm_tn_groups(const void* A, int K, int M, int ngroups, const
     g.ngroups = ngroups;
     g.A[0] = A; g.B[0] = Bg[0]; g.K[0] = K; g.nseg = 1;
     for (int s = 1; s < 3; ++s) { g.A[s] = nullptr; g.B[s] = nullptr; g.K[s] = 0; }
-    g.C = Cg[0]; g.M = M; g.N = N; g.beta = 0.f; g.n_full = 0; g.sub = 1;
+    g.C = Cg[0]; g.M = M; g.N = N; g.beta = 0.f; g.alpha = 1.f; g.n_full = 0; g.sub = 1;
     return launch_bf16<1>(g, st);
 }
 

@@ -230,4 +230,28 @@ hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st) {
     return hipGetLastError();
 }
 
+// dst [cols, rows] = src [rows, cols]^T through a 32x32 LDS tile
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_kernel(const T* __restrict__ src, int rows, int cols,
+                                                        T* __restrict__ dst) {
+    __shared__ T tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
+    for (int i = ty; i < 32; i += 8)
+        if (r0 + i < rows && c0 + tx < cols) tile[i][tx] = src[(int64_t)(r0 + i) * cols + c0 + tx];
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8)
+        if (c0 + i < cols && r0 + tx < rows) dst[(int64_t)(c0 + i) * rows + r0 + tx] = tile[tx][i];
+}
+
+hipError_t launch_transpose(int dtype, const void* src, int rows, int cols, void* dst, hipStream_t st) {
+    if (rows <= 0 || cols <= 0) return hipSuccess;
+    const dim3 grid(ceil_div(cols, 32), ceil_div(rows, 32));
+    if (dtype == CF_F32)
+        transpose_kernel<float><<<grid, 256, 0, st>>>((const float*)src, rows, cols, (float*)dst);
+    else
+        transpose_kernel<bf16_t><<<grid, 256, 0, st>>>((const bf16_t*)src, rows, cols, (bf16_t*)dst);
+    return hipGetLastError();
+}
+
 }  // namespace cf

@@ -132,6 +132,27 @@ def test_layer_argument_errors(L):
     assert fd(C.byref(_desc(dtype="bf16", d=32)), C.byref(sv), C.byref(w), FAKE, C.byref(g), FAKE, ok_ws, None) == 2
 
 
+def test_lora_argument_errors(L):
+    d = _desc()
+    sv = Bn.Saved(*([0x10000] * 9 + [None, None]))
+    w = Bn.Weights(*([0x10000] * 9))
+    g = Bn.LoraGrads(*([0x10000] * 9))
+    n = C.c_int32(0)
+    f = L.cf_layer_bwd_lora
+    ok_ws = L.cf_lora_workspace_bytes(C.byref(d), 8, 256)
+    assert ok_ws > L.cf_layer_workspace_bytes(C.byref(d), 256)
+    assert L.cf_lora_workspace_bytes(C.byref(d), 0, 256) == 0
+    lo = Bn.Lora(*([0x10000] * 8 + [8, 2.0]))
+    assert f(C.byref(d), C.byref(sv), C.byref(w), None, FAKE, FAKE, C.byref(g), None, None, C.byref(n), FAKE, ok_ws, None) == 1
+    assert f(C.byref(d), C.byref(sv), C.byref(w), C.byref(lo), FAKE, FAKE, C.byref(g), None, None, None, FAKE, ok_ws, None) == 1
+    lo_bad = Bn.Lora(*([0x10000] * 7 + [0, 8, 2.0]))
+    assert f(C.byref(d), C.byref(sv), C.byref(w), C.byref(lo_bad), FAKE, FAKE, C.byref(g), None, None, C.byref(n), FAKE, ok_ws, None) == 1
+    lo_rank = Bn.Lora(*([0x10000] * 8 + [6, 2.0]))
+    assert f(C.byref(d), C.byref(sv), C.byref(w), C.byref(lo_rank), FAKE, FAKE, C.byref(g), None, None, C.byref(n), FAKE, ok_ws, None) == 2
+    assert f(C.byref(d), C.byref(sv), C.byref(w), C.byref(lo), FAKE, FAKE, C.byref(g), None, None, C.byref(n), FAKE, 256, None) == 4
+    assert f(C.byref(d), C.byref(sv), C.byref(w), C.byref(lo), FAKE, None, C.byref(g), None, None, None, FAKE, 256, None) == 4
+
+
 def test_product_path_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_2502_00340_amd")
     for dirpath, _, files in os.walk(pkg):

@@ -76,3 +76,31 @@ def test_tensor_parallel_share_of_the_8b_layer_with_rotary():
     shape = WL.LayerShape("llama31_8b_tp8_share", B=2, S=4096, H=4096, Hq=4, Hkv=1, d=128, F=1792,
                           dtype="bf16", mask_kind="spans")
     _run(5, shape=shape, rope=True)
+
+
+def test_lora_rank64_on_the_3b_layer():
+    """The paper's LoRA setting (Sec. 5.3): rank-64 adapters on q, k, v, o of the 3B-shaped
+    layer, base weights frozen; keep ratio 0.5."""
+    shape = WL.CONFIGS[2]
+    print("[case] full size LoRA rank 64 on %s" % shape.name, flush=True)
+    p = Hn.Problem(shape, WL.config_seed(2), "independent", rho=0.5, oracle_dtype=np.float32)
+    rng = np.random.default_rng(64)
+    lora_np = {k: (Hn.quantize(v, "bf16") if isinstance(v, np.ndarray) else v)
+               for k, v in WL.make_lora(shape, rng, rank=64, alpha=128.0).items()}
+    sv, W, dy, mask = p.device_tensors(DEV)
+    lo = {k: (Hn.to_dev(v, "bf16", DEV) if isinstance(v, np.ndarray) else v) for k, v in lora_np.items()}
+    plan = Bn.LoraBackward(p.desc(), 64, device=DEV)
+    n = plan.run(sv, W, lo, dy, mask)
+    torch.cuda.synchronize()
+    print("[case]   GPU done (n_kept=%d), running the oracle" % n, flush=True)
+    ref = O.layer_bwd({k: v.astype(np.float32) for k, v in p.saved.items()},
+                      {k: v.astype(np.float32) for k, v in p.W.items()}, p.dy.astype(np.float32), p.mask,
+                      lora={k: (v.astype(np.float32) if isinstance(v, np.ndarray) else v) for k, v in lora_np.items()},
+                      **p.kw)
+    ridx = np.flatnonzero(p.mask.reshape(-1))
+    assert n == len(ridx)
+    errs = {k: Hn.rel_fro(Hn.to_np(plan.grads[k]), ref[k]) for k in ("daq", "dbq", "dak", "dbk", "dav", "dbv", "dao", "dbo")}
+    errs["dx"] = Hn.rel_fro(Hn.to_np(plan.grads["dx"][:n]), ref["dx"][ridx])
+    print("[case]   " + " ".join("%s=%.1e" % kv for kv in errs.items()), flush=True)
+    bad = {k: v for k, v in errs.items() if not (v <= Hn.TOL["bf16"])}
+    assert not bad, bad

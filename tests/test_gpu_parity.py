@@ -399,3 +399,45 @@ def test_no_write_outside_the_outputs_and_the_workspace():
     torch.cuda.synchronize()
     for name, buf in raw.items():
         assert bool((buf[:PAD] == 0xA5).all()) and bool((buf[-PAD:] == 0xA5).all()), name
+
+
+LORA_NAMES = ("daq", "dbq", "dak", "dbk", "dav", "dbv", "dao", "dbo")
+
+
+def _run_lora(p, lora_np, rank, mask_on=True):
+    sv, W, dy, mask = p.device_tensors(DEV)
+    lo = {k: (Hn.to_dev(v, p.dtype, DEV) if isinstance(v, np.ndarray) else v) for k, v in lora_np.items()}
+    plan = Bn.LoraBackward(p.desc(), rank, device=DEV)
+    n = plan.run(sv, W, lo, dy, mask if mask_on else None)
+    torch.cuda.synchronize()
+    return plan, n
+
+
+@pytest.mark.parametrize("dtype,mode,rank", [("f32", "consistent", 8), ("bf16", "independent", 16), ("bf16", "independent", 64)])
+def test_layer_lora(dtype, mode, rank):
+    """Adapters on q, k, v, o with frozen base weights: adapter gradients and compact dx against
+    the oracle, filtered and with every token kept."""
+    shape = WL.LayerShape("lora", B=2, S=224, H=256, Hq=4, Hkv=2, d=64, F=384, dtype=dtype)
+    say("layer lora %s rank %d" % (dtype, rank))
+    rng = np.random.default_rng(51)
+    lora_np = {k: (Hn.quantize(v, dtype) if isinstance(v, np.ndarray) else v)
+               for k, v in WL.make_lora(shape, rng, rank=rank, alpha=2.0 * rank).items()}
+    p = Hn.Problem(shape, 52, mode, rho=0.5)
+    if mode == "consistent":    # saved tensors of the adapted forward
+        lo64 = {k: (v.astype(np.float64) if isinstance(v, np.ndarray) else v) for k, v in lora_np.items()}
+        _, sv = O.layer_fwd(p.saved["x"].astype(np.float64), {k: v.astype(np.float64) for k, v in p.W.items()},
+                            lora=lo64, **p.kw)
+        p.saved = {k: (np.asarray(v, dtype=np.float32) if k == "lse" else Hn.quantize(v, dtype)) for k, v in sv.items()}
+    lo = {k: (v.astype(p.oracle_dtype) if isinstance(v, np.ndarray) else v) for k, v in lora_np.items()}
+    svo = {k: v.astype(p.oracle_dtype) for k, v in p.saved.items()}
+    Wo = {k: v.astype(p.oracle_dtype) for k, v in p.W.items()}
+    for mask_on in (True, False):
+        plan, n = _run_lora(p, lora_np, rank, mask_on)
+        ref = O.layer_bwd(svo, Wo, p.dy.astype(p.oracle_dtype), p.mask if mask_on else None, lora=lo, **p.kw)
+        ridx = np.flatnonzero(p.mask.reshape(-1)) if mask_on else np.arange(shape.T)
+        assert n == len(ridx)
+        errs = {k: Hn.rel_fro(Hn.to_np(plan.grads[k]), ref[k]) for k in LORA_NAMES}
+        errs["dx"] = Hn.rel_fro(Hn.to_np(plan.grads["dx"][:n]), ref["dx"][ridx])
+        say("  " + " ".join("%s=%.1e" % kv for kv in errs.items()))
+        bad = {k: v for k, v in errs.items() if not (v <= Hn.TOL[dtype])}
+        assert not bad, bad
