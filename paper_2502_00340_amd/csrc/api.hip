@@ -260,8 +260,13 @@ struct LoraWs {
     void *u;                    // [N, rank]           scale * X * a
     void *tq, *tk, *tv, *to;    // [N, rank]           scale * dY * b^T
     void *dg_scratch;           // [H]
+    void *splitk;               // fp32 parts of the split-K adapter GEMMs
     size_t total;
 };
+
+// Upper bound of what a split-K launch uses: parts <= CUs / tiles and a part holds at most
+// tiles * 128 * 128 floats, so 64 KB per CU; sized for 512 CUs.
+constexpr size_t kSplitKBytes = (size_t)32 << 20;
 
 LoraWs carve_lora(const cf_layer_desc& L, int rank, int max_kept, void* ws) {
     LoraWs w;
@@ -278,6 +283,7 @@ LoraWs carve_lora(const cf_layer_desc& L, int rank, int max_kept, void* ws) {
     w.tv = c.take(N * rank * e);
     w.to = c.take(N * rank * e);
     w.dg_scratch = c.take((size_t)L.H * e);
+    w.splitk = c.take(kSplitKBytes);
     w.total = c.off;
     return w;
 }
@@ -289,20 +295,20 @@ cf_status lora_proj(int dt, const void* x, const void* dy, const void* a, const 
                     hipStream_t st) {
     {   // t [N,rank] = scale * dy [N,out] * b [rank,out]^T
         GemmSeg s{dy, b, out};
-        CF_HIP(launch_gemm(dt, 0, &s, 1, t, N, rank, 0.f, st, scale));
+        CF_HIP(launch_gemm(dt, 0, &s, 1, t, N, rank, 0.f, st, scale, w.splitk, kSplitKBytes));
     }
     CF_HIP(launch_transpose(dt, a, in, rank, w.a_t, st));
     {   // u [N,rank] = scale * x [N,in] * a_t [rank,in]^T
         GemmSeg s{x, w.a_t, in};
-        CF_HIP(launch_gemm(dt, 0, &s, 1, w.u, N, rank, 0.f, st, scale));
+        CF_HIP(launch_gemm(dt, 0, &s, 1, w.u, N, rank, 0.f, st, scale, w.splitk, kSplitKBytes));
     }
     {   // db [rank,out] = u^T * dy
         GemmSeg s{w.u, dy, N};
-        CF_HIP(launch_gemm(dt, 1, &s, 1, db, rank, out, 0.f, st));
+        CF_HIP(launch_gemm(dt, 1, &s, 1, db, rank, out, 0.f, st, 1.f, w.splitk, kSplitKBytes));
     }
     {   // da [in,rank] = x^T * t
         GemmSeg s{x, t, N};
-        CF_HIP(launch_gemm(dt, 1, &s, 1, da, in, rank, 0.f, st));
+        CF_HIP(launch_gemm(dt, 1, &s, 1, da, in, rank, 0.f, st, 1.f, w.splitk, kSplitKBytes));
     }
     return CF_OK;
 }

@@ -122,8 +122,12 @@ struct GemmSeg {
 // C[M,N] = beta*C + alpha * sum_seg op(A_seg)*op(B_seg); all matrices dense row-major.
 //   mode 0 ("NT"): A_seg [M,K], B_seg [N,K]      (C = A * B^T)
 //   mode 1 ("TN"): A_seg [K,M], B_seg [K,N]      (C = A^T * B)
+// splitk_ws (device, splitk_bytes, 16-byte aligned, may be null): scratch that lets a bf16 product
+// with one segment, few output tiles and a long K run as a split-K launch (fp32 parts summed in a
+// fixed order by a second kernel).
 hipError_t launch_gemm(int dtype, int mode, const GemmSeg* segs, int nseg, void* C, int M, int N,
-                       float beta, hipStream_t st, float alpha = 1.0f);
+                       float beta, hipStream_t st, float alpha = 1.0f, void* splitk_ws = nullptr,
+                       size_t splitk_bytes = 0);
 
 // One TN launch for up to three products that share A [K,M]: C_j [M,Ng[j]] = A^T * B_j [K,Ng[j]].
 // bf16 only, every Ng[j] a multiple of 256 (gemm_tn_groups_supported says whether it applies).

@@ -45,6 +45,7 @@
 //     bf16, stages the whole C tile in LDS (the operand stages are dead by then)
 //     and writes full rows with 16-byte stores.
 // fp32 path (check mode): plain LDS-tiled FMA kernel.
+#include <algorithm>
 #include <type_traits>
 
 #include "common.h"
@@ -100,9 +101,12 @@ __device__ __forceinline__ void tile_coords(int l, int tiles_m, int tiles_n, int
     bn = r / gsize;
 }
 
-// One output tile of (64*TM) x (64*TN) at (m0, n0).
-template <int MODE, int TM, int TN>
-__device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const int n0, unsigned char* smem) {
+// One output tile of (64*TM) x (64*TN) at (m0, n0).  SPLIT: the block contracts only k in
+// [kbeg, kend) of the single segment and stores its fp32 accumulators, unscaled, to `part_out`
+// ([M, N] fp32); a second kernel adds the parts up.
+template <int MODE, int TM, int TN, bool SPLIT = false>
+__device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const int n0, unsigned char* smem,
+                                          const int kbeg = 0, const int kend = 0, float* part_out = nullptr) {
     constexpr int BM = 64 * TM, BN = 64 * TN, KB = 32, NST = GEMM_STAGES, STAGE = GEMM_STAGE_BYTES;
     constexpr int A_BYTES = BM * KB * 2;                // B tile follows the A tile inside a stage
     constexpr int NU = TM + TN;                         // 1 KB wave-loads per wave per K-step: TM for A, TN for B
@@ -305,10 +309,15 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
     };
 
     // K-steps of 32 including the zero K-step that pads a segment with an odd count
-    const int steps = 2 * ((g.K[0] + 2 * KB - 1) / (2 * KB) + (g.K[1] + 2 * KB - 1) / (2 * KB) +
-                           (g.K[2] + 2 * KB - 1) / (2 * KB));
+    const int steps = SPLIT ? 2 * ((kend - kbeg + 2 * KB - 1) / (2 * KB))
+                            : 2 * ((g.K[0] + 2 * KB - 1) / (2 * KB) + (g.K[1] + 2 * KB - 1) / (2 * KB) +
+                                   (g.K[2] + 2 * KB - 1) / (2 * KB));
     if (steps > 0) {
         open_segment(0);
+        if (SPLIT) {                    // the block's K range stands for the segment
+            k0 = kbeg;
+            Kseg = kend;
+        }
         issue_pair(0, 1);
         advance_pair();
         issue_pair(2, 3);
@@ -325,6 +334,25 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
         wait_vmcnt<0>();
     }
 
+    if (SPLIT) {
+        // ---- split-K epilogue: fp32 accumulators straight to the block's part ----------
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int v4 = 0; v4 < 4; ++v4) {
+                    const int m = m0 + wm * (32 * TM) + i * 32 + slot;
+                    const int n = n0 + wn * (32 * TN) + j * 32 + 8 * v4 + 4 * hh;
+                    if (m < g.M && n < g.N) {               // N is a multiple of 8
+                        float4 o;
+                        o.x = acc[i][j][4 * v4 + 0]; o.y = acc[i][j][4 * v4 + 1];
+                        o.z = acc[i][j][4 * v4 + 2]; o.w = acc[i][j][4 * v4 + 3];
+                        *reinterpret_cast<float4*>(part_out + (int64_t)m * g.N + n) = o;
+                    }
+                }
+        return;
+    }
     // ---- epilogue: acc -> bf16 -> LDS C tile -> global with 16-byte stores -----------
     const float alpha = g.alpha;
     lds_barrier();
@@ -402,6 +430,46 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     if (cut == 1) gemm_tile<MODE, 4, 4>(g, m0, n0, smem);
     else if (cut == 2) gemm_tile<MODE, 4, 2>(g, m0, n0, smem);
     else gemm_tile<MODE, 2, 2>(g, m0, n0, smem);
+}
+
+// Split-K variant for outputs with too few tiles to fill the chip (a skinny M or N with a long
+// K: the products with a rank-r adapter matrix).  grid = (128x128 tiles, parts); part p contracts
+// k in [p*kchunk, (p+1)*kchunk) into partial[p]; splitk_reduce_kernel sums the parts in a fixed
+// order, so the result does not depend on scheduling.
+template <int MODE>
+__global__ __launch_bounds__(256) void gemm_bf16_splitk_kernel(GemmArgs g, float* partial, int kchunk) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tiles_m = (g.M + 127) / 128;
+    const int m0 = ((int)blockIdx.x % tiles_m) * 128, n0 = ((int)blockIdx.x / tiles_m) * 128;
+    const int kbeg = (int)blockIdx.y * kchunk;
+    const int kend = min(g.K[0], kbeg + kchunk);
+    gemm_tile<MODE, 2, 2, true>(g, m0, n0, smem, kbeg, kend, partial + (int64_t)blockIdx.y * g.M * g.N);
+}
+
+// C[m, n..n+7] = alpha * sum_p partial[p][m, n..n+7] + beta * C
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, bf16_t* __restrict__ C,
+                                                            int64_t mn, int parts, float alpha, float beta) {
+    const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
+    if (e >= mn) return;
+    float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int p = 0; p < parts; ++p) {
+        const float4 a = *reinterpret_cast<const float4*>(partial + p * mn + e);
+        const float4 b = *reinterpret_cast<const float4*>(partial + p * mn + e + 4);
+        s[0] += a.x; s[1] += a.y; s[2] += a.z; s[3] += a.w;
+        s[4] += b.x; s[5] += b.y; s[6] += b.z; s[7] += b.w;
+    }
+    u32x4_t val;
+    if (beta != 0.f) {
+        const u32x4_t old = *reinterpret_cast<const u32x4_t*>(C + e);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            val[q] = pack_bf16x2(alpha * s[2 * q] + beta * __uint_as_float(old[q] << 16),
+                                 alpha * s[2 * q + 1] + beta * __uint_as_float(old[q] & 0xFFFF0000u));
+    } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) val[q] = pack_bf16x2(alpha * s[2 * q], alpha * s[2 * q + 1]);
+    }
+    *reinterpret_cast<u32x4_t*>(C + e) = val;
 }
 
 // ---------------------------------------------------------------------------
@@ -498,6 +566,41 @@ static int compute_units() {
     return n;
 }
 
+// Number of K parts for a split-K launch (0: use the ordinary kernel) and the K range of a part.
+// Splitting pays when the 128x128 tiles cover at most half of the CUs and K is long enough that
+// every part still runs several K-steps.
+static int plan_splitk(const GemmArgs& g, int n_cu, size_t ws_bytes, int& kchunk) {
+    if (g.nseg != 1 || g.ngroups > 1) return 0;
+    const int K = g.K[0];
+    const int tiles = ceil_div(g.M, 128) * ceil_div(g.N, 128);
+    if (tiles * 2 > n_cu || K < 1024) return 0;
+    const size_t per_part = (size_t)g.M * g.N * sizeof(float);
+    int parts = std::min(std::min(n_cu / tiles, K / 256), 32);
+    parts = (int)std::min<size_t>((size_t)parts, ws_bytes / per_part);
+    if (parts < 2) return 0;
+    kchunk = ceil_div(ceil_div(K, parts), 64) * 64;
+    return ceil_div(K, kchunk);
+}
+
+template <int MODE>
+static hipError_t launch_bf16_splitk(GemmArgs& g, int parts, int kchunk, float* partial, hipStream_t st) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_splitk_kernel<MODE>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_SMEM);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const dim3 grid(ceil_div(g.M, 128) * ceil_div(g.N, 128), parts);
+    gemm_bf16_splitk_kernel<MODE><<<grid, 256, GEMM_SMEM, st>>>(g, partial, kchunk);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int64_t mn = (int64_t)g.M * g.N;
+    splitk_reduce_kernel<<<(unsigned)ceil_div(mn / 8, (int64_t)256), 256, 0, st>>>(
+        partial, static_cast<bf16_t*>(g.C), mn, parts, g.alpha, g.beta);
+    return hipGetLastError();
+}
+
 template <int MODE>
 static hipError_t launch_bf16(GemmArgs& g, hipStream_t st) {
     static bool attr_set = false;
@@ -515,7 +618,7 @@ static hipError_t launch_bf16(GemmArgs& g, hipStream_t st) {
 }
 
 hipError_t launch_gemm(int dtype, int mode, const GemmSeg* segs, int nseg, void* C, int M, int N,
-                       float beta, hipStream_t st, float alpha) {
+                       float beta, hipStream_t st, float alpha, void* splitk_ws, size_t splitk_bytes) {
     if (M <= 0 || N <= 0) return hipSuccess;
     GemmArgs g;
     g.nseg = 0;
@@ -546,6 +649,13 @@ hipError_t launch_gemm(int dtype, int mode, const GemmSeg* segs, int nseg, void*
         if (mode == 0) gemm_f32_kernel<0><<<grid, 256, 0, st>>>(g);
         else gemm_f32_kernel<1><<<grid, 256, 0, st>>>(g);
         return hipGetLastError();
+    }
+    if (splitk_ws != nullptr) {
+        int kchunk = 0;
+        const int parts = plan_splitk(g, compute_units(), splitk_bytes, kchunk);
+        if (parts >= 2)
+            return mode == 0 ? launch_bf16_splitk<0>(g, parts, kchunk, static_cast<float*>(splitk_ws), st)
+                             : launch_bf16_splitk<1>(g, parts, kchunk, static_cast<float*>(splitk_ws), st);
     }
     return mode == 0 ? launch_bf16<0>(g, st) : launch_bf16<1>(g, st);
 }

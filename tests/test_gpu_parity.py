@@ -413,16 +413,28 @@ def _run_lora(p, lora_np, rank, mask_on=True):
     return plan, n
 
 
-@pytest.mark.parametrize("dtype,mode,rank", [("f32", "consistent", 8), ("bf16", "independent", 16), ("bf16", "independent", 64)])
-def test_layer_lora(dtype, mode, rank):
+LORA_SHAPES = {
+    "small": dict(B=2, S=224, H=256, Hq=4, Hkv=2, d=64, F=384),
+    # long enough contractions (H, Hq*d and the kept-token count above 1024) for the adapter products
+    # to take the split-K path, with ragged K ranges
+    "splitk": dict(B=2, S=640, H=1024, Hq=16, Hkv=4, d=64, F=512),
+}
+
+
+@pytest.mark.parametrize("dtype,mode,rank,which", [("f32", "consistent", 8, "small"),
+                                                   ("bf16", "independent", 16, "small"),
+                                                   ("bf16", "independent", 64, "small"),
+                                                   ("bf16", "independent", 64, "splitk"),
+                                                   ("bf16", "independent", 24, "splitk")])
+def test_layer_lora(dtype, mode, rank, which):
     """Adapters on q, k, v, o with frozen base weights: adapter gradients and compact dx against
     the oracle, filtered and with every token kept."""
-    shape = WL.LayerShape("lora", B=2, S=224, H=256, Hq=4, Hkv=2, d=64, F=384, dtype=dtype)
-    say("layer lora %s rank %d" % (dtype, rank))
+    shape = WL.LayerShape("lora", dtype=dtype, **LORA_SHAPES[which])
+    say("layer lora %s rank %d %s" % (dtype, rank, which))
     rng = np.random.default_rng(51)
     lora_np = {k: (Hn.quantize(v, dtype) if isinstance(v, np.ndarray) else v)
                for k, v in WL.make_lora(shape, rng, rank=rank, alpha=2.0 * rank).items()}
-    p = Hn.Problem(shape, 52, mode, rho=0.5)
+    p = Hn.Problem(shape, 52, mode, rho=0.9 if which == "splitk" else 0.5)
     if mode == "consistent":    # saved tensors of the adapted forward
         lo64 = {k: (v.astype(np.float64) if isinstance(v, np.ndarray) else v) for k, v in lora_np.items()}
         _, sv = O.layer_fwd(p.saved["x"].astype(np.float64), {k: v.astype(np.float64) for k, v in p.W.items()},
