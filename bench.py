@@ -257,6 +257,15 @@ def lora_leg(shape: WL.LayerShape, sv, W, dy, mask_dev, rng, steps: int, warmup:
             "speedup": round(t_d / t_f, 4)}
 
 
+def main_grad_leg(desc, sv, W, dy, mask_dev, steps: int, warmup: int):
+    """The same layer with fp32 main-gradient buffers that every call adds to (gradient
+    accumulation over micro-batches): each dW element is read and written as fp32."""
+    plan = Bn.LayerBackward(desc, device=DEV, main_grad=True)
+    t_f = time_steps(lambda: plan.filtered(sv, W, dy, mask_dev), steps, warmup)
+    t_d = time_steps(lambda: plan.dense(sv, W, dy), steps, warmup)
+    return {"filtered_ms": round(t_f * 1e3, 4), "dense_ms": round(t_d * 1e3, 4), "speedup": round(t_d / t_f, 4)}
+
+
 def cpu_baseline_leg(shape: WL.LayerShape, W, sv, dy, mask):
     """The CPU oracle (fp32 arrays, numpy) on the same workload (the whole batch
     is a bounded sample already: about ten seconds of host time)."""
@@ -288,6 +297,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-parts", action="store_true", help="skip the per-part timings")
     ap.add_argument("--lora", action="store_true", help="also time the LoRA-adapted layer backward (rank 64)")
+    ap.add_argument("--main-grad", action="store_true",
+                    help="also time the layer with fp32 main-gradient accumulation of the parameter gradients")
     ap.add_argument("--context-sweep", action="store_true",
                     help="also time context lengths 1K..8K at fixed token count and keep ratios 0.1..1.0 (slow)")
     a = ap.parse_args()
@@ -349,6 +360,11 @@ def main():
         log("LoRA leg")
         lora = lora_leg(shape, sv, W, dy, mask_dev, rng, a.steps, a.warmup)
         log("LoRA: filtered %.3f ms dense %.3f ms speedup %.3f" % (lora["filtered_ms"], lora["dense_ms"], lora["speedup"]))
+    mgrad = None
+    if a.main_grad:
+        log("main-grad leg")
+        mgrad = main_grad_leg(desc, sv, W, dy, mask_dev, a.steps, a.warmup)
+        log("main-grad: filtered %.3f ms dense %.3f ms speedup %.3f" % (mgrad["filtered_ms"], mgrad["dense_ms"], mgrad["speedup"]))
     log("roofline leg")
     roof = roofline_leg(shape, n_k)
     cpu = None
@@ -376,6 +392,7 @@ def main():
         "parts": parts,
         "context_sweep": ctx,
         "lora": lora,
+        "main_grad": mgrad,
         "roofline": roof,
         "cpu_baseline": cpu,
     }

@@ -96,12 +96,17 @@ typedef struct {
     const void *g1, *g2;       /* [H] RMSNorm gains */
 } cf_weights;
 
-/* Outputs.  Parameter gradients have the shapes of the parameters and are
- * overwritten.  dx is [N_k,H] compact for the filtered call and [T,H] for the
- * dense call. */
+/* Outputs.  Parameter gradients have the shapes of the parameters.  dx is [N_k,H]
+ * compact for the filtered call and [T,H] for the dense call, always overwritten.
+ *   main_grad == 0: parameter gradients in the storage dtype, overwritten.
+ *   main_grad == 1: the nine parameter-gradient tensors are fp32 buffers (whatever the
+ *     storage dtype) and the call ADDS this batch's gradient to them, without rounding
+ *     the fp32 accumulators to the storage dtype first: gradient accumulation over
+ *     micro-batches in a master-precision buffer.  With no kept token nothing is added. */
 typedef struct {
     void *dwq, *dwk, *dwv, *dwo, *dwg, *dwu, *dwd, *dg1, *dg2;
     void *dx;
+    int32_t main_grad;
 } cf_grads;
 
 const char* cf_status_str(cf_status s);

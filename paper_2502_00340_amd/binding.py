@@ -48,8 +48,11 @@ class Weights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g1", "g2")]
 
 
+GRAD_NAMES = ("dwq", "dwk", "dwv", "dwo", "dwg", "dwu", "dwd", "dg1", "dg2", "dx")
+
+
 class Grads(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("dwq", "dwk", "dwv", "dwo", "dwg", "dwu", "dwd", "dg1", "dg2", "dx")]
+    _fields_ = [(n, C.c_void_p) for n in GRAD_NAMES] + [("main_grad", C.c_int32)]
 
 
 _LORA_T = ("aq", "bq", "ak", "bk", "av", "bv", "ao", "bo")
@@ -229,7 +232,8 @@ _WEIGHTS = ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g1", "g2")
 class LayerBackward:
     """Pre-allocated outputs + workspace for repeated calls on one layer shape."""
 
-    def __init__(self, desc: LayerDesc, device="cuda:0", max_kept: int | None = None):
+    def __init__(self, desc: LayerDesc, device="cuda:0", max_kept: int | None = None, main_grad: bool = False):
+        """main_grad: the parameter gradients are fp32 buffers, zeroed here, that every call adds to."""
         self.desc = desc
         self.device = torch.device(device)
         dt = torch_dtype(desc)
@@ -237,15 +241,16 @@ class LayerBackward:
         H, F, Nq, Nkv = desc.H, desc.F, desc.Hq * desc.d, desc.Hkv * desc.d
         self.max_kept = T if max_kept is None else max_kept
         e = lambda *s: torch.empty(s, dtype=dt, device=self.device)
-        self.grads = dict(dwq=e(H, Nq), dwk=e(H, Nkv), dwv=e(H, Nkv), dwo=e(Nq, H), dwg=e(H, F), dwu=e(H, F),
-                          dwd=e(F, H), dg1=e(H), dg2=e(H), dx=e(T, H))
+        p = (lambda *s: torch.zeros(s, dtype=torch.float32, device=self.device)) if main_grad else e
+        self.grads = dict(dwq=p(H, Nq), dwk=p(H, Nkv), dwv=p(H, Nkv), dwo=p(Nq, H), dwg=p(H, F), dwu=p(H, F),
+                          dwd=p(F, H), dg1=p(H), dg2=p(H), dx=e(T, H))
         self.idx = torch.empty(T, dtype=torch.int32, device=self.device)
         self.cu_kept = torch.empty(desc.B + 1, dtype=torch.int32, device=self.device)
         self.ws_bytes = lib().cf_layer_workspace_bytes(C.byref(desc), self.max_kept)
         if self.ws_bytes == 0:
             raise CfError(2, "cf_layer_workspace_bytes")
         self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=self.device)
-        self._g = Grads(*[self.grads[n].data_ptr() for n, _ in Grads._fields_])
+        self._g = Grads(*([self.grads[n].data_ptr() for n in GRAD_NAMES] + [1 if main_grad else 0]))
         # N_k comes back through page-locked host memory: the copy needs no staging buffer
         self._n_host = torch.empty(1, dtype=torch.int32).pin_memory()
 

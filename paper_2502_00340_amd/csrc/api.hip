@@ -158,8 +158,15 @@ cf_status layer_core(const cf_layer_desc& L, const cf_saved& sv, const cf_weight
     const int dt = L.dtype;
     const size_t e = dtype_size(dt);
     const int H = L.H, F = L.F, Nq = L.Hq * L.d, Nkv = L.Hkv * L.d;
+    // main-gradient mode: the nine parameter gradients are fp32 buffers that this call adds to
+    const bool mg = G.main_grad != 0;
+    auto dw_gemm = [&](const void* A, const void* B, void* C, int M, int Ncols) {
+        GemmSeg s{A, B, N};
+        return launch_gemm(dt, 1, &s, 1, C, M, Ncols, mg ? 1.f : 0.f, st, 1.f, nullptr, 0, mg);
+    };
 
     if (N == 0) {   // nothing kept: every gradient is zero, dx has no rows
+        if (mg) return CF_OK;
         void* outs[9] = {G.dwq, G.dwk, G.dwv, G.dwo, G.dwg, G.dwu, G.dwd, G.dg1, G.dg2};
         size_t sz[9] = {(size_t)H * Nq, (size_t)H * Nkv, (size_t)H * Nkv, (size_t)Nq * H,
                         (size_t)H * F, (size_t)H * F, (size_t)F * H, (size_t)H, (size_t)H};
@@ -188,19 +195,12 @@ cf_status layer_core(const cf_layer_desc& L, const cf_saved& sv, const cf_weight
     void* d_up = w.bufF0;
     void* act = w.bufF2;
     CF_HIP(launch_swiglu_bwd(dt, d_act, sv.gate, sv.up, idx, N, F, d_gate, d_up, act, st));
-    {   // dWd = act^T * dy           [F,H]
-        GemmSeg s{act, dy_rows, N};
-        CF_HIP(launch_gemm(dt, 1, &s, 1, G.dwd, F, H, 0.f, st));
-    }
+    CF_HIP(dw_gemm(act, dy_rows, G.dwd, F, H));     // dWd = act^T * dy           [F,H]
 
     void* h2 = w.bufHa;
     CF_HIP(launch_rmsnorm_fwd(dt, sv.r, W.g2, idx, N, H, L.rms_eps, h2, st));
-    {
-        GemmSeg s{h2, d_gate, N};
-        CF_HIP(launch_gemm(dt, 1, &s, 1, G.dwg, H, F, 0.f, st));
-        GemmSeg s2{h2, d_up, N};
-        CF_HIP(launch_gemm(dt, 1, &s2, 1, G.dwu, H, F, 0.f, st));
-    }
+    CF_HIP(dw_gemm(h2, d_gate, G.dwg, H, F));
+    CF_HIP(dw_gemm(h2, d_up, G.dwu, H, F));
     void* dh2 = w.bufHb;
     {   // dh2 = d_gate*Wg^T + d_up*Wu^T   [N,H], contraction over F twice
         GemmSeg s[2] = {{d_gate, W.wg, F}, {d_up, W.wu, F}};
@@ -208,12 +208,11 @@ cf_status layer_core(const cf_layer_desc& L, const cf_saved& sv, const cf_weight
     }
     // dr = dy + rmsnorm_bwd(dh2; r, g2);  dg2
     CF_HIP(launch_rmsnorm_bwd(dt, dh2, sv.r, W.g2, idx, dy_rows, N, H, L.rms_eps, w.dr, w.dg_partial,
-                              G.dg2, st));
+                              G.dg2, st, mg));
 
     // ---- attention block: r = x + attn_out*Wo ------------------------------------
+    CF_HIP(dw_gemm(a_rows, w.dr, G.dwo, Nq, H));          // dWo = a^T * dr      [Nq,H]
     {
-        GemmSeg s{a_rows, w.dr, N};                       // dWo = a^T * dr      [Nq,H]
-        CF_HIP(launch_gemm(dt, 1, &s, 1, G.dwo, Nq, H, 0.f, st));
         GemmSeg s2{w.dr, W.wo, H};                        // da = dr * Wo^T      [N,Nq]
         CF_HIP(launch_gemm(dt, 0, &s2, 1, w.da, N, Nq, 0.f, st));
     }
@@ -232,14 +231,11 @@ cf_status layer_core(const cf_layer_desc& L, const cf_saved& sv, const cf_weight
         if (N > 0 && gemm_tn_groups_supported(dt, N, 3, Ng)) {
             const void* Bg[3] = {w.dq, w.dk, w.dv};
             void* Cg[3] = {G.dwq, G.dwk, G.dwv};
-            CF_HIP(launch_gemm_tn_groups(h1, N, H, 3, Bg, Cg, Ng, st));
+            CF_HIP(launch_gemm_tn_groups(h1, N, H, 3, Bg, Cg, Ng, st, mg ? 1.f : 0.f, mg));
         } else {
-            GemmSeg s{h1, w.dq, N};
-            CF_HIP(launch_gemm(dt, 1, &s, 1, G.dwq, H, Nq, 0.f, st));
-            GemmSeg s2{h1, w.dk, N};
-            CF_HIP(launch_gemm(dt, 1, &s2, 1, G.dwk, H, Nkv, 0.f, st));
-            GemmSeg s3{h1, w.dv, N};
-            CF_HIP(launch_gemm(dt, 1, &s3, 1, G.dwv, H, Nkv, 0.f, st));
+            CF_HIP(dw_gemm(h1, w.dq, G.dwq, H, Nq));
+            CF_HIP(dw_gemm(h1, w.dk, G.dwk, H, Nkv));
+            CF_HIP(dw_gemm(h1, w.dv, G.dwv, H, Nkv));
         }
     }
     void* dh1 = w.bufHb;
@@ -249,7 +245,7 @@ cf_status layer_core(const cf_layer_desc& L, const cf_saved& sv, const cf_weight
     }
     // dx = dr + rmsnorm_bwd(dh1; x, g1);  dg1
     CF_HIP(launch_rmsnorm_bwd(dt, dh1, sv.x, W.g1, idx, w.dr, N, H, L.rms_eps, G.dx, w.dg_partial,
-                              G.dg1, st));
+                              G.dg1, st, mg));
     return CF_OK;
 }
 
@@ -401,6 +397,7 @@ cf_status check_layer_ptrs(const cf_saved* sv, const cf_weights* W, const void* 
     }
     if ((sv->rope_cos == nullptr) != (sv->rope_sin == nullptr)) return CF_ERR_NULL;
     if (sv->rope_cos && (misaligned(sv->rope_cos) || misaligned(sv->rope_sin))) return CF_ERR_SHAPE;
+    if (G->main_grad != 0 && G->main_grad != 1) return CF_ERR_SHAPE;
     return CF_OK;
 }
 

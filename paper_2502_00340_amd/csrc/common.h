@@ -98,11 +98,13 @@ hipError_t launch_swiglu_bwd(int dtype, const void* d_act, const void* gate, con
                              void* act, hipStream_t st);
 hipError_t launch_rmsnorm_fwd(int dtype, const void* x, const void* g, const int32_t* idx,
                               int n_rows, int H, float eps, void* h, hipStream_t st);
-// dx_out = res + rmsnorm_bwd(dh; x, g); dg_partial is [rmsnorm_bwd_blocks(n_rows), H] fp32 scratch
+// dx_out = res + rmsnorm_bwd(dh; x, g); dg_partial is [rmsnorm_bwd_blocks(n_rows), H] fp32 scratch.
+// dg_acc_f32: dg_out is fp32 [H] and the gain gradient is added to it instead of written.
 int rmsnorm_bwd_blocks(int n_rows);
 hipError_t launch_rmsnorm_bwd(int dtype, const void* dh, const void* x, const void* g,
                               const int32_t* idx, const void* res, int n_rows, int H, float eps,
-                              void* dx_out, float* dg_partial, void* dg_out, hipStream_t st);
+                              void* dx_out, float* dg_partial, void* dg_out, hipStream_t st,
+                              bool dg_acc_f32 = false);
 // g[j, h*d + i] (in place, [n_rows, heads*d]): transposed rotary rotation at position idx[j] % S
 // (idx null: j % S); cos, sin are [S, d/2] fp32
 hipError_t launch_rope_bwd(int dtype, void* g, const int32_t* idx, int n_rows, int heads, int d, int S,
@@ -122,17 +124,20 @@ struct GemmSeg {
 // C[M,N] = beta*C + alpha * sum_seg op(A_seg)*op(B_seg); all matrices dense row-major.
 //   mode 0 ("NT"): A_seg [M,K], B_seg [N,K]      (C = A * B^T)
 //   mode 1 ("TN"): A_seg [K,M], B_seg [K,N]      (C = A^T * B)
+// c_f32 (bf16 dtype only): C is an fp32 matrix (a main-gradient buffer) and the accumulators are
+// added to beta*C without rounding to bf16.
 // splitk_ws (device, splitk_bytes, 16-byte aligned, may be null): scratch that lets a bf16 product
 // with one segment, few output tiles and a long K run as a split-K launch (fp32 parts summed in a
 // fixed order by a second kernel).
 hipError_t launch_gemm(int dtype, int mode, const GemmSeg* segs, int nseg, void* C, int M, int N,
                        float beta, hipStream_t st, float alpha = 1.0f, void* splitk_ws = nullptr,
-                       size_t splitk_bytes = 0);
+                       size_t splitk_bytes = 0, bool c_f32 = false);
 
 // One TN launch for up to three products that share A [K,M]: C_j [M,Ng[j]] = A^T * B_j [K,Ng[j]].
 // bf16 only, every Ng[j] a multiple of 256 (gemm_tn_groups_supported says whether it applies).
 bool gemm_tn_groups_supported(int dtype, int K, int ngroups, const int* Ng);
 hipError_t launch_gemm_tn_groups(const void* A, int K, int M, int ngroups, const void* const* Bg,
-                                 void* const* Cg, const int* Ng, hipStream_t st);
+                                 void* const* Cg, const int* Ng, hipStream_t st, float beta = 0.f,
+                                 bool c_f32 = false);
 
 }  // namespace cf

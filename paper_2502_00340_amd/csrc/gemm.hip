@@ -62,6 +62,7 @@ struct GemmArgs {
     int M, N;
     float beta;
     float alpha;    // the product is scaled by alpha before beta*C is added
+    int c_f32;      // bf16 kernels: C is fp32 (a main-gradient buffer), written without rounding
     int n_full;     // leading blocks that own a whole 256x256 tile
     int sub;        // the remaining tiles are cut into `sub` (1, 2 or 4) sub-tiles, one block each
     // Column groups (ngroups > 1, one K segment): output columns [off_j, off_j + Ng[j]) belong to a
@@ -353,8 +354,67 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
                 }
         return;
     }
-    // ---- epilogue: acc -> bf16 -> LDS C tile -> global with 16-byte stores -----------
     const float alpha = g.alpha;
+    if (g.c_f32) {
+        // ---- fp32 epilogue: the two halves of the tile rows (one per wave row) go through LDS in
+        // turn, then out as full rows of 16-byte stores, added to beta*C in fp32
+        constexpr int HP = BN * 4 + 16;                     // pitch of a staged row of floats
+        static_assert((BM / 2) * HP <= GEMM_SMEM, "fp32 staging");
+        float* C = static_cast<float*>(g.C);
+        const float beta = g.beta;
+        constexpr int CPR = BN / 4, RPP = 256 / CPR;        // 16-byte chunks per row, rows per pass
+        const int c = tid % CPR, r0 = tid / CPR;
+        const int n = n0 + c * 4;
+#pragma unroll 1
+        for (int h = 0; h < 2; ++h) {
+            lds_barrier();
+            if (wm == h) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int v4 = 0; v4 < 4; ++v4) {
+                            const int r = i * 32 + slot;
+                            const int cc = wn * (32 * TN) + j * 32 + 8 * v4 + 4 * hh;
+                            float4 o;
+                            o.x = acc[i][j][4 * v4 + 0] * alpha; o.y = acc[i][j][4 * v4 + 1] * alpha;
+                            o.z = acc[i][j][4 * v4 + 2] * alpha; o.w = acc[i][j][4 * v4 + 3] * alpha;
+                            *reinterpret_cast<float4*>(smem + r * HP + cc * 4) = o;
+                        }
+            }
+            lds_barrier();
+            if (n < g.N) {                                  // N is a multiple of 8
+                // eight rows per round: all loads of the old values are in flight before the first add
+                constexpr int RB = 8;
+                static_assert((BM / 2) % (RPP * RB) == 0, "row batches");
+#pragma unroll 1
+                for (int rb = r0; rb < BM / 2; rb += RPP * RB) {
+                    float4 old[RB], val[RB];
+#pragma unroll
+                    for (int q = 0; q < RB; ++q) {
+                        const int m = m0 + h * (BM / 2) + rb + q * RPP;
+                        old[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+                        if (beta != 0.f && m < g.M) old[q] = *reinterpret_cast<const float4*>(C + (int64_t)m * g.N + n);
+                    }
+#pragma unroll
+                    for (int q = 0; q < RB; ++q)
+                        val[q] = *reinterpret_cast<const float4*>(smem + (rb + q * RPP) * HP + c * 16);
+#pragma unroll
+                    for (int q = 0; q < RB; ++q) {
+                        const int m = m0 + h * (BM / 2) + rb + q * RPP;
+                        if (m < g.M) {
+                            val[q].x += beta * old[q].x; val[q].y += beta * old[q].y;
+                            val[q].z += beta * old[q].z; val[q].w += beta * old[q].w;
+                            *reinterpret_cast<float4*>(C + (int64_t)m * g.N + n) = val[q];
+                        }
+                    }
+                }
+            }
+        }
+        return;
+    }
+    // ---- epilogue: acc -> bf16 -> LDS C tile -> global with 16-byte stores -----------
     lds_barrier();
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -570,7 +630,7 @@ static int compute_units() {
 // Splitting pays when the 128x128 tiles cover at most half of the CUs and K is long enough that
 // every part still runs several K-steps.
 static int plan_splitk(const GemmArgs& g, int n_cu, size_t ws_bytes, int& kchunk) {
-    if (g.nseg != 1 || g.ngroups > 1) return 0;
+    if (g.nseg != 1 || g.ngroups > 1 || g.c_f32) return 0;
     const int K = g.K[0];
     const int tiles = ceil_div(g.M, 128) * ceil_div(g.N, 128);
     if (tiles * 2 > n_cu || K < 1024) return 0;
@@ -618,7 +678,8 @@ static hipError_t launch_bf16(GemmArgs& g, hipStream_t st) {
 }
 
 hipError_t launch_gemm(int dtype, int mode, const GemmSeg* segs, int nseg, void* C, int M, int N,
-                       float beta, hipStream_t st, float alpha, void* splitk_ws, size_t splitk_bytes) {
+                       float beta, hipStream_t st, float alpha, void* splitk_ws, size_t splitk_bytes,
+                       bool c_f32) {
     if (M <= 0 || N <= 0) return hipSuccess;
     GemmArgs g;
     g.nseg = 0;
@@ -631,11 +692,12 @@ hipError_t launch_gemm(int dtype, int mode, const GemmSeg* segs, int nseg, void*
     }
     for (int s = g.nseg; s < 3; ++s) { g.A[s] = nullptr; g.B[s] = nullptr; g.K[s] = 0; }
     g.C = C; g.M = M; g.N = N; g.beta = beta; g.alpha = alpha; g.n_full = 0; g.sub = 1;
+    g.c_f32 = (c_f32 && dtype == CF_BF16) ? 1 : 0;
     g.ngroups = 1;
     for (int j = 0; j < 3; ++j) { g.Bg[j] = nullptr; g.Cg[j] = nullptr; g.Ng[j] = 0; }
     if (g.nseg == 0) {
         // empty contraction: C = beta*C; only beta in {0,1} is supported by the API
-        if (beta == 0.f) return launch_fill_zero(C, (size_t)M * N * dtype_size(dtype), st);
+        if (beta == 0.f) return launch_fill_zero(C, (size_t)M * N * (c_f32 ? 4 : dtype_size(dtype)), st);
         return hipSuccess;
     }
     if (dtype == CF_BF16) {
@@ -668,7 +730,7 @@ bool gemm_tn_groups_supported(int dtype, int K, int ngroups, const int* Ng) {
 }
 
 hipError_t launch_gemm_tn_groups(const void* A, int K, int M, int ngroups, const void* const* Bg,
-                                 void* const* Cg, const int* Ng, hipStream_t st) {
+                                 void* const* Cg, const int* Ng, hipStream_t st, float beta, bool c_f32) {
     if (M <= 0) return hipSuccess;
     GemmArgs g;
     int N = 0;
@@ -683,7 +745,8 @@ hipError_t launch_gemm_tn_groups(const void* A, int K, int M, int ngroups, const
     g.ngroups = ngroups;
     g.A[0] = A; g.B[0] = Bg[0]; g.K[0] = K; g.nseg = 1;
     for (int s = 1; s < 3; ++s) { g.A[s] = nullptr; g.B[s] = nullptr; g.K[s] = 0; }
-    g.C = Cg[0]; g.M = M; g.N = N; g.beta = 0.f; g.alpha = 1.f; g.n_full = 0; g.sub = 1;
+    g.C = Cg[0]; g.M = M; g.N = N; g.beta = beta; g.alpha = 1.f; g.n_full = 0; g.sub = 1;
+    g.c_f32 = c_f32 ? 1 : 0;
     return launch_bf16<1>(g, st);
 }
 

@@ -193,8 +193,9 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ 
 
 // out[c] = sum_b partial[b,c]: a block owns 32 columns (8 lanes x 4 columns), 32 row groups
 // stride through the partials with 16-byte loads, many in flight; H is a multiple of 4.
-// The order of the additions is fixed, so the result is reproducible.
-template <typename T>
+// The order of the additions is fixed, so the result is reproducible.  ACC: out is fp32 and the
+// sum is added to it (main-gradient accumulation).
+template <typename T, bool ACC = false>
 __global__ __launch_bounds__(256) void colsum_finish_kernel(const float* __restrict__ partial,
                                                             int nblk, int H, T* __restrict__ out) {
     __shared__ float red[32][33];
@@ -215,7 +216,8 @@ __global__ __launch_bounds__(256) void colsum_finish_kernel(const float* __restr
         float t = 0.f;
 #pragma unroll
         for (int r = 0; r < 32; ++r) t += red[r][threadIdx.x];
-        out[blockIdx.x * 32 + threadIdx.x] = from_f32<T>(t);
+        if (ACC) out[blockIdx.x * 32 + threadIdx.x] += from_f32<T>(t);
+        else out[blockIdx.x * 32 + threadIdx.x] = from_f32<T>(t);
     }
 }
 
@@ -333,17 +335,19 @@ static void rmsnorm_bwd_dispatch(int nv, int nblk, hipStream_t st, const void* d
 
 hipError_t launch_rmsnorm_bwd(int dtype, const void* dh, const void* x, const void* g,
                               const int32_t* idx, const void* res, int n_rows, int H, float eps,
-                              void* dx_out, float* dg_partial, void* dg_out, hipStream_t st) {
+                              void* dx_out, float* dg_partial, void* dg_out, hipStream_t st, bool dg_acc_f32) {
     const int nblk = rmsnorm_bwd_blocks(n_rows);
-    if (n_rows <= 0) return launch_fill_zero(dg_out, (size_t)H * dtype_size(dtype), st);
+    if (n_rows <= 0) return dg_acc_f32 ? hipSuccess : launch_fill_zero(dg_out, (size_t)H * dtype_size(dtype), st);
     const int vn = dtype == CF_F32 ? 4 : 8;
     const int nv = ceil_div(H / vn, 256);           // 16-byte vectors per thread (<= RMS_MAX_VEC, checked by the API)
     if (dtype == CF_F32) {
         rmsnorm_bwd_dispatch<float>(nv, nblk, st, dh, x, g, idx, res, n_rows, H, eps, dx_out, dg_partial);
-        colsum_finish_kernel<float><<<ceil_div(H, 32), 256, 0, st>>>(dg_partial, nblk, H, (float*)dg_out);
+        if (dg_acc_f32) colsum_finish_kernel<float, true><<<ceil_div(H, 32), 256, 0, st>>>(dg_partial, nblk, H, (float*)dg_out);
+        else colsum_finish_kernel<float><<<ceil_div(H, 32), 256, 0, st>>>(dg_partial, nblk, H, (float*)dg_out);
     } else {
         rmsnorm_bwd_dispatch<bf16_t>(nv, nblk, st, dh, x, g, idx, res, n_rows, H, eps, dx_out, dg_partial);
-        colsum_finish_kernel<bf16_t><<<ceil_div(H, 32), 256, 0, st>>>(dg_partial, nblk, H, (bf16_t*)dg_out);
+        if (dg_acc_f32) colsum_finish_kernel<float, true><<<ceil_div(H, 32), 256, 0, st>>>(dg_partial, nblk, H, (float*)dg_out);
+        else colsum_finish_kernel<bf16_t><<<ceil_div(H, 32), 256, 0, st>>>(dg_partial, nblk, H, (bf16_t*)dg_out);
     }
     return hipGetLastError();
 }

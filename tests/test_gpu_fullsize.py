@@ -47,8 +47,25 @@ def _run(index, rho=None, shape=None, rope=False):
     return plan, p, sv, W, dy
 
 
+def _check_main_grad(plan, p, sv, W, dy):
+    """fp32 main-gradient buffers at full size: two accumulating calls from zero hold exactly twice
+    the fp32 accumulators (x + x is exact), so their half, rounded to bf16, must equal the ordinary
+    call's bf16 outputs (already checked against the oracle) bit for bit."""
+    print("[case]   main-grad accumulation, two calls", flush=True)
+    mask = torch.from_numpy(p.mask).to(DEV)
+    mg = Bn.LayerBackward(p.desc(), device=DEV, main_grad=True)
+    n = mg.filtered(sv, W, dy, mask)
+    mg.filtered(sv, W, dy, mask)
+    torch.cuda.synchronize()
+    for name in Hn.GRADS:
+        assert mg.grads[name].dtype == torch.float32
+        assert torch.equal((mg.grads[name] * 0.5).to(torch.bfloat16), plan.grads[name]), name
+    assert torch.equal(mg.grads["dx"][:n], plan.grads["dx"][:n])
+
+
 def test_config1_tinyllama_full():
-    _run(1)
+    plan, p, sv, W, dy = _run(1)
+    _check_main_grad(plan, p, sv, W, dy)
 
 
 def test_config2_llama3b_ratio07():
@@ -72,10 +89,11 @@ def test_config4_40b_ragged():
 def test_tensor_parallel_share_of_the_8b_layer_with_rotary():
     """The per-GPU share of the 8B layer under 8-way tensor parallelism (the setting the
     paper timed that model in): 4 query heads, 1 KV head, F/8 = 1792, full hidden size;
-    skinny projections, and q/k are rotated tensors."""
+    skinny projections, and q/k are rotated tensors; also with fp32 main-gradient buffers."""
     shape = WL.LayerShape("llama31_8b_tp8_share", B=2, S=4096, H=4096, Hq=4, Hkv=1, d=128, F=1792,
                           dtype="bf16", mask_kind="spans")
-    _run(5, shape=shape, rope=True)
+    plan, p, sv, W, dy = _run(5, shape=shape, rope=True)
+    _check_main_grad(plan, p, sv, W, dy)
 
 
 def test_lora_rank64_on_the_3b_layer():

@@ -270,6 +270,46 @@ def test_layer_small_bf16(shape, rho):
     Hn.check_layer(p, gotd, p.oracle(dense=True), None, Hn.TOL["bf16"])
 
 
+MAIN_GRAD_SHAPES = [
+    SMALL_BF16, SMALL_BF16_D128, SMALL_BF16_GROUPED,
+    WL.LayerShape("main_grad_f32", B=2, S=96, H=128, Hq=2, Hkv=1, d=64, F=256, dtype="f32"),
+]
+
+
+@pytest.mark.parametrize("shape", MAIN_GRAD_SHAPES, ids=lambda s: s.name)
+def test_layer_main_grad_accumulation(shape):
+    """main_grad = 1: the parameter gradients are fp32 buffers the calls add to.  Start from random
+    buffers G0, run the filtered backward twice and the dense one once: the buffers must hold
+    G0 + 2*filtered + dense gradients of the oracle; dx is the last call's, as without the flag."""
+    say("layer main-grad %s" % shape.name)
+    p = Hn.Problem(shape, 91, "independent", rho=0.5)
+    ref, refd = p.oracle(), p.oracle(dense=True)
+    sv, W, dy, mask = p.device_tensors(DEV)
+    plan = Bn.LayerBackward(p.desc(), device=DEV, main_grad=True)
+    rng = np.random.default_rng(92)
+    g0 = {}
+    for name in Hn.GRADS:
+        assert plan.grads[name].dtype == torch.float32
+        g0[name] = (rng.standard_normal(ref[name].shape) * ref[name].std()).astype(np.float32)
+        plan.grads[name].copy_(torch.from_numpy(g0[name]))
+    n = plan.filtered(sv, W, dy, mask)
+    plan.filtered(sv, W, dy, mask)
+    torch.cuda.synchronize()
+    ridx = np.flatnonzero(p.mask.reshape(-1))
+    assert n == len(ridx)
+    assert Hn.rel_fro(Hn.to_np(plan.grads["dx"][:n]), ref["dx"][ridx]) <= Hn.TOL[shape.dtype]
+    plan.dense(sv, W, dy)
+    torch.cuda.synchronize()
+    assert Hn.rel_fro(Hn.to_np(plan.grads["dx"]), refd["dx"]) <= Hn.TOL[shape.dtype]
+    errs = {}
+    for name in Hn.GRADS:
+        added = Hn.to_np(plan.grads[name]).astype(np.float64) - g0[name]
+        errs[name] = Hn.rel_fro(added, 2.0 * ref[name] + refd[name])
+    say("  " + " ".join("%s=%.1e" % kv for kv in errs.items()))
+    bad = {k: v for k, v in errs.items() if not (v <= Hn.TOL[shape.dtype])}
+    assert not bad, bad
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_layer_invariants_on_gpu_outputs(dtype):
     """Keep ratio 1 reproduces the dense call bit for bit (same kernels, same
@@ -391,7 +431,7 @@ def test_no_write_outside_the_outputs_and_the_workspace():
     raw["idx"], plan.idx = guarded(plan.idx)
     raw["cu"], plan.cu_kept = guarded(plan.cu_kept)
     raw["ws"], plan.ws = guarded(plan.ws)
-    plan._g = Bn.Grads(*[plan.grads[n].data_ptr() for n, _ in Bn.Grads._fields_])
+    plan._g = Bn.Grads(*[plan.grads[n].data_ptr() for n in Bn.GRAD_NAMES])
     n = plan.filtered(sv, W, dy, mask)
     dyk = Bn.gather_rows(dy, plan.idx, n)
     plan.compact(sv, W, dyk, plan.idx, plan.cu_kept, n)
