@@ -120,6 +120,8 @@ def test_layer_argument_errors(L):
     assert f(C.byref(_desc(H=250)), C.byref(sv), C.byref(w), FAKE, FAKE, C.byref(g), None, None, C.byref(n), FAKE, ok_ws, None) == 2
     sv_rope = Bn.Saved(*([0x10000] * 9 + [0x10000, None]))      # one rotary table without the other
     assert f(C.byref(d), C.byref(sv_rope), C.byref(w), FAKE, FAKE, C.byref(g), None, None, C.byref(n), FAKE, ok_ws, None) == 1
+    g_bad = Bn.Grads(*([0x10000] * 10 + [2]))                   # main_grad is 0 or 1
+    assert f(C.byref(d), C.byref(sv), C.byref(w), FAKE, FAKE, C.byref(g_bad), None, None, C.byref(n), FAKE, ok_ws, None) == 2
     fc = L.cf_layer_bwd_compact
     assert fc(C.byref(d), C.byref(sv), C.byref(w), FAKE, None, FAKE, 4, C.byref(g), FAKE, ok_ws, None) == 1
     assert fc(C.byref(d), C.byref(sv), C.byref(w), None, FAKE, FAKE, 4, C.byref(g), FAKE, ok_ws, None) == 1
