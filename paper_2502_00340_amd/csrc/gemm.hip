@@ -105,7 +105,7 @@ __device__ __forceinline__ void tile_coords(int l, int tiles_m, int tiles_n, int
 // One output tile of (64*TM) x (64*TN) at (m0, n0).  SPLIT: the block contracts only k in
 // [kbeg, kend) of the single segment and stores its fp32 accumulators, unscaled, to `part_out`
 // ([M, N] fp32); a second kernel adds the parts up.
-template <int MODE, int TM, int TN, bool SPLIT = false>
+template <int MODE, int TM, int TN, bool SPLIT = false, bool CF32 = false>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const int n0, unsigned char* smem,
                                           const int kbeg = 0, const int kend = 0, float* part_out = nullptr) {
     constexpr int BM = 64 * TM, BN = 64 * TN, KB = 32, NST = GEMM_STAGES, STAGE = GEMM_STAGE_BYTES;
@@ -355,7 +355,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
         return;
     }
     const float alpha = g.alpha;
-    if (g.c_f32) {
+    if (CF32) {
         // ---- fp32 epilogue: the two halves of the tile rows (one per wave row) go through LDS in
         // turn, then out as full rows of 16-byte stores, added to beta*C in fp32
         constexpr int HP = BN * 4 + 16;                     // pitch of a staged row of floats
@@ -459,9 +459,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
     }
 }
 
-template <int MODE>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
-    extern __shared__ __align__(16) unsigned char smem[];
+template <int MODE, bool CF32>
+__device__ __forceinline__ void gemm_bf16_block(GemmArgs& g, unsigned char* smem) {
     const int tiles_m = (g.M + 255) / 256, tiles_n = (g.N + 255) / 256;
     const int pid = blockIdx.x;
     int bm, bn, m0, n0, cut = 1;
@@ -487,9 +486,22 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
         g.N = j == 0 ? g.Ng[0] : (j == 1 ? g.Ng[1] : g.Ng[2]);
         n0 -= off;
     }
-    if (cut == 1) gemm_tile<MODE, 4, 4>(g, m0, n0, smem);
-    else if (cut == 2) gemm_tile<MODE, 4, 2>(g, m0, n0, smem);
-    else gemm_tile<MODE, 2, 2>(g, m0, n0, smem);
+    if (cut == 1) gemm_tile<MODE, 4, 4, false, CF32>(g, m0, n0, smem);
+    else if (cut == 2) gemm_tile<MODE, 4, 2, false, CF32>(g, m0, n0, smem);
+    else gemm_tile<MODE, 2, 2, false, CF32>(g, m0, n0, smem);
+}
+
+template <int MODE>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    gemm_bf16_block<MODE, false>(g, smem);
+}
+
+// The same with fp32 output (main-gradient buffers): C is float, added to beta*C without rounding.
+template <int MODE>
+__global__ __launch_bounds__(256) void gemm_bf16_f32out_kernel(GemmArgs g) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    gemm_bf16_block<MODE, true>(g, smem);
 }
 
 // Split-K variant for outputs with too few tiles to fill the chip (a skinny M or N with a long
@@ -668,12 +680,16 @@ static hipError_t launch_bf16(GemmArgs& g, hipStream_t st) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<MODE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_SMEM);
         if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_f32out_kernel<MODE>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_SMEM);
+        if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int tiles = ceil_div(g.M, 256) * ceil_div(g.N, 256);
     plan_tiles(tiles, compute_units(), g.n_full, g.sub);
     const int grid = g.n_full + (tiles - g.n_full) * g.sub;
-    gemm_bf16_kernel<MODE><<<grid, 256, GEMM_SMEM, st>>>(g);
+    if (g.c_f32) gemm_bf16_f32out_kernel<MODE><<<grid, 256, GEMM_SMEM, st>>>(g);
+    else gemm_bf16_kernel<MODE><<<grid, 256, GEMM_SMEM, st>>>(g);
     return hipGetLastError();
 }
 
