@@ -79,9 +79,9 @@ typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4_t;
 typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8_t;
 typedef __attribute__((address_space(3))) s16x4_t* lds_s16x4_ptr;
 
-static constexpr int GEMM_STAGES = 5;
+static constexpr int GEMM_STAGES = 4;
 static constexpr int GEMM_STAGE_BYTES = 32768;
-static constexpr int GEMM_SMEM = GEMM_STAGES * GEMM_STAGE_BYTES;   // 160 KB: the whole LDS of a CU
+static constexpr int GEMM_SMEM = 160 * 1024;    // the whole LDS of a CU: four operand stages; the C tile staging of the epilogue needs 132 KB
 
 // Position l of a block in the logical order of its group of n blocks: XCD x (block id
 // mod 8) takes the x-th contiguous share of the order.
@@ -108,7 +108,7 @@ __device__ __forceinline__ void tile_coords(int l, int tiles_m, int tiles_n, int
 template <int MODE, int TM, int TN, bool SPLIT = false, bool CF32 = false>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const int n0, unsigned char* smem,
                                           const int kbeg = 0, const int kend = 0, float* part_out = nullptr) {
-    constexpr int BM = 64 * TM, BN = 64 * TN, KB = 32, NST = GEMM_STAGES, STAGE = GEMM_STAGE_BYTES;
+    constexpr int BM = 64 * TM, BN = 64 * TN, KB = 32, STAGE = GEMM_STAGE_BYTES;
     constexpr int A_BYTES = BM * KB * 2;                // B tile follows the A tile inside a stage
     constexpr int NU = TM + TN;                         // 1 KB wave-loads per wave per K-step: TM for A, TN for B
     constexpr int NQ = TM * TN, NF = TM + TN;           // MFMAs and fragment reads per 16-wide sub-step
@@ -219,118 +219,158 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
     };
 
     const unsigned lds0 = __builtin_amdgcn_readfirstlane(lds_addr_of(smem) + wave * 1024);
-    // wave-load u of K-step `second` (0 / 1) of the pair at (seg, k0): u < TM -> A tile, else B tile; tile
-    // bytes [(4*i + wave) KB, +1 KB).  NT: 16 rows x 4 chunks, the chunk a lane fetches undoes the XOR
-    // swizzle of its LDS slot.  TN: 1024 / (2*rows) k-rows of the tile.
-    auto dma_one = [&](int stage, int u, int second) __attribute__((always_inline)) {
-        const bool isA = u < TM;
-        const int i = isA ? u : u - TM;
-        const unsigned dst = lds0 + stage * STAGE + (isA ? 0 : A_BYTES) + i * 4096;
-        if (isA) dma16s(dst, rsA, second ? v1[u] : v0[u], second ? ka1 : ka0);
-        else dma16s(dst, rsB, second ? v1[u] : v0[u], second ? kb1 : kb0);
+    // wave-load U of K-step SEC (0 / 1) of the pair at (seg, k0) into stage S: U < TM -> A tile, else B
+    // tile; tile bytes [(4*i + wave) KB, +1 KB).  NT: 16 rows x 4 chunks, the chunk a lane fetches undoes
+    // the XOR swizzle of its LDS slot; the second K-step of a pair is the other half of the same
+    // 128-byte lines (instruction offset 64).  TN: 1024 / (2*rows) k-rows of the tile.
+    auto dma_one = [&](auto S, auto U, auto SEC) __attribute__((always_inline)) {
+        constexpr int s = decltype(S)::value, u = decltype(U)::value, sec = decltype(SEC)::value;
+        constexpr bool isA = u < TM;
+        constexpr int i = isA ? u : u - TM;
+        constexpr int dst = s * STAGE + (isA ? 0 : A_BYTES) + i * 4096;
+        // the instruction offset moves the LDS destination along with the global address, so the
+        // M0 base of the second K-step is set back by the same amount
+        if (MODE == 0) dma16i<dst - (sec ? KB * 2 : 0), sec ? KB * 2 : 0>(lds0, isA ? rsA : rsB, sec ? v1[u] : v0[u], ka0);
+        else dma16i<dst, 0>(lds0, isA ? rsA : rsB, sec ? v1[u] : v0[u], isA ? (sec ? ka1 : ka0) : (sec ? kb1 : kb0));
     };
 
-    // ---- LDS -> fragments: fragment u < TM is 32-row block u of the wave's A rows, else of its B rows
+    // ---- LDS -> fragments: fragment u < TM is 32-row block u of the wave's A rows, else of its B rows.
+    // An LDS address is a per-lane base register that never changes plus a compile-time constant
+    // (stage, sub-step, block) in the instruction's 16-bit offset field; stages 2 and 3 lie past that
+    // field's reach from the base of stage 0 and get base registers of their own.
+    typedef __attribute__((address_space(3))) unsigned char* lds_u8_ptr;
+    typedef const __attribute__((address_space(3))) u32x4_t* lds_u32x4_cptr;
+    constexpr int NBASE = MODE == 0 ? 4 : NU;       // NT: (A, B) x sub-step; TN: one per block (the swizzle mixes the block in)
+    unsigned fbase[NBASE][2];
+    {
+        const unsigned s0 = lds_addr_of(smem);
+        if (MODE == 0) {
+            const int nt_sw = (slot >> 2) & 3;
+#pragma unroll
+            for (int ab = 0; ab < 2; ++ab)
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) {
+                    const int wrow = ab == 0 ? wm * (32 * TM) : wn * (32 * TN);
+                    const unsigned v = s0 + (ab == 0 ? 0 : A_BYTES) + (wrow + slot) * 64 + (((ks * 2 + hh) ^ nt_sw) << 4);
+                    fbase[ab * 2 + ks][0] = v;
+                    fbase[ab * 2 + ks][1] = v + 2 * STAGE;
+                }
+        } else {
+#pragma unroll
+            for (int u = 0; u < NU; ++u) {
+                const bool isA = u < TM;
+                const int i = isA ? u : u - TM;
+                const int W2 = (isA ? BM : BN) * 2;                 // bytes per k-row
+                const int row0 = isA ? wm * (32 * TM) + i * 32 : wn * (32 * TN) + i * 32;
+                const int kl = 8 * hh + ((lane & 15) >> 2);         // k within a 16-wide sub-step (and kl + 4)
+                const int lc = row0 / 8 + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+                const int sw = (kl & 3) << 2;                       // the same for k and k + 4
+                const unsigned v = s0 + (isA ? 0 : A_BYTES) + kl * W2 + ((lc ^ sw) << 4) + (lane & 1) * 8;
+                fbase[u][0] = v;
+                fbase[u][1] = v + 2 * STAGE;
+            }
+        }
+    }
     bf16x8_t fa[2][TM], fb[2][TN];
-    const int nt_sw = (slot >> 2) & 3;
-    auto frag_one = [&](int stage, int ks, int u, int buf) __attribute__((always_inline)) {
-        const bool isA = u < TM;
-        const int i = isA ? u : u - TM;
-        const unsigned char* tile = smem + stage * STAGE + (isA ? 0 : A_BYTES);
-        const int row0 = isA ? wm * (32 * TM) + i * 32 : wn * (32 * TN) + i * 32;
+    auto frag_one = [&](auto S, auto KS, auto U, auto BUF) __attribute__((always_inline)) {
+        constexpr int s = decltype(S)::value, ks = decltype(KS)::value, u = decltype(U)::value, buf = decltype(BUF)::value;
+        constexpr bool isA = u < TM;
+        constexpr int i = isA ? u : u - TM;
+        constexpr int win = s >> 1, soff = (s & 1) * STAGE;
         bf16x8_t f;
         if (MODE == 0) {
-            f = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(
-                                                 tile + (row0 + slot) * 64 + (((ks * 2 + hh) ^ nt_sw) << 4)));
+            const lds_u8_ptr p = reinterpret_cast<lds_u8_ptr>(fbase[(isA ? 0 : 2) + ks][win]);
+            f = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<lds_u32x4_cptr>(p + (soff + i * 2048)));
         } else {
-            const int W2 = (isA ? BM : BN) * 2;                 // bytes per k-row
-            const int k = ks * 16 + 8 * hh + ((lane & 15) >> 2);
-            const int lc = row0 / 8 + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
-            const int sub = (lane & 1) * 8;
-            const int sw = (k & 3) << 2;                        // the same for k and k + 4
-            const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (lds_s16x4_ptr)(tile + k * W2 + ((lc ^ sw) << 4) + sub));
-            const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (lds_s16x4_ptr)(tile + (k + 4) * W2 + ((lc ^ sw) << 4) + sub));
+            constexpr int W2 = (isA ? BM : BN) * 2;
+            const lds_u8_ptr p = reinterpret_cast<lds_u8_ptr>(fbase[u][win]);
+            const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + (soff + ks * 16 * W2)));
+            const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + (soff + ks * 16 * W2 + 4 * W2)));
             f = __builtin_bit_cast(bf16x8_t, (s16x8_t)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         }
         if (isA) fa[buf][i] = f;
         else fb[buf][i] = f;
     };
     // MFMA q of a sub-step: D = Bfrag x Afrag, lane = output row, registers = 4-column groups
-    auto mma_one = [&](int q, int buf) __attribute__((always_inline)) {
-        const int i = q / TN, j = q % TN;
+    auto mma_one = [&](auto Q, auto BUF) __attribute__((always_inline)) {
+        constexpr int q = decltype(Q)::value, buf = decltype(BUF)::value;
+        constexpr int i = q / TN, j = q % TN;
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][j], fa[buf][i], acc[i][j], 0, 0, 0);
     };
-    // One 16-wide sub-step: NQ MFMAs on fragment buffer `buf`; spread evenly between them, the NF
-    // fragments of (stage ns, sub-step nks) go into the other buffer.  with_dma: also the 2*NU
-    // wave-loads of the pair at (seg, k0) (into stages d0, d1), the two halves of each 128-byte
-    // line of an NT operand row in adjacent instructions.
-    auto substep = [&](int buf, int ns, int nks, bool with_dma, int d0, int d1) __attribute__((always_inline)) {
-#pragma unroll
-        for (int q = 0; q < NQ; ++q) {
-            if (with_dma) {
-#pragma unroll
-                for (int e = 0; e < 2 * NU; ++e)
-                    if ((e * NQ) / (2 * NU) == q) dma_one((e & 1) ? d1 : d0, e >> 1, e & 1);
+    // One 16-wide sub-step: NQ MFMAs on fragment buffer BUF; spread evenly between them, the NF
+    // fragments of (stage NS, sub-step NKS) go into the other buffer.  DMA = 1 / 2: also the first /
+    // second half of the 2*NU wave-loads of the pair at (seg, k0) (K-steps into stages D0, D1), the
+    // two halves of each 128-byte line of an NT operand row in adjacent instructions.
+    auto substep = [&](auto BUF, auto NS, auto NKS, auto DMA, auto D0, auto D1) __attribute__((always_inline)) {
+        constexpr int buf = decltype(BUF)::value, dma = decltype(DMA)::value;
+        static_for<NQ>([&](auto Q) __attribute__((always_inline)) {
+            constexpr int q = decltype(Q)::value;
+            if constexpr (dma != 0) {
+                static_for<NU>([&](auto E) __attribute__((always_inline)) {
+                    constexpr int e = decltype(E)::value + (dma - 1) * NU;
+                    if constexpr ((decltype(E)::value * NQ) / NU == q)
+                        dma_one(ic<(e & 1) ? decltype(D1)::value : decltype(D0)::value>{}, ic<(e >> 1)>{}, ic<(e & 1)>{});
+                });
             }
-#pragma unroll
-            for (int f = 0; f < NF; ++f)
-                if ((f * NQ) / NF == q) frag_one(ns, nks, f, buf ^ 1);
+            static_for<NF>([&](auto F) __attribute__((always_inline)) {
+                constexpr int f = decltype(F)::value;
+                if constexpr ((f * NQ) / NF == q) frag_one(NS, NKS, F, ic<(buf ^ 1)>{});
+            });
             CF_SCHED_FENCE();
-            mma_one(q, buf);
+            mma_one(Q, BUF);
             CF_SCHED_FENCE();
-        }
+        });
     };
-    // loads of the pair at (seg, k0) outside the MFMA stream (prologue)
-    auto issue_pair = [&](int d0, int d1) __attribute__((always_inline)) {
+    // loads of the pair at (seg, k0) outside the MFMA stream (prologue): all of them, or the first half
+    auto issue_pair = [&](auto D0, auto D1, auto HALF) __attribute__((always_inline)) {
         prepare_pair();
-#pragma unroll
-        for (int u = 0; u < NU; ++u) {
-            dma_one(d0, u, 0);
-            dma_one(d1, u, 1);
-        }
+        static_for<(decltype(HALF)::value ? NU : 2 * NU)>([&](auto E) __attribute__((always_inline)) {
+            constexpr int e = decltype(E)::value;
+            dma_one(ic<(e & 1) ? decltype(D1)::value : decltype(D0)::value>{}, ic<(e >> 1)>{}, ic<(e & 1)>{});
+        });
     };
-    // One pair of K-steps s, s+1 in stages st, st+1 (mod 5)
-    auto pair_body = [&](int st) __attribute__((always_inline)) {
-        const int st1 = st + 1 >= NST ? st + 1 - NST : st + 1;
-        const int st2 = st1 + 1 >= NST ? st1 + 1 - NST : st1 + 1;
-        const int st3 = st2 + 2 >= NST ? st2 + 2 - NST : st2 + 2;      // (s+4) % 5
-        // K-step s (stage st): no loads, no barrier: K-step s+1 was published together with
-        // K-step s at the barrier of the previous pair
-        substep(0, st, 1, false, 0, 0);
-        substep(1, st1, 0, false, 0, 0);
+    // One pair of K-steps s, s+1 in stages ST, ST+1 of the ring of four; the next pair lies in the
+    // other two stages, and the loads of the pair after that go back into ST, ST+1 once the barrier
+    // has retired them.  The loop body is two pairs, so every stage is a compile-time constant.
+    // The loads of a pair are issued in two halves, right after the barrier that frees their stages
+    // and in the sub-step after that, which halves the burst that the load path sees; the second
+    // half still has two sub-steps to land before the next barrier.
+    auto pair_body = [&](auto ST) __attribute__((always_inline)) {
+        constexpr int st = decltype(ST)::value, st1 = st + 1, st2 = (st + 2) & 3;
+        // K-step s (stage st): no barrier: K-step s+1 was published together with K-step s at the
+        // barrier of the previous pair.  Second half of the loads of K-steps s+2, s+3.
+        substep(ic<0>{}, ic<st>{}, ic<1>{}, ic<2>{}, ic<st2>{}, ic<st2 + 1>{});
+        advance_pair();
+        substep(ic<1>{}, ic<st1>{}, ic<0>{}, ic<0>{}, ic<0>{}, ic<0>{});
         // K-step s+1 (stage st1)
-        substep(0, st1, 1, false, 0, 0);
+        substep(ic<0>{}, ic<st1>{}, ic<1>{}, ic<0>{}, ic<0>{}, ic<0>{});
         prepare_pair();
         wait_vmcnt<0>();            // K-steps s+2, s+3 have landed (nothing else is in flight)
-        lds_barrier();              // ... and every wave is done with stages st and (s+4)%5
-        substep(1, st2, 0, true, st3, st);      // loads of K-steps s+4 -> st3, s+5 -> st
-        advance_pair();
+        lds_barrier();              // ... and every wave is done with stages st and st1
+        substep(ic<1>{}, ic<st2>{}, ic<0>{}, ic<1>{}, ic<st>{}, ic<st1>{});     // first half of the loads of K-steps s+4, s+5
     };
 
-    // K-steps of 32 including the zero K-step that pads a segment with an odd count
-    const int steps = SPLIT ? 2 * ((kend - kbeg + 2 * KB - 1) / (2 * KB))
-                            : 2 * ((g.K[0] + 2 * KB - 1) / (2 * KB) + (g.K[1] + 2 * KB - 1) / (2 * KB) +
-                                   (g.K[2] + 2 * KB - 1) / (2 * KB));
-    if (steps > 0) {
+    // pairs of K-steps, a segment with an odd number of K-steps padded with a zero K-step
+    const int npairs = SPLIT ? (kend - kbeg + 2 * KB - 1) / (2 * KB)
+                             : (g.K[0] + 2 * KB - 1) / (2 * KB) + (g.K[1] + 2 * KB - 1) / (2 * KB) +
+                                   (g.K[2] + 2 * KB - 1) / (2 * KB);
+    if (npairs > 0) {
         open_segment(0);
         if (SPLIT) {                    // the block's K range stands for the segment
             k0 = kbeg;
             Kseg = kend;
         }
-        issue_pair(0, 1);
+        issue_pair(ic<0>{}, ic<1>{}, ic<0>{});
         advance_pair();
-        issue_pair(2, 3);
-        advance_pair();
-        wait_vmcnt<2 * NU>();           // K-steps 0 and 1 have landed; 2 and 3 may be in flight
+        issue_pair(ic<2>{}, ic<3>{}, ic<1>{});      // the loop's first sub-step issues the other half
+        wait_vmcnt<NU>();               // K-steps 0 and 1 have landed; half of 2 and 3 may be in flight
         lds_barrier();
-#pragma unroll
-        for (int u = 0; u < NF; ++u) frag_one(0, 0, u, 0);
-        int st = 0;                     // stage of K-step s
-        for (int s = 0; s < steps; s += 2) {
-            pair_body(st);
-            st = st + 2 >= NST ? st + 2 - NST : st + 2;
+        static_for<NF>([&](auto U) __attribute__((always_inline)) { frag_one(ic<0>{}, ic<0>{}, U, ic<0>{}); });
+        // two pairs per iteration; an odd count runs one pair of zero K-steps (loads past the last
+        // segment return zeros)
+        for (int p = 0; p < npairs; p += 2) {
+            pair_body(ic<0>{});
+            pair_body(ic<2>{});
         }
         wait_vmcnt<0>();
     }

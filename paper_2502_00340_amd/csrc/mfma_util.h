@@ -2,6 +2,8 @@
 // LDS-only barrier, manual vmcnt waits and the global -> LDS 16-byte-per-lane load.
 #pragma once
 
+#include <utility>
+
 #include "common.h"
 
 namespace cf {
@@ -89,6 +91,39 @@ __device__ __forceinline__ void dma16s(unsigned lds_base /*wave-uniform*/, i32x4
                  : "s"(lds_base), "v"(voffset), "s"(rsrc), "s"(soffset)
                  : "memory");
 }
+
+// The same with the LDS destination as a wave-uniform base plus a compile-time byte offset (one
+// scalar add straight into M0) and a compile-time offset on the global address (the instruction's
+// 12-bit offset field, which takes part in the descriptor's range check and is ALSO added to the
+// LDS destination: lane l writes [lds_base + LDS_IMM + INST_OFF + 16*l, +16)).  With one wave per SIMD
+// every scalar or vector ALU instruction between two MFMAs costs issue time, so the load carries
+// as few of them as the hardware allows.  All scalar operands must be wave-uniform values.
+template <int LDS_IMM, int INST_OFF>
+__device__ __forceinline__ void dma16i(unsigned lds_base, i32x4_t rsrc, unsigned voffset, unsigned soffset) {
+    static_assert(INST_OFF >= 0 && INST_OFF < 4096, "12-bit instruction offset");
+    // say that the scalar operands are uniform (free when the compiler already knows)
+    lds_base = __builtin_amdgcn_readfirstlane(lds_base);
+    soffset = __builtin_amdgcn_readfirstlane(soffset);
+    rsrc.x = __builtin_amdgcn_readfirstlane(rsrc.x);
+    rsrc.y = __builtin_amdgcn_readfirstlane(rsrc.y);
+    rsrc.z = __builtin_amdgcn_readfirstlane(rsrc.z);
+    rsrc.w = __builtin_amdgcn_readfirstlane(rsrc.w);
+    asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tbuffer_load_dwordx4 %2, %3, %4 offen offset:%5 lds"
+                 :
+                 : "s"(lds_base), "n"(LDS_IMM), "v"(voffset), "s"(rsrc), "s"(soffset), "n"(INST_OFF)
+                 : "memory", "scc");
+}
+
+// Compile-time loop: f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N-1>{})
+template <typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+template <int V> using ic = std::integral_constant<int, V>;
 
 __device__ __forceinline__ unsigned lds_addr_of(const void* p) {
     return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
