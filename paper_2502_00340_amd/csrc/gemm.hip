@@ -18,20 +18,30 @@
 //     of full tiles and one of half tiles instead of 4 rounds).  Within each group
 //     the 8 XCDs (block id mod 8) take contiguous runs of a band-major tile order,
 //     so the blocks resident on one XCD share operand panels in that XCD's L2.
-//   * Operand tiles move in K-steps of 32 through a ring of five 32 KB LDS stages,
-//     filled by buffer_load ... lds (16 bytes per lane, no register hop).  The
-//     loads of two consecutive K-steps (one whole 128-byte line of every NT operand
-//     row) are issued back to back, a full 64-wide step ahead of the barrier that
-//     publishes them; completion is tracked with vmcnt.  Ragged edges come from the
-//     buffer descriptor's range check, which returns zeros, so there are no
-//     branches around loads.
+//   * Operand tiles move in K-steps of 32 through a ring of four 32 KB LDS stages,
+//     filled by buffer_load ... lds (16 bytes per lane, no register hop).  K-steps are
+//     handled in pairs (64 k: one whole 128-byte line of every NT operand row, fetched
+//     by two adjacent instructions); a pair is loaded two pairs ahead, into the two
+//     stages that the barrier of the pair being computed has just retired; completion
+//     is tracked with vmcnt.  Ragged edges come from the buffer descriptor's range
+//     check, which returns zeros, so there are no branches around loads.
 //   * One LDS barrier per 64 K (four 16-wide sub-steps); the fragments of the next
 //     sub-step are read ahead of the MFMAs of the current one, and the instruction
 //     stream is laid out by hand so that no burst of memory instructions stands
-//     between two MFMAs.  With one wave per SIMD every instruction between two MFMAs
-//     costs MFMA issue time, so the stream is kept lean: a load takes its per-lane
-//     offset from a register that is fixed for the whole K segment, the K position
-//     being the instruction's scalar offset.
+//     between two MFMAs.  The loop body is two pairs, which makes every stage a
+//     compile-time constant: an LDS read is a loop-invariant per-lane base register
+//     plus an instruction offset, a load sets M0 with one scalar add, takes its
+//     per-lane offset from a register that is fixed for the whole K segment and its K
+//     position from the instruction's scalar offset, so the steady state has no vector
+//     ALU instruction besides the MFMAs.
+//   * What bounds the loop (measured with per-wave cycle counters): not the fragment
+//     reads (removing them changes nothing), not the waits at the barrier (3 %), but the
+//     global -> LDS loads: a CU sustains only so many bytes in flight, so 64 KB per pair
+//     cost about four average load latencies however the loads are issued.  Issuing a
+//     pair's loads in two halves (after the barrier, and one sub-step later) instead
+//     of one burst brought the pair from 2950 to 2660 cycles (2048 of them MFMA
+//     time); without any loads it takes 2250.  Two waves per SIMD (eight waves of
+//     128x64) take the same 2660 cycles, so one wave per SIMD stays.
 //   * NT stage: [rows][32 k], 64-byte rows, 16-byte chunk index XOR (row/4)%4, which
 //     makes the 16 lanes of a ds_read_b128 hit distinct banks; a lane of the loading
 //     wave picks the global chunk that belongs in its (fixed) LDS slot.
