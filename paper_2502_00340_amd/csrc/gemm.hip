@@ -12,12 +12,16 @@
 // block per CU.  The block tile is (64*TM) x (64*TN) with wave tiles of
 // (32*TM) x (32*TN); three shapes are compiled into one kernel: 256x256 (the
 // wave tile with the fewest LDS bytes per MFMA), 256x128 and 128x128.
-//   * Tile scheduling.  The 256x256 tiles that fill whole rounds of the 256 CUs
-//     come first; the tiles of the last, partial round are cut into 2 or 4
-//     sub-tiles when that shortens the tail (a 3.5-round problem takes 3 rounds
-//     of full tiles and one of half tiles instead of 4 rounds).  Within each group
-//     the 8 XCDs (block id mod 8) take contiguous runs of a band-major tile order,
-//     so the blocks resident on one XCD share operand panels in that XCD's L2.
+//   * Tile scheduling.  A launch has as many blocks as CUs; a block walks through its
+//     share of the output tiles.  The 256x256 tiles that fill whole rounds of the CUs
+//     come first; the tiles of the last, partial round are cut into 2 or 4 sub-tiles
+//     when that shortens the tail (a 3.5-round problem takes 3 rounds of full tiles
+//     and one of half tiles instead of 4 rounds).  Within each group the 8 XCDs (block
+//     id mod 8) take contiguous runs of a band-major tile order, so the blocks resident
+//     on one XCD share operand panels in that XCD's L2.  Between two tiles of a block
+//     the loads of the next tile's first K-steps are already in flight while the
+//     finished tile leaves, and its stores drain under the next tile's MFMAs (the
+//     write-out of a tile used to be 13 % of its time).
 //   * Operand tiles move in K-steps of 32 through a ring of four 32 KB LDS stages,
 //     filled by buffer_load ... lds (16 bytes per lane, no register hop).  K-steps are
 //     handled in pairs (64 k: one whole 128-byte line of every NT operand row, fetched
@@ -52,8 +56,9 @@
 //     one transpose read land in four different 64-byte bank groups.
 //   * The MFMA is issued with the operands swapped (D = B-frag x A-frag), so a lane
 //     ends up with groups of 4 adjacent output columns; the epilogue packs them to
-//     bf16, stages the whole C tile in LDS (the operand stages are dead by then)
-//     and writes full rows with 16-byte stores.
+//     bf16 and sends them, 32 rows of the wave tile at a time, through 8 KB of LDS of
+//     the wave's own (above the operand stages, which the next tile is filling by
+//     then) to full-row 16-byte stores.
 // fp32 path (check mode): plain LDS-tiled FMA kernel.
 #include <algorithm>
 #include <type_traits>
@@ -112,17 +117,27 @@ __device__ __forceinline__ void tile_coords(int l, int tiles_m, int tiles_n, int
     bn = r / gsize;
 }
 
-// One output tile of (64*TM) x (64*TN) at (m0, n0).  SPLIT: the block contracts only k in
+// One output tile: its origin, and the B operand (of segment 0), output matrix and column count
+// it belongs to (those of its column group in a grouped launch).
+struct TileRef {
+    int m0, n0, N;
+    const void* B0;
+    void* C;
+};
+
+// The block's output tiles of (64*TM) x (64*TN), one after the other: `first`, then whatever
+// next_tile(TileRef&) hands out until it returns false.  With bf16 output the loads of the next
+// tile's first K-steps are in flight while the finished tile leaves through a staging area of its
+// own, and its stores drain under the next tile's MFMAs.  SPLIT: the block contracts only k in
 // [kbeg, kend) of the single segment and stores its fp32 accumulators, unscaled, to `part_out`
 // ([M, N] fp32); a second kernel adds the parts up.
-template <int MODE, int TM, int TN, bool SPLIT = false, bool CF32 = false>
-__device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const int n0, unsigned char* smem,
-                                          const int kbeg = 0, const int kend = 0, float* part_out = nullptr) {
+template <int MODE, int TM, int TN, bool SPLIT, bool CF32, typename Next>
+__device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef first, Next next_tile, unsigned char* smem,
+                                           const int kbeg = 0, const int kend = 0, float* part_out = nullptr) {
     constexpr int BM = 64 * TM, BN = 64 * TN, KB = 32, STAGE = GEMM_STAGE_BYTES;
     constexpr int A_BYTES = BM * KB * 2;                // B tile follows the A tile inside a stage
     constexpr int NU = TM + TN;                         // 1 KB wave-loads per wave per K-step: TM for A, TN for B
     constexpr int NQ = TM * TN, NF = TM + TN;           // MFMAs and fragment reads per 16-wide sub-step
-    constexpr int C_PITCH = BN * 2 + 16;
     static_assert(A_BYTES + BN * KB * 2 <= STAGE, "tile shape");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -130,12 +145,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
     const int slot = lane & 31, hh = lane >> 5;
 
     f32x16_t acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    TileRef ld = first;             // the tile whose operands are being loaded
 
     // ---- global -> LDS -----------------------------------------------------------
     // (seg, k0): the K-step that the next loads fetch.  Past the last segment Kseg = 0, so
@@ -155,20 +165,21 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
     const unsigned nt_lc = (unsigned)((lane & 3) ^ ((lane >> 4) & 3));
     auto open_segment = [&](int s) __attribute__((always_inline)) {
         const bool live = s < g.nseg;
+        const int m0 = ld.m0, n0 = ld.n0;
         const bf16_t* A = static_cast<const bf16_t*>(s == 1 ? g.A[1] : (s == 2 ? g.A[2] : g.A[0]));
-        const bf16_t* B = static_cast<const bf16_t*>(s == 1 ? g.B[1] : (s == 2 ? g.B[2] : g.B[0]));
+        const bf16_t* B = static_cast<const bf16_t*>(s == 1 ? g.B[1] : (s == 2 ? g.B[2] : ld.B0));
         const int Kraw = s == 1 ? g.K[1] : (s == 2 ? g.K[2] : g.K[0]);
         Kseg = live ? Kraw : 0;
         const int64_t K = Kraw;
         if (MODE == 0) {
             rsA = make_rsrc(A + (int64_t)m0 * K, ((int64_t)g.M - m0) * K * 2);
-            rsB = make_rsrc(B + (int64_t)n0 * K, ((int64_t)g.N - n0) * K * 2);
+            rsB = make_rsrc(B + (int64_t)n0 * K, ((int64_t)ld.N - n0) * K * 2);
             ldA = ldB = (unsigned)K * 2u;
         } else {
             rsA = make_rsrc(A + m0, (K * g.M - m0) * 2);
-            rsB = make_rsrc(B + n0, (K * g.N - n0) * 2);
+            rsB = make_rsrc(B + n0, (K * ld.N - n0) * 2);
             ldA = (unsigned)g.M * 2u;
-            ldB = (unsigned)g.N * 2u;
+            ldB = (unsigned)ld.N * 2u;
         }
 #pragma unroll
         for (int u = 0; u < NU; ++u) {
@@ -182,7 +193,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
                 const int qq = (4 * i + wave) * 64 + lane;
                 const int kr = qq / cpr;
                 const int c = (qq % cpr) ^ ((kr & 3) << 2);
-                const bool ok = (isA ? m0 : n0) + c * 8 < (isA ? g.M : g.N);
+                const bool ok = (isA ? m0 : n0) + c * 8 < (isA ? g.M : ld.N);
                 vbase[u] = ok ? (unsigned)kr * (isA ? ldA : ldB) + c * 16u : OOB_FAST;
             }
         }
@@ -364,7 +375,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
     const int npairs = SPLIT ? (kend - kbeg + 2 * KB - 1) / (2 * KB)
                              : (g.K[0] + 2 * KB - 1) / (2 * KB) + (g.K[1] + 2 * KB - 1) / (2 * KB) +
                                    (g.K[2] + 2 * KB - 1) / (2 * KB);
-    if (npairs > 0) {
+    // prologue of tile ld: K-steps 0, 1 and the first half of the loads of K-steps 2, 3
+    auto start_tile = [&]() __attribute__((always_inline)) {
+        seg = 0;
+        k0 = 0;
         open_segment(0);
         if (SPLIT) {                    // the block's K range stands for the segment
             k0 = kbeg;
@@ -373,17 +387,38 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
         issue_pair(ic<0>{}, ic<1>{}, ic<0>{});
         advance_pair();
         issue_pair(ic<2>{}, ic<3>{}, ic<1>{});      // the loop's first sub-step issues the other half
-        wait_vmcnt<NU>();               // K-steps 0 and 1 have landed; half of 2 and 3 may be in flight
-        lds_barrier();
-        static_for<NF>([&](auto U) __attribute__((always_inline)) { frag_one(ic<0>{}, ic<0>{}, U, ic<0>{}); });
-        // two pairs per iteration; an odd count runs one pair of zero K-steps (loads past the last
-        // segment return zeros)
-        for (int p = 0; p < npairs; p += 2) {
-            pair_body(ic<0>{});
-            pair_body(ic<2>{});
+    };
+    constexpr bool OVERLAP = !SPLIT && !CF32;       // the epilogue leaves the operand stages alone
+    if (npairs > 0) start_tile();
+    for (;;) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+        if (npairs > 0) {
+            // K-steps 0 and 1 have landed.  Everything is waited for, the previous tile's stores
+            // included: loads and stores share the counter and retire out of order with respect
+            // to each other, so a partial count would say nothing about the loads.
+            wait_vmcnt<0>();
+            lds_barrier();
+            static_for<NF>([&](auto U) __attribute__((always_inline)) { frag_one(ic<0>{}, ic<0>{}, U, ic<0>{}); });
+            // two pairs per iteration; an odd count runs one pair of zero K-steps (loads past the last
+            // segment return zeros)
+            for (int p = 0; p < npairs; p += 2) {
+                pair_body(ic<0>{});
+                pair_body(ic<2>{});
+            }
+            wait_vmcnt<0>();
         }
-        wait_vmcnt<0>();
-    }
+        const TileRef ep = ld;          // the tile that leaves
+        const bool has_next = next_tile(ld);
+        if (OVERLAP) {
+            lds_barrier();              // every wave has read its last fragments: the stages are free
+            if (has_next && npairs > 0) start_tile();
+        }
+        const int m0 = ep.m0, n0 = ep.n0;
 
     if (SPLIT) {
         // ---- split-K epilogue: fp32 accumulators straight to the block's part ----------
@@ -395,14 +430,14 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
                 for (int v4 = 0; v4 < 4; ++v4) {
                     const int m = m0 + wm * (32 * TM) + i * 32 + slot;
                     const int n = n0 + wn * (32 * TN) + j * 32 + 8 * v4 + 4 * hh;
-                    if (m < g.M && n < g.N) {               // N is a multiple of 8
+                    if (m < g.M && n < ep.N) {               // N is a multiple of 8
                         float4 o;
                         o.x = acc[i][j][4 * v4 + 0]; o.y = acc[i][j][4 * v4 + 1];
                         o.z = acc[i][j][4 * v4 + 2]; o.w = acc[i][j][4 * v4 + 3];
-                        *reinterpret_cast<float4*>(part_out + (int64_t)m * g.N + n) = o;
+                        *reinterpret_cast<float4*>(part_out + (int64_t)m * ep.N + n) = o;
                     }
                 }
-        return;
+        break;
     }
     const float alpha = g.alpha;
     if (CF32) {
@@ -410,7 +445,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
         // turn, then out as full rows of 16-byte stores, added to beta*C in fp32
         constexpr int HP = BN * 4 + 16;                     // pitch of a staged row of floats
         static_assert((BM / 2) * HP <= GEMM_SMEM, "fp32 staging");
-        float* C = static_cast<float*>(g.C);
+        float* C = static_cast<float*>(ep.C);
         const float beta = g.beta;
         constexpr int CPR = BN / 4, RPP = 256 / CPR;        // 16-byte chunks per row, rows per pass
         const int c = tid % CPR, r0 = tid / CPR;
@@ -434,7 +469,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
                         }
             }
             lds_barrier();
-            if (n < g.N) {                                  // N is a multiple of 8
+            if (n < ep.N) {                                  // N is a multiple of 8
                 // eight rows per round: all loads of the old values are in flight before the first add
                 constexpr int RB = 8;
                 static_assert((BM / 2) % (RPP * RB) == 0, "row batches");
@@ -445,7 +480,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
                     for (int q = 0; q < RB; ++q) {
                         const int m = m0 + h * (BM / 2) + rb + q * RPP;
                         old[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-                        if (beta != 0.f && m < g.M) old[q] = *reinterpret_cast<const float4*>(C + (int64_t)m * g.N + n);
+                        if (beta != 0.f && m < g.M) old[q] = *reinterpret_cast<const float4*>(C + (int64_t)m * ep.N + n);
                     }
 #pragma unroll
                     for (int q = 0; q < RB; ++q)
@@ -456,89 +491,139 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
                         if (m < g.M) {
                             val[q].x += beta * old[q].x; val[q].y += beta * old[q].y;
                             val[q].z += beta * old[q].z; val[q].w += beta * old[q].w;
-                            *reinterpret_cast<float4*>(C + (int64_t)m * g.N + n) = val[q];
+                            *reinterpret_cast<float4*>(C + (int64_t)m * ep.N + n) = val[q];
                         }
                     }
                 }
             }
         }
-        return;
+        if (!has_next) break;
+        lds_barrier();                  // the staging area overlaps the stages
+        if (npairs > 0) start_tile();
+        continue;
     }
-    // ---- epilogue: acc -> bf16 -> LDS C tile -> global with 16-byte stores -----------
-    lds_barrier();
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int v4 = 0; v4 < 4; ++v4) {
-                const int r = wm * (32 * TM) + i * 32 + slot;
-                const int c = wn * (32 * TN) + j * 32 + 8 * v4 + 4 * hh;
-                uint2 o;
-                o.x = pack_bf16x2(acc[i][j][4 * v4 + 0] * alpha, acc[i][j][4 * v4 + 1] * alpha);
-                o.y = pack_bf16x2(acc[i][j][4 * v4 + 2] * alpha, acc[i][j][4 * v4 + 3] * alpha);
-                *reinterpret_cast<uint2*>(smem + r * C_PITCH + c * 2) = o;
-            }
-    lds_barrier();
+    // ---- epilogue: 32 rows of the wave tile at a time: acc -> bf16 -> the wave's own 8 KB above the
+    // four stages -> global with 16-byte stores, whole rows per group of lanes.  The 16-byte chunks
+    // of a staged row are XOR-ed with the row number, which keeps both the column-wise writes (a
+    // lane holds 4 adjacent columns of one row) and the row-wise reads spread over the banks.  No
+    // block barrier: the area is private to the wave and its LDS operations execute in order.
     {
-        bf16_t* C = static_cast<bf16_t*>(g.C);
+        constexpr int RBY = 64 * TN;                        // bytes of a staged row (32*TN columns)
+        constexpr int CPR = RBY / 16, RPP = 64 / CPR;       // 16-byte chunks per row, rows per pass of the wave
+        unsigned char* stg = smem + GEMM_STAGES * STAGE + wave * 8192;
+        bf16_t* C = static_cast<bf16_t*>(ep.C);
         const float beta = g.beta;
-        constexpr int CPR = BN / 8, RPP = 256 / CPR;        // 16-byte chunks per tile row, rows per pass
-        const int c = tid % CPR, r0 = tid / CPR;
-        const int n = n0 + c * 8;
-        if (n < g.N) {                                      // N is a multiple of 8
-#pragma unroll 4
-            for (int r = r0; r < BM; r += RPP) {
-                const int m = m0 + r;
-                if (m >= g.M) break;
-                u32x4_t val = *reinterpret_cast<const u32x4_t*>(smem + r * C_PITCH + c * 16);
-                bf16_t* p = C + (int64_t)m * g.N + n;
-                if (beta != 0.f) {
-                    const u32x4_t old = *reinterpret_cast<const u32x4_t*>(p);
+        const int c = lane % CPR, rl = lane / CPR;
+        const int n = n0 + wn * (32 * TN) + c * 8;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float lo = __uint_as_float(val[e] << 16) + beta * __uint_as_float(old[e] << 16);
-                        const float hi = __uint_as_float(val[e] & 0xFFFF0000u) +
-                                         beta * __uint_as_float(old[e] & 0xFFFF0000u);
-                        val[e] = pack_bf16x2(lo, hi);
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int v4 = 0; v4 < 4; ++v4) {
+                    uint2 o;
+                    o.x = pack_bf16x2(acc[i][j][4 * v4 + 0] * alpha, acc[i][j][4 * v4 + 1] * alpha);
+                    o.y = pack_bf16x2(acc[i][j][4 * v4 + 2] * alpha, acc[i][j][4 * v4 + 3] * alpha);
+                    const int chunk = (j * 4 + v4) ^ (slot & (CPR - 1));
+                    *reinterpret_cast<uint2*>(stg + slot * RBY + chunk * 16 + hh * 8) = o;
+                }
+            if (n < ep.N) {                                 // N is a multiple of 8
+#pragma unroll
+                for (int r = rl; r < 32; r += RPP) {
+                    const int m = m0 + wm * (32 * TM) + i * 32 + r;
+                    if (m < g.M) {
+                        u32x4_t val = *reinterpret_cast<const u32x4_t*>(stg + r * RBY + ((c ^ (r & (CPR - 1))) << 4));
+                        bf16_t* p = C + (int64_t)m * ep.N + n;
+                        if (beta != 0.f) {
+                            const u32x4_t old = *reinterpret_cast<const u32x4_t*>(p);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const float lo = __uint_as_float(val[e] << 16) + beta * __uint_as_float(old[e] << 16);
+                                const float hi = __uint_as_float(val[e] & 0xFFFF0000u) +
+                                                 beta * __uint_as_float(old[e] & 0xFFFF0000u);
+                                val[e] = pack_bf16x2(lo, hi);
+                            }
+                        }
+                        *reinterpret_cast<u32x4_t*>(p) = val;
                     }
                 }
-                *reinterpret_cast<u32x4_t*>(p) = val;
             }
         }
     }
+    if (!has_next) break;
+    }   // tile loop
 }
 
+// The work items of a launch: the n_full whole tiles first, then the sub-tiles of the remaining
+// tiles.  Block b takes items b, b + gridDim.x, ...: with as many blocks as CUs every block runs
+// its share of the whole tiles back to back and then at most a few sub-tiles, and the items of
+// one block stay on one XCD (item id mod 8 = block id mod 8).
 template <int MODE, bool CF32>
-__device__ __forceinline__ void gemm_bf16_block(GemmArgs& g, unsigned char* smem) {
+__device__ __forceinline__ void gemm_bf16_block(const GemmArgs& g, unsigned char* smem) {
     const int tiles_m = (g.M + 255) / 256, tiles_n = (g.N + 255) / 256;
-    const int pid = blockIdx.x;
-    int bm, bn, m0, n0, cut = 1;
-    if (pid < g.n_full) {
-        tile_coords(xcd_order(pid, g.n_full), tiles_m, tiles_n, bm, bn);
-        m0 = bm * 256;
-        n0 = bn * 256;
-    } else {
-        cut = g.sub;
-        const int j = xcd_order(pid - g.n_full, (int)gridDim.x - g.n_full);
-        const int part = j % cut;
-        tile_coords(g.n_full + j / cut, tiles_m, tiles_n, bm, bn);
-        m0 = bm * 256 + (cut == 4 ? (part >> 1) * 128 : 0);
-        n0 = bn * 256 + (cut == 4 ? (part & 1) * 128 : (cut == 2 ? part * 128 : 0));
-        if (m0 >= g.M || n0 >= g.N) return;
+    const int n_items = g.n_full + (tiles_m * tiles_n - g.n_full) * g.sub;
+    const int stride = (int)gridDim.x;
+    // item -> tile; false when a sub-tile lies outside the matrix
+    auto decode = [&](int w, TileRef& t) __attribute__((always_inline)) {
+        int bm, bn, m0, n0;
+        if (w < g.n_full) {
+            tile_coords(xcd_order(w, g.n_full), tiles_m, tiles_n, bm, bn);
+            m0 = bm * 256;
+            n0 = bn * 256;
+        } else {
+            const int cut = g.sub;
+            const int j = xcd_order(w - g.n_full, n_items - g.n_full);
+            const int part = j % cut;
+            tile_coords(g.n_full + j / cut, tiles_m, tiles_n, bm, bn);
+            m0 = bm * 256 + (cut == 4 ? (part >> 1) * 128 : 0);
+            n0 = bn * 256 + (cut == 4 ? (part & 1) * 128 : (cut == 2 ? part * 128 : 0));
+            if (m0 >= g.M || n0 >= g.N) return false;
+        }
+        t.B0 = g.B[0];
+        t.C = g.C;
+        t.N = g.N;
+        if (g.ngroups > 1) {
+            // the tile's column group: rebase the B operand, the output and the column range on it
+            const int j = n0 < g.Ng[0] ? 0 : (n0 < g.Ng[0] + g.Ng[1] ? 1 : 2);
+            const int off = j == 0 ? 0 : (j == 1 ? g.Ng[0] : g.Ng[0] + g.Ng[1]);
+            t.B0 = j == 0 ? g.Bg[0] : (j == 1 ? g.Bg[1] : g.Bg[2]);
+            t.C = j == 0 ? g.Cg[0] : (j == 1 ? g.Cg[1] : g.Cg[2]);
+            t.N = j == 0 ? g.Ng[0] : (j == 1 ? g.Ng[1] : g.Ng[2]);
+            n0 -= off;
+        }
+        t.m0 = m0;
+        t.n0 = n0;
+        return true;
+    };
+    int w = (int)blockIdx.x;
+    TileRef t;
+    // the next item of this block below `end` that is a tile
+    auto advance = [&](int end) __attribute__((always_inline)) {
+        for (w += stride; w < end; w += stride)
+            if (decode(w, t)) return true;
+        return false;
+    };
+    if (w < g.n_full) {         // whole tiles
+        decode(w, t);
+        gemm_tiles<MODE, 4, 4, false, CF32>(g, t, [&](TileRef& nx) __attribute__((always_inline)) {
+            if (!advance(g.n_full)) return false;
+            nx = t;
+            return true;
+        }, smem);
     }
-    if (g.ngroups > 1) {
-        // the tile's column group: rebase the B operand, the output and the column range on it
-        const int j = n0 < g.Ng[0] ? 0 : (n0 < g.Ng[0] + g.Ng[1] ? 1 : 2);
-        const int off = j == 0 ? 0 : (j == 1 ? g.Ng[0] : g.Ng[0] + g.Ng[1]);
-        g.B[0] = j == 0 ? g.Bg[0] : (j == 1 ? g.Bg[1] : g.Bg[2]);
-        g.C = j == 0 ? g.Cg[0] : (j == 1 ? g.Cg[1] : g.Cg[2]);
-        g.N = j == 0 ? g.Ng[0] : (j == 1 ? g.Ng[1] : g.Ng[2]);
-        n0 -= off;
-    }
-    if (cut == 1) gemm_tile<MODE, 4, 4, false, CF32>(g, m0, n0, smem);
-    else if (cut == 2) gemm_tile<MODE, 4, 2, false, CF32>(g, m0, n0, smem);
-    else gemm_tile<MODE, 2, 2, false, CF32>(g, m0, n0, smem);
+    // sub-tiles: w is now this block's first item at or past n_full
+    bool have = false;
+    for (; w < n_items; w += stride)
+        if (decode(w, t)) { have = true; break; }
+    if (!have) return;
+    auto next_sub = [&](TileRef& nx) __attribute__((always_inline)) {
+        if (!advance(n_items)) return false;
+        nx = t;
+        return true;
+    };
+    if (g.sub == 1) gemm_tiles<MODE, 4, 4, false, CF32>(g, t, next_sub, smem);
+    else if (g.sub == 2) gemm_tiles<MODE, 4, 2, false, CF32>(g, t, next_sub, smem);
+    else gemm_tiles<MODE, 2, 2, false, CF32>(g, t, next_sub, smem);
 }
 
 template <int MODE>
@@ -565,7 +650,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_splitk_kernel(GemmArgs g, float
     const int m0 = ((int)blockIdx.x % tiles_m) * 128, n0 = ((int)blockIdx.x / tiles_m) * 128;
     const int kbeg = (int)blockIdx.y * kchunk;
     const int kend = min(g.K[0], kbeg + kchunk);
-    gemm_tile<MODE, 2, 2, true>(g, m0, n0, smem, kbeg, kend, partial + (int64_t)blockIdx.y * g.M * g.N);
+    const TileRef t{m0, n0, g.N, g.B[0], g.C};
+    gemm_tiles<MODE, 2, 2, true, false>(g, t, [](TileRef&) { return false; }, smem, kbeg, kend,
+                                        partial + (int64_t)blockIdx.y * g.M * g.N);
 }
 
 // C[m, n..n+7] = alpha * sum_p partial[p][m, n..n+7] + beta * C
@@ -737,7 +824,8 @@ static hipError_t launch_bf16(GemmArgs& g, hipStream_t st) {
     }
     const int tiles = ceil_div(g.M, 256) * ceil_div(g.N, 256);
     plan_tiles(tiles, compute_units(), g.n_full, g.sub);
-    const int grid = g.n_full + (tiles - g.n_full) * g.sub;
+    const int items = g.n_full + (tiles - g.n_full) * g.sub;
+    const int grid = std::min(items, compute_units());      // a block walks through its items
     if (g.c_f32) gemm_bf16_f32out_kernel<MODE><<<grid, 256, GEMM_SMEM, st>>>(g);
     else gemm_bf16_kernel<MODE><<<grid, 256, GEMM_SMEM, st>>>(g);
     return hipGetLastError();
