@@ -117,6 +117,13 @@ __device__ __forceinline__ void tile_coords(int l, int tiles_m, int tiles_n, int
     bn = r / gsize;
 }
 
+template <typename P>
+__device__ __forceinline__ P* uniform_ptr(P* p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<P*>(((uint64_t)hi << 32) | lo);
+}
+
 // One output tile: its origin, and the B operand (of segment 0), output matrix and column count
 // it belongs to (those of its column group in a grouped launch).
 struct TileRef {
@@ -181,16 +188,22 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
             ldA = (unsigned)g.M * 2u;
             ldB = (unsigned)ld.N * 2u;
         }
+        // The per-lane parts below never change, but they are cheap to rebuild and registers are
+        // scarce while a finished tile is still in the accumulators: keep the compiler from carrying
+        // them across the main loop (and spilling them) by hiding where the lane number comes from.
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
+        const unsigned lc_nt = (unsigned)((ln & 3) ^ ((ln >> 4) & 3));
 #pragma unroll
         for (int u = 0; u < NU; ++u) {
             const bool isA = u < TM;
             const int i = isA ? u : u - TM;
             if (MODE == 0) {
-                const unsigned row = (4 * i + wave) * 16 + (lane >> 2);
-                vbase[u] = row * (isA ? ldA : ldB) + nt_lc * 16u;
+                const unsigned row = (4 * i + wave) * 16 + (ln >> 2);
+                vbase[u] = row * (isA ? ldA : ldB) + lc_nt * 16u;
             } else {
                 const int cpr = (isA ? BM : BN) / 8;
-                const int qq = (4 * i + wave) * 64 + lane;
+                const int qq = (4 * i + wave) * 64 + ln;
                 const int kr = qq / cpr;
                 const int c = (qq % cpr) ^ ((kr & 3) << 2);
                 const bool ok = (isA ? m0 : n0) + c * 8 < (isA ? g.M : ld.N);
@@ -507,14 +520,30 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
     // of a staged row are XOR-ed with the row number, which keeps both the column-wise writes (a
     // lane holds 4 adjacent columns of one row) and the row-wise reads spread over the banks.  No
     // block barrier: the area is private to the wave and its LDS operations execute in order.
+    // The stores go through a buffer descriptor over the whole output matrix, so there is no
+    // branch in the stream: rows past M fall outside its range and lanes whose columns lie past
+    // N carry an out-of-range offset.
     {
         constexpr int RBY = 64 * TN;                        // bytes of a staged row (32*TN columns)
         constexpr int CPR = RBY / 16, RPP = 64 / CPR;       // 16-byte chunks per row, rows per pass of the wave
+        constexpr int NP = 32 / RPP, NV = CPR / RPP;        // passes per 32 rows; distinct swizzle phases
         unsigned char* stg = smem + GEMM_STAGES * STAGE + wave * 8192;
-        bf16_t* C = static_cast<bf16_t*>(ep.C);
+        const __amdgpu_buffer_rsrc_t rc =
+            __builtin_amdgcn_make_buffer_rsrc(ep.C, 0, (int)((int64_t)g.M * ep.N * 2), 0x00020000);
         const float beta = g.beta;
-        const int c = lane % CPR, rl = lane / CPR;
+        int ln = lane;                                      // as in open_segment: rebuilt per tile, not carried
+        asm volatile("" : "+v"(ln));
+        const int c = ln % CPR, rl = ln / CPR;
+        const int slot = ln & 31, hh = ln >> 5;
         const int n = n0 + wn * (32 * TN) + c * 8;
+        const unsigned row_bytes = (unsigned)ep.N * 2u;
+        // N is a multiple of 8, so a 16-byte chunk lies inside a row or outside it
+        const unsigned voff = n < ep.N ? (unsigned)(m0 + wm * (32 * TM) + rl) * row_bytes + (unsigned)n * 2u : OOB_FAST;
+        const unsigned char* rd[NV];
+#pragma unroll
+        for (int v = 0; v < NV; ++v) rd[v] = stg + rl * RBY + ((c ^ ((rl + RPP * v) & (CPR - 1))) << 4);
+        unsigned char* const wr = stg + slot * RBY + hh * 8;
+        const int wsw = slot & (CPR - 1);
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -524,30 +553,29 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
                     uint2 o;
                     o.x = pack_bf16x2(acc[i][j][4 * v4 + 0] * alpha, acc[i][j][4 * v4 + 1] * alpha);
                     o.y = pack_bf16x2(acc[i][j][4 * v4 + 2] * alpha, acc[i][j][4 * v4 + 3] * alpha);
-                    const int chunk = (j * 4 + v4) ^ (slot & (CPR - 1));
-                    *reinterpret_cast<uint2*>(stg + slot * RBY + chunk * 16 + hh * 8) = o;
+                    *reinterpret_cast<uint2*>(wr + (((j * 4 + v4) ^ wsw) << 4)) = o;
                 }
-            if (n < ep.N) {                                 // N is a multiple of 8
+            u32x4_t val[NP];
 #pragma unroll
-                for (int r = rl; r < 32; r += RPP) {
-                    const int m = m0 + wm * (32 * TM) + i * 32 + r;
-                    if (m < g.M) {
-                        u32x4_t val = *reinterpret_cast<const u32x4_t*>(stg + r * RBY + ((c ^ (r & (CPR - 1))) << 4));
-                        bf16_t* p = C + (int64_t)m * ep.N + n;
-                        if (beta != 0.f) {
-                            const u32x4_t old = *reinterpret_cast<const u32x4_t*>(p);
+            for (int q = 0; q < NP; ++q)
+                val[q] = *reinterpret_cast<const u32x4_t*>(rd[q % NV] + q * RPP * RBY);
+            if (beta != 0.f) {
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                const float lo = __uint_as_float(val[e] << 16) + beta * __uint_as_float(old[e] << 16);
-                                const float hi = __uint_as_float(val[e] & 0xFFFF0000u) +
-                                                 beta * __uint_as_float(old[e] & 0xFFFF0000u);
-                                val[e] = pack_bf16x2(lo, hi);
-                            }
-                        }
-                        *reinterpret_cast<u32x4_t*>(p) = val;
+                for (int q = 0; q < NP; ++q) {
+                    const u32x4_t old = __builtin_amdgcn_raw_buffer_load_b128(
+                        rc, voff + (unsigned)(i * 32 + q * RPP) * row_bytes, 0, 0);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float lo = __uint_as_float(val[q][e] << 16) + beta * __uint_as_float(old[e] << 16);
+                        const float hi = __uint_as_float(val[q][e] & 0xFFFF0000u) +
+                                         beta * __uint_as_float(old[e] & 0xFFFF0000u);
+                        val[q][e] = pack_bf16x2(lo, hi);
                     }
                 }
             }
+#pragma unroll
+            for (int q = 0; q < NP; ++q)
+                __builtin_amdgcn_raw_buffer_store_b128(val[q], rc, voff + (unsigned)(i * 32 + q * RPP) * row_bytes, 0, 0);
         }
     }
     if (!has_next) break;
@@ -591,8 +619,13 @@ __device__ __forceinline__ void gemm_bf16_block(const GemmArgs& g, unsigned char
             t.N = j == 0 ? g.Ng[0] : (j == 1 ? g.Ng[1] : g.Ng[2]);
             n0 -= off;
         }
-        t.m0 = m0;
-        t.n0 = n0;
+        // every field is the same in all lanes: say so, which keeps the address arithmetic of the
+        // tile's prologue on the scalar unit
+        t.m0 = __builtin_amdgcn_readfirstlane(m0);
+        t.n0 = __builtin_amdgcn_readfirstlane(n0);
+        t.N = __builtin_amdgcn_readfirstlane(t.N);
+        t.B0 = uniform_ptr(t.B0);
+        t.C = uniform_ptr(t.C);
         return true;
     };
     int w = (int)blockIdx.x;
@@ -855,10 +888,11 @@ hipError_t launch_gemm(int dtype, int mode, const GemmSeg* segs, int nseg, void*
         return hipSuccess;
     }
     if (dtype == CF_BF16) {
-        // per-lane load offsets are 32-bit with the upper half reserved for "out of range"
+        // per-lane load and store offsets are 32-bit with the upper half reserved for "out of range"
         for (int s = 0; s < g.nseg; ++s)
             if ((int64_t)M * g.K[s] * 2 >= ((int64_t)1 << 31) || (int64_t)N * g.K[s] * 2 >= ((int64_t)1 << 31))
                 return hipErrorInvalidValue;
+        if (((int64_t)M + 256) * N * 2 >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
     }
     if (dtype == CF_F32) {
         const int grid = ceil_div(M, 64) * ceil_div(N, 64);
@@ -896,6 +930,8 @@ hipError_t launch_gemm_tn_groups(const void* A, int K, int M, int ngroups, const
         if ((int64_t)g.Ng[j] * K * 2 >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
     }
     if ((int64_t)M * K * 2 >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
+    for (int j = 0; j < ngroups; ++j)
+        if (((int64_t)M + 256) * Ng[j] * 2 >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
     g.ngroups = ngroups;
     g.A[0] = A; g.B[0] = Bg[0]; g.K[0] = K; g.nseg = 1;
     for (int s = 1; s < 3; ++s) { g.A[s] = nullptr; g.B[s] = nullptr; g.K[s] = 0; }
