@@ -19,6 +19,9 @@
  *     (leading dimension = number of columns).  Weights are stored [in, out]
  *     (Y = X * W).  "kept"/compact tensors have one row per kept token in
  *     ascending token order.
+ *   - Size limit in CF_BF16 mode: every matrix a call touches ([T,F], [F,H], ...) must stay
+ *     below 2 GiB (the GEMM kernels use 32-bit byte offsets); larger requests return
+ *     CF_ERR_UNSUPPORTED before anything is launched.
  *   - dtype CF_BF16: bfloat16 storage, fp32 accumulation and fp32 row
  *     statistics; CF_F32: fp32 everywhere (check mode, not tuned).  LSE is
  *     always fp32.  In CF_BF16 mode H, Hq*d, Hkv*d and F must be multiples of

@@ -2,6 +2,8 @@
 // orchestration.  See include/centrifuge.h for the contract of each call.
 #include <math.h>
 
+#include <algorithm>
+
 #include "common.h"
 
 namespace cf {
@@ -63,6 +65,13 @@ cf_status check_layer_desc(const cf_layer_desc* L) {
     if (L->H % mult || L->F % mult) return CF_ERR_SHAPE;
     if (L->H > 256 * 8 * mult) return CF_ERR_SHAPE;     // row-norm kernels keep a row in registers
     if (!(L->rms_eps >= 0.f)) return CF_ERR_SHAPE;
+    if (L->dtype == CF_BF16) {
+        // the matrix-core GEMM addresses an operand or an output with 32-bit byte offsets whose upper
+        // half means "out of range": every matrix of the layer has to stay below 2 GiB
+        const int64_t rows = std::max<int64_t>((int64_t)L->B * L->S, std::max(L->F, L->H)) + 256;
+        const int64_t cols = std::max<int64_t>(std::max(L->F, L->H), (int64_t)L->Hq * L->d);
+        if (rows * cols * 2 >= ((int64_t)1 << 31)) return CF_ERR_UNSUPPORTED;
+    }
     return CF_OK;
 }
 
@@ -472,6 +481,10 @@ cf_status cf_linear_bwd_reduced(const void* x_kept, const void* dy_kept, const v
     const int mult = dtype == CF_BF16 ? 8 : 4;
     if (in % mult || out % mult) return CF_ERR_SHAPE;
     if (dw_beta != 0.f && dw_beta != 1.f) return CF_ERR_SHAPE;
+    if (dtype == CF_BF16) {     // 32-bit byte offsets with the upper half reserved (see check_layer_desc)
+        const int64_t rows = std::max<int64_t>(n_kept, in) + 256, cols = std::max(in, out);
+        if (rows * cols * 2 >= ((int64_t)1 << 31)) return CF_ERR_UNSUPPORTED;
+    }
     if (misaligned(dy_kept) || (w && misaligned(w)) || (x_kept && misaligned(x_kept)) ||
         (dx_kept && misaligned(dx_kept)) || (dw && misaligned(dw)))
         return CF_ERR_SHAPE;

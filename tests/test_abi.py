@@ -87,6 +87,7 @@ def test_linear_argument_errors(L):
     assert f(FAKE, FAKE, FAKE, 4, 8, 8, 1, FAKE, FAKE, 0.5, None) == 2   # beta must be 0 or 1
     assert f(FAKE, FAKE, FAKE, -1, 8, 8, 1, FAKE, FAKE, 0.0, None) == 2
     assert f(C.c_void_p(0x10004), FAKE, FAKE, 4, 8, 8, 1, FAKE, FAKE, 0.0, None) == 2  # misaligned
+    assert f(FAKE, FAKE, FAKE, 1 << 20, 14336, 4096, 0, FAKE, FAKE, 0.0, None) == 5    # bf16 matrix of 2 GiB or more
 
 
 def test_attention_argument_errors(L):
@@ -120,6 +121,10 @@ def test_layer_argument_errors(L):
     assert f(C.byref(_desc(H=250)), C.byref(sv), C.byref(w), FAKE, FAKE, C.byref(g), None, None, C.byref(n), FAKE, ok_ws, None) == 2
     sv_rope = Bn.Saved(*([0x10000] * 9 + [0x10000, None]))      # one rotary table without the other
     assert f(C.byref(d), C.byref(sv_rope), C.byref(w), FAKE, FAKE, C.byref(g), None, None, C.byref(n), FAKE, ok_ws, None) == 1
+    # a [T,F] matrix of 2 GiB or more is beyond the bf16 GEMM's 32-bit offsets: refused up front
+    big = _desc(dtype="bf16", B=64, S=8192, H=4096, Hq=32, Hkv=8, d=128, F=14336)
+    assert f(C.byref(big), C.byref(sv), C.byref(w), FAKE, FAKE, C.byref(g), None, None, C.byref(n), FAKE, ok_ws, None) == 5
+    assert L.cf_layer_workspace_bytes(C.byref(big), 1024) == 0
     g_bad = Bn.Grads(*([0x10000] * 10 + [2]))                   # main_grad is 0 or 1
     assert f(C.byref(d), C.byref(sv), C.byref(w), FAKE, FAKE, C.byref(g_bad), None, None, C.byref(n), FAKE, ok_ws, None) == 2
     fc = L.cf_layer_bwd_compact
