@@ -345,7 +345,11 @@ __global__ __launch_bounds__(256, 1) void attn_dkv_kernel(AttnParams p) {
     issue_q(2, 2);
     wait_vmcnt<2 * LPS>();
     lds_barrier();
-    for (int step = 0; step < steps; ++step) {
+    // One step = 64 queries.  MASKED: the step may hold queries that lie before some of the tile's
+    // keys (the first two steps of a tile) or the tile has fewer than 128 keys; every later step of a
+    // full tile sees all of its keys and spends no instruction on the mask.
+    auto step_body = [&](const int step, auto MASKED) __attribute__((always_inline)) {
+        constexpr bool masked = decltype(MASKED)::value != 0;
         const int cur = step & 3;
         issue_q(step + 3, (step + 3) & 3);
         const int qbase = c0 + step * 64;
@@ -397,8 +401,11 @@ __global__ __launch_bounds__(256, 1) void attn_dkv_kernel(AttnParams p) {
                 const int v4 = v >> 2, e = v & 3;
                 const float lv = e == 0 ? lq[v4].x : (e == 1 ? lq[v4].y : (e == 2 ? lq[v4].z : lq[v4].w));
                 const float dd = e == 0 ? dq4[v4].x : (e == 1 ? dq4[v4].y : (e == 2 ? dq4[v4].z : dq4[v4].w));
-                const bool ok = kvalid && (qbase + h * 32 + 8 * v4 + 4 * hh + e >= jk);
-                const float pr = ok ? __builtin_amdgcn_exp2f(st[h][v] * scale2 - lv) : 0.f;
+                float pr = __builtin_amdgcn_exp2f(st[h][v] * scale2 - lv);
+                if (masked) {
+                    const bool ok = kvalid && (qbase + h * 32 + 8 * v4 + 4 * hh + e >= jk);
+                    pr = ok ? pr : 0.f;
+                }
                 st[h][v] = pr;
                 dpt[h][v] = pr * (dpt[h][v] - dd);
                 if ((v & 7) == 7) {                          // a 16-query block (8 registers) is complete
@@ -455,7 +462,11 @@ __global__ __launch_bounds__(256, 1) void attn_dkv_kernel(AttnParams p) {
         }
         wait_vmcnt<2 * LPS>();          // step + 1 has landed; steps + 2 and + 3 may be in flight
         lds_barrier();
-    }
+    };
+    const int masked_steps = keys_in_tile < 128 ? steps : min(steps, 2);
+    int step = 0;
+    for (; step < masked_steps; ++step) step_body(step, ic<1>{});
+    for (; step < steps; ++step) step_body(step, ic<0>{});
     wait_vmcnt<0>();
 
     if (G == 1) {
