@@ -320,6 +320,20 @@ __global__ __launch_bounds__(256, 1) void attn_dkv_kernel(AttnParams p) {
     const i32x4_t rsL = make_rsrc(p.stat + (int64_t)h * p.n_kept + c0, (int64_t)(seq_end - c0) * 4);
     const i32x4_t rsD = make_rsrc(p.stat + (int64_t)(p.Hq + h) * p.n_kept + c0, (int64_t)(seq_end - c0) * 4);
     const unsigned lds0 = __builtin_amdgcn_readfirstlane(lds_addr_of(smem));
+    // Per-lane byte offsets of the fragment reads inside a 64-row tile, fixed for the whole kernel:
+    // row fragments (this lane's row of a 32-row half, d chunk ks) and token fragments (d block nt,
+    // low / high four rows of a 16-row block).  The XOR swizzle is folded in here, so a read in the
+    // loop is "stage base + this + compile-time offset".
+    unsigned ra[KS], ta[NT][2];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) ra[ks] = (unsigned)tile_off<D>(slot, ks * 2 + hh);
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int r = 4 * hh + ((lane & 15) >> 2);
+        const int chunk = nt * 4 + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+        ta[nt][0] = (unsigned)tile_off<D>(r, chunk) + (lane & 1) * 8;
+        ta[nt][1] = (unsigned)tile_off<D>(r + 8, chunk) + (lane & 1) * 8;
+    }
     auto issue_q = [&](int step, int stage) {
         const unsigned sq = lds0 + stage * STAGE;
         const unsigned base = (unsigned)(step * 64) * (unsigned)(Nq * 2);
@@ -357,9 +371,20 @@ __global__ __launch_bounds__(256, 1) void attn_dkv_kernel(AttnParams p) {
         // step of a tile) or past the sequence end multiplies zeros, which costs less than keeping
         // the accumulators live across a branch
         {
-            const unsigned char* sq = smem + cur * STAGE;
-            const unsigned char* sdo = sq + TILE;
-            const float* sl = reinterpret_cast<const float*>(sq + 2 * TILE);
+            typedef __attribute__((address_space(3))) unsigned char* lds_u8_ptr;
+            typedef const __attribute__((address_space(3))) u32x4_t* lds_u4_cptr;
+            typedef float f32x4v_t __attribute__((ext_vector_type(4)));
+            typedef const __attribute__((address_space(3))) f32x4v_t* lds_f4_cptr;
+            const unsigned sq = lds0 + cur * STAGE;         // Q tile; the dO tile follows at + TILE, the statistics at + 2*TILE
+            lds_u8_ptr pra[KS], pta[NT][2];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) pra[ks] = reinterpret_cast<lds_u8_ptr>(sq + ra[ks]);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                pta[nt][0] = reinterpret_cast<lds_u8_ptr>(sq + ta[nt][0]);
+                pta[nt][1] = reinterpret_cast<lds_u8_ptr>(sq + ta[nt][1]);
+            }
+            const lds_u8_ptr psl = reinterpret_cast<lds_u8_ptr>(sq + 2 * TILE + 16 * hh);
             // The tile is two halves of 32 queries (h = 0, 1).  Per half: A(h) = S and dP (2*KS MFMAs),
             // B(h) = P and dS from them (vector ALU: exp2, masks, products), C(h) = dV and dK (4*NT
             // MFMAs).  A wave runs alone on its SIMD, so the three kinds of work are software-pipelined
@@ -371,20 +396,30 @@ __global__ __launch_bounds__(256, 1) void attn_dkv_kernel(AttnParams p) {
             bf16x8_t fa[2][2], fc[2][2];                    // [buffer][Q / dO]: row and token fragments
             float4 lq[4], dq4[4];                           // log2(e)*LSE and D of the current half's queries, in groups of 4
             bf16x8_t ap[2][2], ads[2][2];                   // packed P and dS, [half][16-query block]
+            // h, ks, c are compile-time after unrolling: every address is a register plus an immediate
             auto load_a = [&](int h, int ks, int buf) __attribute__((always_inline)) {
-                fa[buf][0] = frag_rows<D>(sq, h * 32 + slot, ks, hh);
-                fa[buf][1] = frag_rows<D>(sdo, h * 32 + slot, ks, hh);
+                fa[buf][0] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<lds_u4_cptr>(pra[ks] + h * 32 * (D * 2)));
+                fa[buf][1] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<lds_u4_cptr>(pra[ks] + (TILE + h * 32 * (D * 2))));
+                (void)buf;
+            };
+            auto tokens = [&](int nt, int off) __attribute__((always_inline)) {
+                typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8_t;
+                const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(pta[nt][0] + off));
+                const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(pta[nt][1] + off));
+                return __builtin_bit_cast(bf16x8_t, (s16x8_t)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
             };
             auto load_c = [&](int h, int c, int buf) __attribute__((always_inline)) {
                 const int j = c / NT, nt = c % NT;
-                fc[buf][0] = frag_tokens<D>(sq, h * 32 + 16 * j, nt, lane);
-                fc[buf][1] = frag_tokens<D>(sdo, h * 32 + 16 * j, nt, lane);
+                fc[buf][0] = tokens(nt, (h * 32 + 16 * j) * (D * 2));
+                fc[buf][1] = tokens(nt, TILE + (h * 32 + 16 * j) * (D * 2));
             };
             auto load_stats = [&](int h) __attribute__((always_inline)) {
 #pragma unroll
                 for (int v4 = 0; v4 < 4; ++v4) {
-                    lq[v4] = *reinterpret_cast<const float4*>(sl + h * 32 + 8 * v4 + 4 * hh);
-                    dq4[v4] = *reinterpret_cast<const float4*>(sl + 64 + h * 32 + 8 * v4 + 4 * hh);
+                    const f32x4v_t a = *reinterpret_cast<lds_f4_cptr>(psl + (h * 32 + 8 * v4) * 4);
+                    const f32x4v_t c = *reinterpret_cast<lds_f4_cptr>(psl + (64 + h * 32 + 8 * v4) * 4);
+                    lq[v4] = make_float4(a.x, a.y, a.z, a.w);
+                    dq4[v4] = make_float4(c.x, c.y, c.z, c.w);
                 }
             };
             auto mma_a = [&](int h, int ks, int buf) __attribute__((always_inline)) {
