@@ -95,6 +95,9 @@ LINEAR_CASES = [
     (257, 688, 256), (2867, 512, 1536),
     (4000, 4096, 1024),      # enough 256x256 tiles for the large-tile kernels (dX and dW)
     (2049, 3584, 4096),
+    # more output tiles than CUs with ragged edges in both directions: blocks walk through several
+    # tiles, the last round is cut into sub-tiles, some of which lie outside the matrix
+    (520, 4232, 4360),
 ]
 
 
