@@ -266,6 +266,32 @@ def main_grad_leg(desc, sv, W, dy, mask_dev, steps: int, warmup: int):
     return {"filtered_ms": round(t_f * 1e3, 4), "dense_ms": round(t_d * 1e3, 4), "speedup": round(t_d / t_f, 4)}
 
 
+def stack_leg(desc, sv, W, dy, mask_dev, layers: int, steps: int, warmup: int):
+    """A stack of `layers` identical layers (Sec. 3.2: once the first gradient is reduced all
+    later ones are): the top layer builds the index (one host read of N_k), every layer below takes
+    the compact dx of the layer above and the shared index through cf_layer_bwd_compact without
+    synchronising.  The layers reuse one set of saved tensors and weights: the timing is that of
+    the kernels, not of a model's memory footprint."""
+    plans = [Bn.LayerBackward(desc, device=DEV) for _ in range(2)]      # ping-pong: dx of one is dy of the next
+
+    def run_filtered():
+        n = plans[0].filtered(sv, W, dy, mask_dev)
+        for l in range(1, layers):
+            src, dst = plans[(l - 1) & 1], plans[l & 1]
+            dst.compact(sv, W, src.grads["dx"], plans[0].idx, plans[0].cu_kept, n)
+
+    def run_dense():
+        plans[0].dense(sv, W, dy)
+        for l in range(1, layers):
+            src, dst = plans[(l - 1) & 1], plans[l & 1]
+            dst.dense(sv, W, src.grads["dx"])
+
+    t_f = time_steps(run_filtered, steps, warmup)
+    t_d = time_steps(run_dense, steps, warmup)
+    return {"layers": layers, "filtered_ms_per_layer": round(t_f * 1e3 / layers, 4),
+            "dense_ms_per_layer": round(t_d * 1e3 / layers, 4), "speedup": round(t_d / t_f, 4)}
+
+
 def cpu_baseline_leg(shape: WL.LayerShape, W, sv, dy, mask):
     """The CPU oracle (fp32 arrays, numpy) on the same workload (the whole batch
     is a bounded sample already: about ten seconds of host time)."""
@@ -299,6 +325,8 @@ def main():
     ap.add_argument("--lora", action="store_true", help="also time the LoRA-adapted layer backward (rank 64)")
     ap.add_argument("--main-grad", action="store_true",
                     help="also time the layer with fp32 main-gradient accumulation of the parameter gradients")
+    ap.add_argument("--stack", type=int, default=0, metavar="L",
+                    help="also time a stack of L layers chained through the compact entry point")
     ap.add_argument("--context-sweep", action="store_true",
                     help="also time context lengths 1K..8K at fixed token count and keep ratios 0.1..1.0 (slow)")
     a = ap.parse_args()
@@ -365,6 +393,12 @@ def main():
         log("main-grad leg")
         mgrad = main_grad_leg(desc, sv, W, dy, mask_dev, a.steps, a.warmup)
         log("main-grad: filtered %.3f ms dense %.3f ms speedup %.3f" % (mgrad["filtered_ms"], mgrad["dense_ms"], mgrad["speedup"]))
+    stack = None
+    if a.stack > 0:
+        log("stack leg")
+        stack = stack_leg(desc, sv, W, dy, mask_dev, a.stack, max(1, a.steps // 2), 1)
+        log("stack of %d: filtered %.3f ms/layer dense %.3f ms/layer speedup %.3f"
+            % (a.stack, stack["filtered_ms_per_layer"], stack["dense_ms_per_layer"], stack["speedup"]))
     log("roofline leg")
     roof = roofline_leg(shape, n_k)
     cpu = None
@@ -393,6 +427,7 @@ def main():
         "context_sweep": ctx,
         "lora": lora,
         "main_grad": mgrad,
+        "stack": stack,
         "roofline": roof,
         "cpu_baseline": cpu,
     }
