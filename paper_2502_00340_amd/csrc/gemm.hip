@@ -322,7 +322,7 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
             const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + (soff + ks * 16 * W2 + 4 * W2)));
             f = __builtin_bit_cast(bf16x8_t, (s16x8_t)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         }
-        if (isA) fa[buf][i] = f;
+        if constexpr (isA) fa[buf][i] = f;
         else fb[buf][i] = f;
     };
     // MFMA q of a sub-step: D = Bfrag x Afrag, lane = output row, registers = 4-column groups
