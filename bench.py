@@ -350,6 +350,8 @@ def main():
     log("timing filtered backward (n_kept=%d of %d)" % (n_k, shape.T))
     t_f = time_steps(lambda: plan.filtered(sv, W, dy, mask_dev), a.steps, a.warmup)
     ev_f = event_times(lambda: plan.filtered(sv, W, dy, mask_dev), a.steps, 0)
+    # the same with N_k known beforehand (top-k keeps a fixed count): no host read, no synchronisation
+    t_k = time_steps(lambda: plan.filtered_known(sv, W, dy, mask_dev, n_k), a.steps, a.warmup)
     log("timing dense backward")
     t_d = time_steps(lambda: plan.dense(sv, W, dy), a.steps, a.warmup)
     flops_f = layer_alg_flops(shape, mask)
@@ -418,6 +420,7 @@ def main():
                                   shape.F, n_k / shape.T, shape.mask_kind),
                    "n_kept": n_k, "tokens": shape.T},
         "speedup_vs_dense": round(t_d / t_f, 4),
+        "ms_per_step_count_known": round(t_k * 1e3, 4),
         "dense_ms_per_step": round(t_d * 1e3, 4),
         "median_ms_per_step_events": round(float(np.median(ev_f)), 4),
         "algorithmic_tflops": round(tfl, 1), "mfma_frac_of_peak_layer": round(tfl / PEAK_BF16_TFLOPS, 4),

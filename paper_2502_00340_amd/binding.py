@@ -244,7 +244,9 @@ class LayerBackward:
         p = (lambda *s: torch.zeros(s, dtype=torch.float32, device=self.device)) if main_grad else e
         self.grads = dict(dwq=p(H, Nq), dwk=p(H, Nkv), dwv=p(H, Nkv), dwo=p(Nq, H), dwg=p(H, F), dwu=p(H, F),
                           dwd=p(F, H), dg1=p(H), dg2=p(H), dx=e(T, H))
-        self.idx = torch.empty(T, dtype=torch.int32, device=self.device)
+        # zeros, not empty: entries past N_k are never written, and must stay valid row numbers for a
+        # caller that passes a wrong count to filtered_known
+        self.idx = torch.zeros(T, dtype=torch.int32, device=self.device)
         self.cu_kept = torch.empty(desc.B + 1, dtype=torch.int32, device=self.device)
         self.ws_bytes = lib().cf_layer_workspace_bytes(C.byref(desc), self.max_kept)
         if self.ws_bytes == 0:
@@ -271,6 +273,23 @@ class LayerBackward:
                                            self.ws_bytes, _stream()),
                "cf_layer_bwd_filtered")
         return int(self._n_host[0])
+
+    def filtered_known(self, saved: dict, weights: dict, dy: torch.Tensor, mask: torch.Tensor, n_kept: int) -> None:
+        """The filtered backward when the caller knows N_k beforehand (a fixed keep ratio: top-k per
+        sequence gives N_k = B*k): cf_build_keep_index without the host copy, cf_gather_rows of the
+        upstream gradient, cf_layer_bwd_compact.  Nothing is read back and the stream is never
+        synchronised.  n_kept must be the number of non-zero mask bytes."""
+        if not hasattr(self, "_index_ws"):
+            wsb = lib().cf_index_workspace_bytes(self.desc.B * self.desc.S)
+            self._index_ws = torch.empty(wsb, dtype=torch.uint8, device=self.device)
+            self._n_dev = torch.empty(1, dtype=torch.int32, device=self.device)
+            self._dy_kept = torch.empty((self.desc.B * self.desc.S, self.desc.H), dtype=dy.dtype, device=self.device)
+        _check(lib().cf_build_keep_index(_ptr(mask), self.desc.B, self.desc.S, _ptr(self.idx), _ptr(self.cu_kept),
+                                         _ptr(self._n_dev), None, _ptr(self._index_ws), self._index_ws.numel(),
+                                         _stream()), "cf_build_keep_index")
+        _check(lib().cf_gather_rows(_ptr(dy), dy.shape[0], dy.shape[1], _dtype_code(dy), _ptr(self.idx), n_kept,
+                                    _ptr(self._dy_kept), _stream()), "cf_gather_rows")
+        self.compact(saved, weights, self._dy_kept, self.idx, self.cu_kept, n_kept)
 
     def compact(self, saved: dict, weights: dict, dy_kept: torch.Tensor, idx: torch.Tensor,
                 cu_kept: torch.Tensor, n_kept: int) -> None:
@@ -316,7 +335,9 @@ class LoraBackward(LayerBackward):
         e = lambda *s: torch.empty(s, dtype=dt, device=self.device)
         self.grads = dict(daq=e(H, rank), dbq=e(rank, Nq), dak=e(H, rank), dbk=e(rank, Nkv), dav=e(H, rank),
                           dbv=e(rank, Nkv), dao=e(Nq, rank), dbo=e(rank, H), dx=e(T, H))
-        self.idx = torch.empty(T, dtype=torch.int32, device=self.device)
+        # zeros, not empty: entries past N_k are never written, and must stay valid row numbers for a
+        # caller that passes a wrong count to filtered_known
+        self.idx = torch.zeros(T, dtype=torch.int32, device=self.device)
         self.cu_kept = torch.empty(desc.B + 1, dtype=torch.int32, device=self.device)
         self.ws_bytes = lib().cf_lora_workspace_bytes(C.byref(desc), rank, T)
         if self.ws_bytes == 0:

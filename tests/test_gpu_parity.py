@@ -273,6 +273,26 @@ def test_layer_small_bf16(shape, rho):
     Hn.check_layer(p, gotd, p.oracle(dense=True), None, Hn.TOL["bf16"])
 
 
+def test_layer_with_a_count_known_beforehand_never_synchronises():
+    """Top-k filtering keeps a known number of tokens: index build without the host copy, gather and
+    the compact entry point give bit for bit what cf_layer_bwd_filtered gives."""
+    shape = SMALL_BF16
+    say("layer known count %s" % shape.name)
+    p = Hn.Problem(shape, 61, "independent", rho=0.5)
+    sv, W, dy, mask = p.device_tensors(DEV)
+    ref = Bn.LayerBackward(p.desc(), device=DEV)
+    n = ref.filtered(sv, W, dy, mask)
+    assert n == int(p.mask.sum())
+    plan = Bn.LayerBackward(p.desc(), device=DEV)
+    plan.filtered_known(sv, W, dy, mask, n)
+    torch.cuda.synchronize()
+    assert torch.equal(plan.idx[:n], ref.idx[:n]) and torch.equal(plan.cu_kept, ref.cu_kept)
+    assert int(plan._n_dev.item()) == n
+    for name in Hn.GRADS:
+        assert torch.equal(plan.grads[name], ref.grads[name]), name
+    assert torch.equal(plan.grads["dx"][:n], ref.grads["dx"][:n])
+
+
 MAIN_GRAD_SHAPES = [
     SMALL_BF16, SMALL_BF16_D128, SMALL_BF16_GROUPED,
     WL.LayerShape("main_grad_f32", B=2, S=96, H=128, Hq=2, Hkv=1, d=64, F=256, dtype="f32"),
