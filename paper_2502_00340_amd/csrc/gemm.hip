@@ -11,7 +11,9 @@
 // bf16 path: 32x32x16 bf16 MFMA, fp32 accumulators, 256 threads = 2x2 waves, one
 // block per CU.  The block tile is (64*TM) x (64*TN) with wave tiles of
 // (32*TM) x (32*TN); three shapes are compiled into one kernel: 256x256 (the
-// wave tile with the fewest LDS bytes per MFMA), 256x128 and 128x128.
+// wave tile with the fewest LDS bytes per MFMA), 256x128 and 128x128; the NT kernel
+// also has 256x192, for outputs whose 256x256 tiles would leave CUs idle (a dX of
+// 4096 x 3072 is 16 x 12 = 192 such tiles but 16 x 16 = 256 of the narrower ones).
 //   * Tile scheduling.  A launch has as many blocks as CUs; a block walks through its
 //     share of the output tiles.  The 256x256 tiles that fill whole rounds of the CUs
 //     come first; the tiles of the last, partial round are cut into 2 or 4 sub-tiles
@@ -80,6 +82,7 @@ struct GemmArgs {
     int c_f32;      // bf16 kernels: C is fp32 (a main-gradient buffer), written without rounding
     int n_full;     // leading blocks that own a whole 256x256 tile
     int sub;        // the remaining tiles are cut into `sub` (1, 2 or 4) sub-tiles, one block each
+    int tile_n;     // 256, or 192 (NT, bf16 output only): every tile is 256x192 and n_full, sub are unused
     // Column groups (ngroups > 1, one K segment): output columns [off_j, off_j + Ng[j]) belong to a
     // matrix of their own, C = Cg[j] [M, Ng[j]] with B operand Bg[j]; every Ng[j] is a multiple of
     // 256, so a tile lies in one group.  N is the sum of the Ng.  One launch then covers several
@@ -144,14 +147,15 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
     constexpr int BM = 64 * TM, BN = 64 * TN, KB = 32, STAGE = GEMM_STAGE_BYTES;
     constexpr int A_BYTES = BM * KB * 2;                // B tile follows the A tile inside a stage
     constexpr int NU = TM + TN;                         // 1 KB wave-loads per wave per K-step: TM for A, TN for B
-    constexpr int NQ = TM * TN, NF = TM + TN;           // MFMAs and fragment reads per 16-wide sub-step
+    constexpr int FM = 2 * TM, FN = 2 * TN;             // 16-row fragments of the wave tile along M and N
+    constexpr int NQ = 2 * FN;                          // MFMAs per sub-step: one 32-row block of A x all of B
     static_assert(A_BYTES + BN * KB * 2 <= STAGE, "tile shape");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    const int slot = lane & 31, hh = lane >> 5;
+    const int l16 = lane & 15, g4 = lane >> 4;
 
-    f32x16_t acc[TM][TN];
+    f32x4_t acc[FM][FN];
     TileRef ld = first;             // the tile whose operands are being loaded
 
     // ---- global -> LDS -----------------------------------------------------------
@@ -268,27 +272,25 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
         else dma16i<dst, 0>(lds0, isA ? rsA : rsB, sec ? v1[u] : v0[u], isA ? (sec ? ka1 : ka0) : (sec ? kb1 : kb0));
     };
 
-    // ---- LDS -> fragments: fragment u < TM is 32-row block u of the wave's A rows, else of its B rows.
-    // An LDS address is a per-lane base register that never changes plus a compile-time constant
-    // (stage, sub-step, block) in the instruction's 16-bit offset field; stages 2 and 3 lie past that
-    // field's reach from the base of stage 0 and get base registers of their own.
+    // ---- LDS -> fragments.  A fragment is 16 rows x 32 k (one K-step): lane l holds row l%16,
+    // k = 8*(l/16) .. +7.  An LDS address is a per-lane base register that never changes plus a
+    // compile-time constant (stage, fragment) in the instruction's 16-bit offset field; stages 2
+    // and 3 lie past that field's reach from the base of stage 0 and get base registers of their own.
     typedef __attribute__((address_space(3))) unsigned char* lds_u8_ptr;
     typedef const __attribute__((address_space(3))) u32x4_t* lds_u32x4_cptr;
-    constexpr int NBASE = MODE == 0 ? 4 : NU;       // NT: (A, B) x sub-step; TN: one per block (the swizzle mixes the block in)
+    constexpr int NBASE = MODE == 0 ? 2 : NU;       // NT: A, B; TN: one per 32-row block (the swizzle mixes the block in)
     unsigned fbase[NBASE][2];
     {
         const unsigned s0 = lds_addr_of(smem);
         if (MODE == 0) {
-            const int nt_sw = (slot >> 2) & 3;
+            const int nt_sw = (l16 >> 2) & 3;
 #pragma unroll
-            for (int ab = 0; ab < 2; ++ab)
-#pragma unroll
-                for (int ks = 0; ks < 2; ++ks) {
-                    const int wrow = ab == 0 ? wm * (32 * TM) : wn * (32 * TN);
-                    const unsigned v = s0 + (ab == 0 ? 0 : A_BYTES) + (wrow + slot) * 64 + (((ks * 2 + hh) ^ nt_sw) << 4);
-                    fbase[ab * 2 + ks][0] = v;
-                    fbase[ab * 2 + ks][1] = v + 2 * STAGE;
-                }
+            for (int ab = 0; ab < 2; ++ab) {
+                const int wrow = ab == 0 ? wm * (32 * TM) : wn * (32 * TN);
+                const unsigned v = s0 + (ab == 0 ? 0 : A_BYTES) + (wrow + l16) * 64 + ((g4 ^ nt_sw) << 4);
+                fbase[ab][0] = v;
+                fbase[ab][1] = v + 2 * STAGE;
+            }
         } else {
 #pragma unroll
             for (int u = 0; u < NU; ++u) {
@@ -296,8 +298,8 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
                 const int i = isA ? u : u - TM;
                 const int W2 = (isA ? BM : BN) * 2;                 // bytes per k-row
                 const int row0 = isA ? wm * (32 * TM) + i * 32 : wn * (32 * TN) + i * 32;
-                const int kl = 8 * hh + ((lane & 15) >> 2);         // k within a 16-wide sub-step (and kl + 4)
-                const int lc = row0 / 8 + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+                const int kl = 8 * g4 + (l16 >> 2);                 // k within the K-step (and kl + 4)
+                const int lc = row0 / 8 + ((lane & 3) >> 1);
                 const int sw = (kl & 3) << 2;                       // the same for k and k + 4
                 const unsigned v = s0 + (isA ? 0 : A_BYTES) + kl * W2 + ((lc ^ sw) << 4) + (lane & 1) * 8;
                 fbase[u][0] = v;
@@ -305,60 +307,87 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
             }
         }
     }
-    bf16x8_t fa[2][TM], fb[2][TN];
-    auto frag_one = [&](auto S, auto KS, auto U, auto BUF) __attribute__((always_inline)) {
-        constexpr int s = decltype(S)::value, ks = decltype(KS)::value, u = decltype(U)::value, buf = decltype(BUF)::value;
-        constexpr bool isA = u < TM;
-        constexpr int i = isA ? u : u - TM;
+    bf16x8_t fa[2][2], fb[2][FN];
+    // fragment F (16 rows; F < FM: of the wave's A rows, else of its B rows) of the K-step in stage S
+    // into fa[BUF][F % 2] or fb[BUF][F - FM]
+    auto frag_one = [&](auto S, auto F, auto BUF) __attribute__((always_inline)) {
+        constexpr int s = decltype(S)::value, fr = decltype(F)::value, buf = decltype(BUF)::value;
+        constexpr bool isA = fr < FM;
+        constexpr int f = isA ? fr : fr - FM;
         constexpr int win = s >> 1, soff = (s & 1) * STAGE;
-        bf16x8_t f;
+        bf16x8_t v;
         if (MODE == 0) {
-            const lds_u8_ptr p = reinterpret_cast<lds_u8_ptr>(fbase[(isA ? 0 : 2) + ks][win]);
-            f = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<lds_u32x4_cptr>(p + (soff + i * 2048)));
+            const lds_u8_ptr p = reinterpret_cast<lds_u8_ptr>(fbase[isA ? 0 : 1][win]);
+            v = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<lds_u32x4_cptr>(p + (soff + f * 1024)));
         } else {
             constexpr int W2 = (isA ? BM : BN) * 2;
-            const lds_u8_ptr p = reinterpret_cast<lds_u8_ptr>(fbase[u][win]);
-            const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + (soff + ks * 16 * W2)));
-            const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + (soff + ks * 16 * W2 + 4 * W2)));
-            f = __builtin_bit_cast(bf16x8_t, (s16x8_t)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            const lds_u8_ptr p = reinterpret_cast<lds_u8_ptr>(fbase[(isA ? 0 : TM) + f / 2][win]);
+            const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + (soff + (f & 1) * 32)));
+            const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + (soff + (f & 1) * 32 + 4 * W2)));
+            v = __builtin_bit_cast(bf16x8_t, (s16x8_t)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         }
-        if constexpr (isA) fa[buf][i] = f;
-        else fb[buf][i] = f;
+        if constexpr (isA) fa[buf][f & 1] = v;
+        else fb[buf][f] = v;
     };
-    // MFMA q of a sub-step: D = Bfrag x Afrag, lane = output row, registers = 4-column groups
-    auto mma_one = [&](auto Q, auto BUF) __attribute__((always_inline)) {
-        constexpr int q = decltype(Q)::value, buf = decltype(BUF)::value;
-        constexpr int i = q / TN, j = q % TN;
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][j], fa[buf][i], acc[i][j], 0, 0, 0);
-    };
-    // One 16-wide sub-step: NQ MFMAs on fragment buffer BUF; spread evenly between them, the NF
-    // fragments of (stage NS, sub-step NKS) go into the other buffer.  DMA = 1 / 2: also the first /
-    // second half of the 2*NU wave-loads of the pair at (seg, k0) (K-steps into stages D0, D1), the
-    // two halves of each 128-byte line of an NT operand row in adjacent instructions.
-    auto substep = [&](auto BUF, auto NS, auto NKS, auto DMA, auto D0, auto D1) __attribute__((always_inline)) {
-        constexpr int buf = decltype(BUF)::value, dma = decltype(DMA)::value;
+    // Sub-step T of a pair (T = KS*TM + A): the MFMAs of K-step KS (stage ST + KS) for the 32-row
+    // block A of the wave's rows against all its columns.  D = Bfrag x Afrag: lane l holds row l%16 of
+    // the fragment and 4 adjacent output columns.  Spread between the MFMAs:
+    //   * the two A fragments of the next sub-step (the next block of the same K-step, or block 0 of
+    //     the next K-step);
+    //   * the B fragments of the next K-step: during K-step 0 of the pair a share of those of K-step 1
+    //     per sub-step; K-step 0 of the next pair is published by the barrier ahead of the pair's last
+    //     sub-step, which therefore reads all of them;
+    //   * a share of the wave-loads: the pair at (seg, k0) is loaded in TM groups, group 0 in the last
+    //     sub-step of a pair (into the two stages its barrier has just retired), groups 1.. in the first
+    //     sub-steps of the next pair, the two halves of each 128-byte line of an NT operand row in
+    //     adjacent instructions.
+    auto substep = [&](auto ST, auto T) __attribute__((always_inline)) {
+        constexpr int st = decltype(ST)::value, t = decltype(T)::value;
+        constexpr int ks = t / TM, a = t % TM;
+        constexpr int st1 = st + 1, st2 = (st + 2) & 3;
+        constexpr bool last = t == 2 * TM - 1;
+        constexpr int cur = st + ks;                                // stage of this K-step
+        constexpr int nxt = ks == 0 ? st1 : st2;                    // stage of the next K-step
+        constexpr int a_stage = a + 1 < TM ? cur : nxt, a_blk = a + 1 < TM ? a + 1 : 0;
+        // reads of this sub-step, in the order their first users come: A fragment 0, B fragments, A fragment 1
+        constexpr int NB = ks == 0 ? 0 : (last ? FN : 0);           // all B fragments at once
+        constexpr int b_lo = ks == 0 ? (a * FN) / TM : 0, b_hi = ks == 0 ? ((a + 1) * FN) / TM : NB;
+        constexpr int NR = 2 + (b_hi - b_lo);
+        // wave-loads of this sub-step: group 0 (last sub-step) or group t + 1 (t < TM - 1)
+        constexpr int grp = last ? 0 : (t < TM - 1 ? t + 1 : -1);
+        constexpr int e_lo = grp < 0 ? 0 : ((grp * NU) / TM) * 2, e_hi = grp < 0 ? 0 : (((grp + 1) * NU) / TM) * 2;
+        constexpr int d0 = last ? st : st2, d1 = d0 + 1;
         static_for<NQ>([&](auto Q) __attribute__((always_inline)) {
             constexpr int q = decltype(Q)::value;
-            if constexpr (dma != 0) {
-                static_for<NU>([&](auto E) __attribute__((always_inline)) {
-                    constexpr int e = decltype(E)::value + (dma - 1) * NU;
-                    if constexpr ((decltype(E)::value * NQ) / NU == q)
-                        dma_one(ic<(e & 1) ? decltype(D1)::value : decltype(D0)::value>{}, ic<(e >> 1)>{}, ic<(e & 1)>{});
-                });
-            }
-            static_for<NF>([&](auto F) __attribute__((always_inline)) {
-                constexpr int f = decltype(F)::value;
-                if constexpr ((f * NQ) / NF == q) frag_one(NS, NKS, F, ic<(buf ^ 1)>{});
+            static_for<e_hi - e_lo>([&](auto E) __attribute__((always_inline)) {
+                constexpr int e = decltype(E)::value + e_lo;
+                if constexpr ((decltype(E)::value * NQ) / (e_hi - e_lo) == q)
+                    dma_one(ic<(e & 1) ? d1 : d0>{}, ic<(e >> 1)>{}, ic<(e & 1)>{});
+            });
+            static_for<NR>([&](auto R) __attribute__((always_inline)) {
+                constexpr int r = decltype(R)::value;
+                if constexpr ((r * NQ) / NR == q) {
+                    if constexpr (r == 0) frag_one(ic<a_stage>{}, ic<2 * a_blk>{}, ic<((a + 1) & 1)>{});
+                    else if constexpr (r == NR - 1) frag_one(ic<a_stage>{}, ic<2 * a_blk + 1>{}, ic<((a + 1) & 1)>{});
+                    else frag_one(ic<nxt>{}, ic<FM + b_lo + r - 1>{}, ic<(ks ^ 1)>{});
+                }
             });
             CF_SCHED_FENCE();
-            mma_one(Q, BUF);
+            {
+                // Inline assembly pins the accumulators to the AGPR file: with the builtin the register
+                // allocator keeps part of the 64 four-register accumulators of a 128x128 wave tile in
+                // VGPRs and copies them to and fro around every MFMA.  An accumulator is touched once
+                // per K-step, so two MFMAs on the same registers are never back to back.
+                constexpr int h = q / FN, j = q % FN, i = 2 * a + h;
+                asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(fb[ks][j]), "v"(fa[a & 1][h]));
+            }
             CF_SCHED_FENCE();
         });
     };
-    // loads of the pair at (seg, k0) outside the MFMA stream (prologue): all of them, or the first half
-    auto issue_pair = [&](auto D0, auto D1, auto HALF) __attribute__((always_inline)) {
+    // loads of the pair at (seg, k0) outside the MFMA stream (prologue): all of them, or group 0 only
+    auto issue_pair = [&](auto D0, auto D1, auto FIRST_GROUP) __attribute__((always_inline)) {
         prepare_pair();
-        static_for<(decltype(HALF)::value ? NU : 2 * NU)>([&](auto E) __attribute__((always_inline)) {
+        static_for<(decltype(FIRST_GROUP)::value ? (NU / TM) * 2 : 2 * NU)>([&](auto E) __attribute__((always_inline)) {
             constexpr int e = decltype(E)::value;
             dma_one(ic<(e & 1) ? decltype(D1)::value : decltype(D0)::value>{}, ic<(e >> 1)>{}, ic<(e & 1)>{});
         });
@@ -366,29 +395,27 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
     // One pair of K-steps s, s+1 in stages ST, ST+1 of the ring of four; the next pair lies in the
     // other two stages, and the loads of the pair after that go back into ST, ST+1 once the barrier
     // has retired them.  The loop body is two pairs, so every stage is a compile-time constant.
-    // The loads of a pair are issued in two halves, right after the barrier that frees their stages
-    // and in the sub-step after that, which halves the burst that the load path sees; the second
-    // half still has two sub-steps to land before the next barrier.
+    // The loads of a pair are issued in TM groups, the first right after the barrier that frees their
+    // stages, which keeps the burst that the load path sees short; the last group still has more
+    // than half a pair to land before the next barrier.
     auto pair_body = [&](auto ST) __attribute__((always_inline)) {
-        constexpr int st = decltype(ST)::value, st1 = st + 1, st2 = (st + 2) & 3;
-        // K-step s (stage st): no barrier: K-step s+1 was published together with K-step s at the
-        // barrier of the previous pair.  Second half of the loads of K-steps s+2, s+3.
-        substep(ic<0>{}, ic<st>{}, ic<1>{}, ic<2>{}, ic<st2>{}, ic<st2 + 1>{});
-        advance_pair();
-        substep(ic<1>{}, ic<st1>{}, ic<0>{}, ic<0>{}, ic<0>{}, ic<0>{});
-        // K-step s+1 (stage st1)
-        substep(ic<0>{}, ic<st1>{}, ic<1>{}, ic<0>{}, ic<0>{}, ic<0>{});
-        prepare_pair();
-        wait_vmcnt<0>();            // K-steps s+2, s+3 have landed (nothing else is in flight)
-        lds_barrier();              // ... and every wave is done with stages st and st1
-        substep(ic<1>{}, ic<st2>{}, ic<0>{}, ic<1>{}, ic<st>{}, ic<st1>{});     // first half of the loads of K-steps s+4, s+5
+        static_for<2 * TM>([&](auto T) __attribute__((always_inline)) {
+            constexpr int t = decltype(T)::value;
+            if constexpr (t == 2 * TM - 1) {
+                prepare_pair();
+                wait_vmcnt<0>();        // K-steps s+2, s+3 have landed (nothing else is in flight)
+                lds_barrier();          // ... and every wave is done with stages ST and ST+1
+            }
+            substep(ST, T);
+            if constexpr (t == TM - 2) advance_pair();      // the last group of the pair has been issued
+        });
     };
 
     // pairs of K-steps, a segment with an odd number of K-steps padded with a zero K-step
     const int npairs = SPLIT ? (kend - kbeg + 2 * KB - 1) / (2 * KB)
                              : (g.K[0] + 2 * KB - 1) / (2 * KB) + (g.K[1] + 2 * KB - 1) / (2 * KB) +
                                    (g.K[2] + 2 * KB - 1) / (2 * KB);
-    // prologue of tile ld: K-steps 0, 1 and the first half of the loads of K-steps 2, 3
+    // prologue of tile ld: K-steps 0, 1 and the first group of the loads of K-steps 2, 3
     auto start_tile = [&]() __attribute__((always_inline)) {
         seg = 0;
         k0 = 0;
@@ -399,24 +426,26 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
         }
         issue_pair(ic<0>{}, ic<1>{}, ic<0>{});
         advance_pair();
-        issue_pair(ic<2>{}, ic<3>{}, ic<1>{});      // the loop's first sub-step issues the other half
+        issue_pair(ic<2>{}, ic<3>{}, ic<1>{});      // the loop's first sub-steps issue the other groups
     };
     constexpr bool OVERLAP = !SPLIT && !CF32;       // the epilogue leaves the operand stages alone
     if (npairs > 0) start_tile();
     for (;;) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < FM; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
+            for (int j = 0; j < FN; ++j)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+                for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.f;
         if (npairs > 0) {
             // K-steps 0 and 1 have landed.  Everything is waited for, the previous tile's stores
             // included: loads and stores share the counter and retire out of order with respect
             // to each other, so a partial count would say nothing about the loads.
             wait_vmcnt<0>();
             lds_barrier();
-            static_for<NF>([&](auto U) __attribute__((always_inline)) { frag_one(ic<0>{}, ic<0>{}, U, ic<0>{}); });
+            frag_one(ic<0>{}, ic<0>{}, ic<0>{});
+            static_for<FN>([&](auto J) __attribute__((always_inline)) { frag_one(ic<0>{}, ic<FM + decltype(J)::value>{}, ic<0>{}); });
+            frag_one(ic<0>{}, ic<1>{}, ic<0>{});
             // two pairs per iteration; an odd count runs one pair of zero K-steps (loads past the last
             // segment return zeros)
             for (int p = 0; p < npairs; p += 2) {
@@ -424,6 +453,10 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
                 pair_body(ic<2>{});
             }
             wait_vmcnt<0>();
+            // The MFMAs are inline assembly (see substep), so the compiler does not know that their
+            // results are still on the way when the next vector instruction wants to read them: the
+            // wait states between a 4-pass MFMA and a reader of its destination are spent here.
+            asm volatile("s_nop 15\n\ts_nop 15");
         }
         const TileRef ep = ld;          // the tile that leaves
         const bool has_next = next_tile(ld);
@@ -436,24 +469,21 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
     if (SPLIT) {
         // ---- split-K epilogue: fp32 accumulators straight to the block's part ----------
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < FM; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int v4 = 0; v4 < 4; ++v4) {
-                    const int m = m0 + wm * (32 * TM) + i * 32 + slot;
-                    const int n = n0 + wn * (32 * TN) + j * 32 + 8 * v4 + 4 * hh;
-                    if (m < g.M && n < ep.N) {               // N is a multiple of 8
-                        float4 o;
-                        o.x = acc[i][j][4 * v4 + 0]; o.y = acc[i][j][4 * v4 + 1];
-                        o.z = acc[i][j][4 * v4 + 2]; o.w = acc[i][j][4 * v4 + 3];
-                        *reinterpret_cast<float4*>(part_out + (int64_t)m * ep.N + n) = o;
-                    }
+            for (int j = 0; j < FN; ++j) {
+                const int m = m0 + wm * (32 * TM) + i * 16 + l16;
+                const int n = n0 + wn * (32 * TN) + j * 16 + 4 * g4;
+                if (m < g.M && n < ep.N) {                   // N is a multiple of 8
+                    float4 o;
+                    o.x = acc[i][j][0]; o.y = acc[i][j][1]; o.z = acc[i][j][2]; o.w = acc[i][j][3];
+                    *reinterpret_cast<float4*>(part_out + (int64_t)m * ep.N + n) = o;
                 }
+            }
         break;
     }
     const float alpha = g.alpha;
-    if (CF32) {
+    if constexpr (CF32) {
         // ---- fp32 epilogue: the two halves of the tile rows (one per wave row) go through LDS in
         // turn, then out as full rows of 16-byte stores, added to beta*C in fp32
         constexpr int HP = BN * 4 + 16;                     // pitch of a staged row of floats
@@ -468,18 +498,16 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
             lds_barrier();
             if (wm == h) {
 #pragma unroll
-                for (int i = 0; i < TM; ++i)
+                for (int i = 0; i < FM; ++i)
 #pragma unroll
-                    for (int j = 0; j < TN; ++j)
-#pragma unroll
-                        for (int v4 = 0; v4 < 4; ++v4) {
-                            const int r = i * 32 + slot;
-                            const int cc = wn * (32 * TN) + j * 32 + 8 * v4 + 4 * hh;
-                            float4 o;
-                            o.x = acc[i][j][4 * v4 + 0] * alpha; o.y = acc[i][j][4 * v4 + 1] * alpha;
-                            o.z = acc[i][j][4 * v4 + 2] * alpha; o.w = acc[i][j][4 * v4 + 3] * alpha;
-                            *reinterpret_cast<float4*>(smem + r * HP + cc * 4) = o;
-                        }
+                    for (int j = 0; j < FN; ++j) {
+                        const int r = i * 16 + l16;
+                        const int cc = wn * (32 * TN) + j * 16 + 4 * g4;
+                        float4 o;
+                        o.x = acc[i][j][0] * alpha; o.y = acc[i][j][1] * alpha;
+                        o.z = acc[i][j][2] * alpha; o.w = acc[i][j][3] * alpha;
+                        *reinterpret_cast<float4*>(smem + r * HP + cc * 4) = o;
+                    }
             }
             lds_barrier();
             if (n < ep.N) {                                  // N is a multiple of 8
@@ -524,7 +552,9 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
     // branch in the stream: rows past M fall outside its range and lanes whose columns lie past
     // N carry an out-of-range offset.
     {
-        constexpr int RBY = 64 * TN;                        // bytes of a staged row (32*TN columns)
+        // bytes of a staged row: 32*TN columns, padded to a power of two of 16-byte chunks (TN = 3:
+        // the lanes of the four pad chunks store nothing)
+        constexpr int RBY = 64 * (TN == 3 ? 4 : TN);
         constexpr int CPR = RBY / 16, RPP = 64 / CPR;       // 16-byte chunks per row, rows per pass of the wave
         constexpr int NP = 32 / RPP, NV = CPR / RPP;        // passes per 32 rows; distinct swizzle phases
         unsigned char* stg = smem + GEMM_STAGES * STAGE + wave * 8192;
@@ -534,26 +564,29 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
         int ln = lane;                                      // as in open_segment: rebuilt per tile, not carried
         asm volatile("" : "+v"(ln));
         const int c = ln % CPR, rl = ln / CPR;
-        const int slot = ln & 31, hh = ln >> 5;
+        const int l16 = ln & 15, g4 = ln >> 4;
         const int n = n0 + wn * (32 * TN) + c * 8;
         const unsigned row_bytes = (unsigned)ep.N * 2u;
         // N is a multiple of 8, so a 16-byte chunk lies inside a row or outside it
-        const unsigned voff = n < ep.N ? (unsigned)(m0 + wm * (32 * TM) + rl) * row_bytes + (unsigned)n * 2u : OOB_FAST;
+        const unsigned voff = (n < ep.N && c < 4 * TN)
+                                  ? (unsigned)(m0 + wm * (32 * TM) + rl) * row_bytes + (unsigned)n * 2u : OOB_FAST;
         const unsigned char* rd[NV];
 #pragma unroll
         for (int v = 0; v < NV; ++v) rd[v] = stg + rl * RBY + ((c ^ ((rl + RPP * v) & (CPR - 1))) << 4);
-        unsigned char* const wr = stg + slot * RBY + hh * 8;
-        const int wsw = slot & (CPR - 1);
+        // a lane's 4 columns of fragment column j are half of the 16-byte chunk 2*j + g4/2 of its row
+        unsigned char* const wr = stg + l16 * RBY + (g4 & 1) * 8;
+        const int wsw = l16 & (CPR - 1);                    // staged row 16*h + l16, and CPR divides 16
+        const int wch = g4 >> 1;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
+            for (int h = 0; h < 2; ++h)
 #pragma unroll
-                for (int v4 = 0; v4 < 4; ++v4) {
+                for (int j = 0; j < FN; ++j) {
                     uint2 o;
-                    o.x = pack_bf16x2(acc[i][j][4 * v4 + 0] * alpha, acc[i][j][4 * v4 + 1] * alpha);
-                    o.y = pack_bf16x2(acc[i][j][4 * v4 + 2] * alpha, acc[i][j][4 * v4 + 3] * alpha);
-                    *reinterpret_cast<uint2*>(wr + (((j * 4 + v4) ^ wsw) << 4)) = o;
+                    o.x = pack_bf16x2(acc[2 * i + h][j][0] * alpha, acc[2 * i + h][j][1] * alpha);
+                    o.y = pack_bf16x2(acc[2 * i + h][j][2] * alpha, acc[2 * i + h][j][3] * alpha);
+                    *reinterpret_cast<uint2*>(wr + h * 16 * RBY + (((2 * j + wch) ^ wsw) << 4)) = o;
                 }
             u32x4_t val[NP];
 #pragma unroll
@@ -589,8 +622,33 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
 template <int MODE, bool CF32>
 __device__ __forceinline__ void gemm_bf16_block(const GemmArgs& g, unsigned char* smem) {
     const int tiles_m = (g.M + 255) / 256, tiles_n = (g.N + 255) / 256;
-    const int n_items = g.n_full + (tiles_m * tiles_n - g.n_full) * g.sub;
     const int stride = (int)gridDim.x;
+    if constexpr (MODE == 0 && !CF32) {
+        if (g.tile_n == 192) {
+            // tiles of 256x192, all of one kind: block b takes tiles b, b + gridDim.x, ...
+            const int tiles_n192 = (g.N + 191) / 192, n_items = tiles_m * tiles_n192;
+            int w = (int)blockIdx.x;
+            auto tile = [&](int w, TileRef& t) __attribute__((always_inline)) {
+                int bm, bn;
+                tile_coords(xcd_order(w, n_items), tiles_m, tiles_n192, bm, bn);
+                t.m0 = __builtin_amdgcn_readfirstlane(bm * 256);
+                t.n0 = __builtin_amdgcn_readfirstlane(bn * 192);
+                t.N = __builtin_amdgcn_readfirstlane(g.N);
+                t.B0 = uniform_ptr(g.B[0]);
+                t.C = uniform_ptr(g.C);
+            };
+            TileRef t;
+            tile(w, t);
+            gemm_tiles<MODE, 4, 3, false, false>(g, t, [&](TileRef& nx) __attribute__((always_inline)) {
+                w += stride;
+                if (w >= n_items) return false;
+                tile(w, nx);
+                return true;
+            }, smem);
+            return;
+        }
+    }
+    const int n_items = g.n_full + (tiles_m * tiles_n - g.n_full) * g.sub;
     // item -> tile; false when a sub-tile lies outside the matrix
     auto decode = [&](int w, TileRef& t) __attribute__((always_inline)) {
         int bm, bn, m0, n0;
@@ -778,11 +836,16 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g) {
 // How the tiles of the last, partial round are cut.  The cost of a round of sub-tiles
 // relative to a round of 256x256 tiles is more than its share of the flops (smaller
 // tiles move more operand bytes per flop); the figures are measured on MI355X at K = 4096.
-static void plan_tiles(int tiles, int n_cu, int& n_full, int& sub) {
+// Returns the launch's length in rounds of 256x256 tiles.
+// A round of 256x192 tiles costs 0.94 of a round of 256x256 tiles although it has 0.75 of the
+// flops: the chip is power-limited under these kernels, so the 192 CUs that a 16 x 12 tile output
+// occupies clock higher than all 256 do (measured: 412 GFLOP in 354 us on 192 CUs, 333 us on 256).
+static constexpr double kCost192 = 0.94;
+static double plan_tiles(int tiles, int n_cu, int& n_full, int& sub) {
     n_full = tiles / n_cu * n_cu;
     const int rem = tiles - n_full;
     sub = 1;
-    if (rem == 0) return;
+    if (rem == 0) return n_full / n_cu;
     const double cost[3] = {1.0, 0.6, 0.4};
     const int cut[3] = {1, 2, 4};
     double best = 1e30;
@@ -793,6 +856,7 @@ static void plan_tiles(int tiles, int n_cu, int& n_full, int& sub) {
             sub = cut[c];
         }
     }
+    return n_full / n_cu + best;
 }
 
 static int compute_units() {
@@ -856,8 +920,17 @@ static hipError_t launch_bf16(GemmArgs& g, hipStream_t st) {
         attr_set = true;
     }
     const int tiles = ceil_div(g.M, 256) * ceil_div(g.N, 256);
-    plan_tiles(tiles, compute_units(), g.n_full, g.sub);
-    const int items = g.n_full + (tiles - g.n_full) * g.sub;
+    const double rounds = plan_tiles(tiles, compute_units(), g.n_full, g.sub);
+    int items = g.n_full + (tiles - g.n_full) * g.sub;
+    if (MODE == 0 && !g.c_f32 && g.ngroups == 1) {
+        // 256x192 tiles instead, when they fill the CUs better (an output of 16 x 12 tiles of
+        // 256x256 leaves a quarter of the CUs idle; as 16 x 16 tiles of 256x192 it is one full round)
+        const int tiles192 = ceil_div(g.M, 256) * ceil_div(g.N, 192);
+        if (ceil_div(tiles192, compute_units()) * kCost192 < rounds - 1e-9) {
+            g.tile_n = 192;
+            items = tiles192;
+        }
+    }
     const int grid = std::min(items, compute_units());      // a block walks through its items
     if (g.c_f32) gemm_bf16_f32out_kernel<MODE><<<grid, 256, GEMM_SMEM, st>>>(g);
     else gemm_bf16_kernel<MODE><<<grid, 256, GEMM_SMEM, st>>>(g);
@@ -878,7 +951,7 @@ hipError_t launch_gemm(int dtype, int mode, const GemmSeg* segs, int nseg, void*
         ++g.nseg;
     }
     for (int s = g.nseg; s < 3; ++s) { g.A[s] = nullptr; g.B[s] = nullptr; g.K[s] = 0; }
-    g.C = C; g.M = M; g.N = N; g.beta = beta; g.alpha = alpha; g.n_full = 0; g.sub = 1;
+    g.C = C; g.M = M; g.N = N; g.beta = beta; g.alpha = alpha; g.n_full = 0; g.sub = 1; g.tile_n = 256;
     g.c_f32 = (c_f32 && dtype == CF_BF16) ? 1 : 0;
     g.ngroups = 1;
     for (int j = 0; j < 3; ++j) { g.Bg[j] = nullptr; g.Cg[j] = nullptr; g.Ng[j] = 0; }
@@ -935,7 +1008,7 @@ hipError_t launch_gemm_tn_groups(const void* A, int K, int M, int ngroups, const
     g.ngroups = ngroups;
     g.A[0] = A; g.B[0] = Bg[0]; g.K[0] = K; g.nseg = 1;
     for (int s = 1; s < 3; ++s) { g.A[s] = nullptr; g.B[s] = nullptr; g.K[s] = 0; }
-    g.C = Cg[0]; g.M = M; g.N = N; g.beta = beta; g.alpha = 1.f; g.n_full = 0; g.sub = 1;
+    g.C = Cg[0]; g.M = M; g.N = N; g.beta = beta; g.alpha = 1.f; g.n_full = 0; g.sub = 1; g.tile_n = 256;
     g.c_f32 = c_f32 ? 1 : 0;
     return launch_bf16<1>(g, st);
 }

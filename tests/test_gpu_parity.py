@@ -98,6 +98,9 @@ LINEAR_CASES = [
     # more output tiles than CUs with ragged edges in both directions: blocks walk through several
     # tiles, the last round is cut into sub-tiles, some of which lie outside the matrix
     (520, 4232, 4360),
+    # dX outputs that fill 256 CUs better as 256x192 tiles: one round with a ragged last tile column
+    # (10 x 19 tiles), and two tiles per block (23 x 22 tiles)
+    (2500, 3600, 264), (5700, 4200, 136),
 ]
 
 
