@@ -127,6 +127,13 @@ __device__ __forceinline__ P* uniform_ptr(P* p) {
     return reinterpret_cast<P*>(((uint64_t)hi << 32) | lo);
 }
 
+// Of D loads spread over the N MFMAs of a sub-step (D <= N), the one that goes with MFMA q, or -1.
+constexpr int load_in_gap(int q, int D, int N) {
+    for (int d = 0; d < D; ++d)
+        if ((d * N) / D == q) return d;
+    return -1;
+}
+
 // One output tile: its origin, and the B operand (of segment 0), output matrix and column count
 // it belongs to (those of its column group in a grouped launch).
 struct TileRef {
@@ -149,6 +156,9 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
     constexpr int NU = TM + TN;                         // 1 KB wave-loads per wave per K-step: TM for A, TN for B
     constexpr int FM = 2 * TM, FN = 2 * TN;             // 16-row fragments of the wave tile along M and N
     constexpr int NQ = 2 * FN;                          // MFMAs per sub-step: one 32-row block of A x all of B
+    // groups that the wave-loads of a pair are issued in (measured: 2 groups cost 4 %; NT is best
+    // with 4 to 6, TN with 3)
+    constexpr int NG = TM == 2 ? 2 : (MODE == 0 ? 4 : 3);
     static_assert(A_BYTES + BN * KB * 2 <= STAGE, "tile shape");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -271,6 +281,18 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
         if (MODE == 0) dma16i<dst - (sec ? KB * 2 : 0), sec ? KB * 2 : 0>(lds0, isA ? rsA : rsB, sec ? v1[u] : v0[u], ka0);
         else dma16i<dst, 0>(lds0, isA ? rsA : rsB, sec ? v1[u] : v0[u], isA ? (sec ? ka1 : ka0) : (sec ? kb1 : kb0));
     };
+    // the same load wrapped around the MFMA acc += a x b (inside the MFMA stream)
+    auto mma_dma_one = [&](f32x4_t& c, const bf16x8_t a, const bf16x8_t b, auto S, auto U, auto SEC) __attribute__((always_inline)) {
+        constexpr int s = decltype(S)::value, u = decltype(U)::value, sec = decltype(SEC)::value;
+        constexpr bool isA = u < TM;
+        constexpr int i = isA ? u : u - TM;
+        constexpr int dst = s * STAGE + (isA ? 0 : A_BYTES) + i * 4096;
+        if (MODE == 0)
+            mfma16_dma16i<dst - (sec ? KB * 2 : 0), sec ? KB * 2 : 0>(c, a, b, lds0, isA ? rsA : rsB, sec ? v1[u] : v0[u], ka0);
+        else
+            mfma16_dma16i<dst, 0>(c, a, b, lds0, isA ? rsA : rsB, sec ? v1[u] : v0[u],
+                                  isA ? (sec ? ka1 : ka0) : (sec ? kb1 : kb0));
+    };
 
     // ---- LDS -> fragments.  A fragment is 16 rows x 32 k (one K-step): lane l holds row l%16,
     // k = 8*(l/16) .. +7.  An LDS address is a per-lane base register that never changes plus a
@@ -337,7 +359,7 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
     //   * the B fragments of the next K-step: during K-step 0 of the pair a share of those of K-step 1
     //     per sub-step; K-step 0 of the next pair is published by the barrier ahead of the pair's last
     //     sub-step, which therefore reads all of them;
-    //   * a share of the wave-loads: the pair at (seg, k0) is loaded in TM groups, group 0 in the last
+    //   * a share of the wave-loads: the pair at (seg, k0) is loaded in NG groups, group 0 in the last
     //     sub-step of a pair (into the two stages its barrier has just retired), groups 1.. in the first
     //     sub-steps of the next pair, the two halves of each 128-byte line of an NT operand row in
     //     adjacent instructions.
@@ -354,16 +376,11 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
         constexpr int b_lo = ks == 0 ? (a * FN) / TM : 0, b_hi = ks == 0 ? ((a + 1) * FN) / TM : NB;
         constexpr int NR = 2 + (b_hi - b_lo);
         // wave-loads of this sub-step: group 0 (last sub-step) or group t + 1 (t < TM - 1)
-        constexpr int grp = last ? 0 : (t < TM - 1 ? t + 1 : -1);
-        constexpr int e_lo = grp < 0 ? 0 : ((grp * NU) / TM) * 2, e_hi = grp < 0 ? 0 : (((grp + 1) * NU) / TM) * 2;
+        constexpr int grp = last ? 0 : (t < NG - 1 ? t + 1 : -1);
+        constexpr int e_lo = grp < 0 ? 0 : ((grp * NU) / NG) * 2, e_hi = grp < 0 ? 0 : (((grp + 1) * NU) / NG) * 2;
         constexpr int d0 = last ? st : st2, d1 = d0 + 1;
         static_for<NQ>([&](auto Q) __attribute__((always_inline)) {
             constexpr int q = decltype(Q)::value;
-            static_for<e_hi - e_lo>([&](auto E) __attribute__((always_inline)) {
-                constexpr int e = decltype(E)::value + e_lo;
-                if constexpr ((decltype(E)::value * NQ) / (e_hi - e_lo) == q)
-                    dma_one(ic<(e & 1) ? d1 : d0>{}, ic<(e >> 1)>{}, ic<(e & 1)>{});
-            });
             static_for<NR>([&](auto R) __attribute__((always_inline)) {
                 constexpr int r = decltype(R)::value;
                 if constexpr ((r * NQ) / NR == q) {
@@ -379,7 +396,13 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
                 // VGPRs and copies them to and fro around every MFMA.  An accumulator is touched once
                 // per K-step, so two MFMAs on the same registers are never back to back.
                 constexpr int h = q / FN, j = q % FN, i = 2 * a + h;
-                asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(fb[ks][j]), "v"(fa[a & 1][h]));
+                constexpr int dsel = load_in_gap(q, e_hi - e_lo, NQ);       // the wave-load that goes with this MFMA
+                if constexpr (dsel >= 0) {
+                    constexpr int e = dsel + e_lo;
+                    mma_dma_one(acc[i][j], fb[ks][j], fa[a & 1][h], ic<(e & 1) ? d1 : d0>{}, ic<(e >> 1)>{}, ic<(e & 1)>{});
+                } else {
+                    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(fb[ks][j]), "v"(fa[a & 1][h]));
+                }
             }
             CF_SCHED_FENCE();
         });
@@ -387,7 +410,7 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
     // loads of the pair at (seg, k0) outside the MFMA stream (prologue): all of them, or group 0 only
     auto issue_pair = [&](auto D0, auto D1, auto FIRST_GROUP) __attribute__((always_inline)) {
         prepare_pair();
-        static_for<(decltype(FIRST_GROUP)::value ? (NU / TM) * 2 : 2 * NU)>([&](auto E) __attribute__((always_inline)) {
+        static_for<(decltype(FIRST_GROUP)::value ? (NU / NG) * 2 : 2 * NU)>([&](auto E) __attribute__((always_inline)) {
             constexpr int e = decltype(E)::value;
             dma_one(ic<(e & 1) ? decltype(D1)::value : decltype(D0)::value>{}, ic<(e >> 1)>{}, ic<(e & 1)>{});
         });
@@ -395,7 +418,7 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
     // One pair of K-steps s, s+1 in stages ST, ST+1 of the ring of four; the next pair lies in the
     // other two stages, and the loads of the pair after that go back into ST, ST+1 once the barrier
     // has retired them.  The loop body is two pairs, so every stage is a compile-time constant.
-    // The loads of a pair are issued in TM groups, the first right after the barrier that frees their
+    // The loads of a pair are issued in NG groups, the first right after the barrier that frees their
     // stages, which keeps the burst that the load path sees short; the last group still has more
     // than half a pair to land before the next barrier.
     auto pair_body = [&](auto ST) __attribute__((always_inline)) {
@@ -407,7 +430,7 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
                 lds_barrier();          // ... and every wave is done with stages ST and ST+1
             }
             substep(ST, T);
-            if constexpr (t == TM - 2) advance_pair();      // the last group of the pair has been issued
+            if constexpr (t == NG - 2) advance_pair();      // the last group of the pair has been issued
         });
     };
 

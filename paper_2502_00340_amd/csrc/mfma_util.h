@@ -115,6 +115,27 @@ __device__ __forceinline__ void dma16i(unsigned lds_base, i32x4_t rsrc, unsigned
                  : "memory", "scc");
 }
 
+// One 16x16x32 bf16 MFMA (acc += a x b, the accumulator pinned to the AGPR file) with a load of
+// the dma16i kind wrapped around it: M0 is written ahead of the MFMA and the load follows it, so
+// the MFMA is the wait state that the load needs after the write of M0, and no gap between two
+// MFMAs of a stream carries more than one of the load's instructions.
+template <int LDS_IMM, int INST_OFF>
+__device__ __forceinline__ void mfma16_dma16i(f32x4_t& acc, bf16x8_t a, bf16x8_t b, unsigned lds_base, i32x4_t rsrc,
+                                              unsigned voffset, unsigned soffset) {
+    static_assert(INST_OFF >= 0 && INST_OFF < 4096, "12-bit instruction offset");
+    lds_base = __builtin_amdgcn_readfirstlane(lds_base);
+    soffset = __builtin_amdgcn_readfirstlane(soffset);
+    rsrc.x = __builtin_amdgcn_readfirstlane(rsrc.x);
+    rsrc.y = __builtin_amdgcn_readfirstlane(rsrc.y);
+    rsrc.z = __builtin_amdgcn_readfirstlane(rsrc.z);
+    rsrc.w = __builtin_amdgcn_readfirstlane(rsrc.w);
+    asm volatile("s_add_u32 m0, %3, %4\n\tv_mfma_f32_16x16x32_bf16 %0, %1, %2, %0\n\t"
+                 "buffer_load_dwordx4 %5, %6, %7 offen offset:%8 lds"
+                 : "+a"(acc)
+                 : "v"(a), "v"(b), "s"(lds_base), "n"(LDS_IMM), "v"(voffset), "s"(rsrc), "s"(soffset), "n"(INST_OFF)
+                 : "memory", "scc");
+}
+
 // Compile-time loop: f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N-1>{})
 template <typename F, int... I>
 __device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
