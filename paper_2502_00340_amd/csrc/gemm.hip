@@ -8,12 +8,20 @@
 // the gradients of a tensor consumed by several linears without rounding in
 // between (e.g. d_gate*Wg^T + d_up*Wu^T).
 //
-// bf16 path: 32x32x16 bf16 MFMA, fp32 accumulators, 256 threads = 2x2 waves, one
+// bf16 path: 16x16x32 bf16 MFMA, fp32 accumulators, 256 threads = 2x2 waves, one
 // block per CU.  The block tile is (64*TM) x (64*TN) with wave tiles of
 // (32*TM) x (32*TN); three shapes are compiled into one kernel: 256x256 (the
 // wave tile with the fewest LDS bytes per MFMA), 256x128 and 128x128; the NT kernel
 // also has 256x192, for outputs whose 256x256 tiles would leave CUs idle (a dX of
 // 4096 x 3072 is 16 x 12 = 192 such tiles but 16 x 16 = 256 of the narrower ones).
+//   * Why the small MFMA.  Under these kernels the chip is power-limited: the shader clock
+//     settles at 1.5-1.9 GHz instead of 2.4, and 128 CUs deliver 75 % of what 256 do.
+//     What counts is therefore energy per flop, not only cycles: 16x16x32 reads and writes
+//     its accumulators half as often per flop as 32x32x16 does, runs at a 14 % higher
+//     clock for the same work and gains 3-6 % on the large products, although its
+//     16-cycle issue rhythm leaves less room for the other instructions (the matrix
+//     cores are busy 72 % of the cycles instead of 77 %).  Fragment reads from LDS cost
+//     no cycles any more but about 9 % of the clock.
 //   * Tile scheduling.  A launch has as many blocks as CUs; a block walks through its
 //     share of the output tiles.  The 256x256 tiles that fill whole rounds of the CUs
 //     come first; the tiles of the last, partial round are cut into 2 or 4 sub-tiles
@@ -31,33 +39,30 @@
 //     stages that the barrier of the pair being computed has just retired; completion
 //     is tracked with vmcnt.  Ragged edges come from the buffer descriptor's range
 //     check, which returns zeros, so there are no branches around loads.
-//   * One LDS barrier per 64 K (four 16-wide sub-steps); the fragments of the next
-//     sub-step are read ahead of the MFMAs of the current one, and the instruction
-//     stream is laid out by hand so that no burst of memory instructions stands
-//     between two MFMAs.  The loop body is two pairs, which makes every stage a
-//     compile-time constant: an LDS read is a loop-invariant per-lane base register
-//     plus an instruction offset, a load sets M0 with one scalar add, takes its
-//     per-lane offset from a register that is fixed for the whole K segment and its K
-//     position from the instruction's scalar offset, so the steady state has no vector
-//     ALU instruction besides the MFMAs.
-//   * What bounds the loop (measured with per-wave cycle counters): not the fragment
-//     reads (removing them changes nothing), not the waits at the barrier (3 %), but the
-//     global -> LDS loads: a CU sustains only so many bytes in flight, so 64 KB per pair
-//     cost about four average load latencies however the loads are issued.  Issuing a
-//     pair's loads in two halves (after the barrier, and one sub-step later) instead
-//     of one burst brought the pair from 2950 to 2660 cycles (2048 of them MFMA
-//     time); without any loads it takes 2250.  Two waves per SIMD (eight waves of
-//     128x64) take the same 2660 cycles, so one wave per SIMD stays.
+//   * One LDS barrier per 64 K.  A pair is 2*TM sub-steps: one 32-row block of the
+//     wave's A rows against all its B columns for one K-step (16 MFMAs in a 128x128 wave
+//     tile).  The A fragments of the next sub-step and a share of the B fragments of
+//     the next K-step are read ahead of their use, and the instruction stream is laid
+//     out by hand: a gap between two MFMAs carries at most one fragment read and one
+//     instruction of a load (the write of M0 goes ahead of an MFMA, the load behind it).
+//     The loop body is two pairs, which makes every stage a compile-time constant: an
+//     LDS read is a loop-invariant per-lane base register plus an instruction offset, a
+//     load takes its per-lane offset from a register that is fixed for the whole K
+//     segment and its K position from the instruction's scalar offset, so the steady
+//     state has no vector ALU instruction besides the MFMAs.
+//   * The loads of a pair go out in groups spread over the sub-steps (four groups in
+//     NT, three in TN; two cost 4 %): a CU sustains only so many bytes in flight, and a
+//     burst of 64 KB stalls the stream.
 //   * NT stage: [rows][32 k], 64-byte rows, 16-byte chunk index XOR (row/4)%4, which
 //     makes the 16 lanes of a ds_read_b128 hit distinct banks; a lane of the loading
 //     wave picks the global chunk that belongs in its (fixed) LDS slot.
 //   * TN stage: [32 k][rows] exactly as in memory, with the 64-byte group index of a
 //     k-row XOR-ed with k%4; fragments come out of LDS through the transpose read
 //     (ds_read_b64_tr_b16), in the same register layout as the NT ones, so MFMA
-//     order and epilogue are shared.  The four k-rows that half a wave touches in
-//     one transpose read land in four different 64-byte bank groups.
+//     order and epilogue are shared.  The four k-rows that a group of 16 lanes touches
+//     in one transpose read land in four different 64-byte bank groups.
 //   * The MFMA is issued with the operands swapped (D = B-frag x A-frag), so a lane
-//     ends up with groups of 4 adjacent output columns; the epilogue packs them to
+//     ends up with 4 adjacent output columns of one row; the epilogue packs them to
 //     bf16 and sends them, 32 rows of the wave tile at a time, through 8 KB of LDS of
 //     the wave's own (above the operand stages, which the next tile is filling by
 //     then) to full-row 16-byte stores.
