@@ -605,16 +605,11 @@ static hipError_t launch_t(const AttnParams& p, const bf16_t* o_kept, const floa
                            int n_kept, hipStream_t st) {
     constexpr int smem_dq = 2 * 2 * 64 * D * 2;
     constexpr int smem_dkv = 4 * (2 * 64 * D * 2 + 512);
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_dq_kernel<D>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem_dq);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_dkv_kernel<D>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, smem_dkv);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_ok_dq{0}, lds_ok_dkv{0};
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(&attn_dq_kernel<D>), smem_dq, lds_ok_dq);
+    if (e != hipSuccess) return e;
+    e = allow_dynamic_lds(reinterpret_cast<const void*>(&attn_dkv_kernel<D>), smem_dkv, lds_ok_dkv);
+    if (e != hipSuccess) return e;
     {
         const int64_t total = (int64_t)n_kept * p.Hq * (D / 8);
         attn_stats_kernel<<<(int)((total + 255) / 256), 256, 0, st>>>(p.do_kept, o_kept, lse_full, p.idx, n_kept,

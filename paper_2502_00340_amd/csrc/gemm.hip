@@ -896,15 +896,17 @@ static double plan_tiles(int tiles, int n_cu, int& n_full, int& sub) {
     return n_full / n_cu + best;
 }
 
+// CUs of the current device (cached per device ordinal; 256 if the query fails)
 static int compute_units() {
-    static int n = 0;
+    static std::atomic<int> cache[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    std::atomic<int>& c = cache[dev & 63];
+    int n = c.load(std::memory_order_relaxed);
     if (n == 0) {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-            n = v;
-        else
-            n = 256;
+        int v = 0;
+        n = (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) ? v : 256;
+        c.store(n, std::memory_order_relaxed);
     }
     return n;
 }
@@ -927,16 +929,12 @@ static int plan_splitk(const GemmArgs& g, int n_cu, size_t ws_bytes, int& kchunk
 
 template <int MODE>
 static hipError_t launch_bf16_splitk(GemmArgs& g, int parts, int kchunk, float* partial, hipStream_t st) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_splitk_kernel<MODE>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_SMEM);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_ok{0};
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(&gemm_bf16_splitk_kernel<MODE>), GEMM_SMEM, lds_ok);
+    if (e != hipSuccess) return e;
     const dim3 grid(ceil_div(g.M, 128) * ceil_div(g.N, 128), parts);
     gemm_bf16_splitk_kernel<MODE><<<grid, 256, GEMM_SMEM, st>>>(g, partial, kchunk);
-    hipError_t e = hipGetLastError();
+    e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int64_t mn = (int64_t)g.M * g.N;
     splitk_reduce_kernel<<<(unsigned)ceil_div(mn / 8, (int64_t)256), 256, 0, st>>>(
@@ -946,16 +944,10 @@ static hipError_t launch_bf16_splitk(GemmArgs& g, int parts, int kchunk, float* 
 
 template <int MODE>
 static hipError_t launch_bf16(GemmArgs& g, hipStream_t st) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<MODE>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_SMEM);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_f32out_kernel<MODE>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_SMEM);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_ok{0}, lds_ok_f32{0};
+    hipError_t e = g.c_f32 ? allow_dynamic_lds(reinterpret_cast<const void*>(&gemm_bf16_f32out_kernel<MODE>), GEMM_SMEM, lds_ok_f32)
+                           : allow_dynamic_lds(reinterpret_cast<const void*>(&gemm_bf16_kernel<MODE>), GEMM_SMEM, lds_ok);
+    if (e != hipSuccess) return e;
     const int tiles = ceil_div(g.M, 256) * ceil_div(g.N, 256);
     const double rounds = plan_tiles(tiles, compute_units(), g.n_full, g.sub);
     int items = g.n_full + (tiles - g.n_full) * g.sub;
