@@ -139,8 +139,19 @@ def roofline_leg(shape: WL.LayerShape, n_k: int, reps: int = 20):
                                        0.0, C.c_void_p(torch.cuda.current_stream().cuda_stream))
         assert rc == 0, rc
 
-    ms = event_times(call_raw, reps)
-    avg = sum(ms) / len(ms)
+    # one event pair around `reps` back-to-back launches: the mean then holds the kernel and the
+    # few microseconds between two kernels of a stream, not a host round trip per launch
+    for _ in range(3):
+        call_raw()
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(reps):
+        call_raw()
+    ev1.record()
+    ev1.synchronize()
+    avg = ev0.elapsed_time(ev1) / reps
     flops = 2.0 * n_k * shape.F * shape.H
     ach = flops / (avg * 1e-3) / 1e12
     # HBM bytes per launch of this kernel, from the two counter runs summarised under profiles/
