@@ -276,6 +276,44 @@ def test_layer_small_bf16(shape, rho):
     Hn.check_layer(p, gotd, p.oracle(dense=True), None, Hn.TOL["bf16"])
 
 
+def _random_layer_cases(seed, n):
+    """Seeded random layer shapes: every size a multiple of 8 only, all head-group ratios, both head
+    dims, every mask kind and keep ratio, with and without rotary tables."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for it in range(n):
+        d = int(rng.choice([64, 128]))
+        Hkv = int(rng.choice([1, 2, 4]))
+        Hq = Hkv * int(rng.choice([1, 2, 4]))
+        out.append(dict(
+            shape=WL.LayerShape("rand%d" % it, B=int(rng.integers(1, 4)), S=int(rng.choice([64, 128, 200, 256, 320, 512])),
+                                H=8 * int(rng.integers(8, 96)), Hq=Hq, Hkv=Hkv, d=d, F=8 * int(rng.integers(8, 160)),
+                                dtype="bf16" if rng.random() < 0.7 else "f32",
+                                rho=float(rng.choice([0.1, 0.3, 0.5, 0.7, 0.9, 1.0])),
+                                mask_kind=str(rng.choice(["topk", "spans", "ragged"]))),
+            rope=bool(rng.random() < 0.3), seed=7000 + it))
+    return out
+
+
+@pytest.mark.parametrize("case", _random_layer_cases(2024, 14), ids=lambda c: c["shape"].name)
+def test_layer_random_shapes(case):
+    shape = case["shape"]
+    say("layer random %s: B=%d S=%d H=%d Hq=%d Hkv=%d d=%d F=%d %s rho=%.1f %s rope=%s" % (
+        shape.name, shape.B, shape.S, shape.H, shape.Hq, shape.Hkv, shape.d, shape.F, shape.dtype, shape.rho,
+        shape.mask_kind, case["rope"]))
+    p = Hn.Problem(shape, case["seed"], "independent",
+                   oracle_dtype=np.float64 if shape.dtype == "f32" else np.float32, rope=case["rope"])
+    sv, W, dy, mask = p.device_tensors(DEV)
+    got, idx, cu, n = Bn.layer_bwd_filtered(p.desc(), sv, W, dy, mask)
+    torch.cuda.synchronize()
+    ridx = np.flatnonzero(p.mask.reshape(-1))
+    assert n == len(ridx) and np.array_equal(idx.cpu().numpy()[:n], ridx)
+    if n == 0:
+        return
+    errs = Hn.check_layer(p, got, p.oracle(), ridx, Hn.TOL[shape.dtype])
+    say("  n_kept=%d max rel err %.2e" % (n, max(errs.values())))
+
+
 def test_layer_with_a_count_known_beforehand_never_synchronises():
     """Top-k filtering keeps a known number of tokens: index build without the host copy, gather and
     the compact entry point give bit for bit what cf_layer_bwd_filtered gives."""
