@@ -120,6 +120,70 @@ def event_times(fn, reps: int, warmup: int = 2):
     return out
 
 
+def _vp(t):
+    import ctypes as C
+    return C.c_void_p(t.data_ptr())
+
+
+def _st():
+    import ctypes as C
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def back_to_back_ms(call, reps: int, warm: int = 3) -> float:
+    """Mean duration of `reps` launches issued back to back on torch's current stream (the stream the
+    library launches on), one HIP-event pair around all of them."""
+    for _ in range(warm):
+        call()
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(reps):
+        call()
+    ev1.record()
+    ev1.synchronize()
+    return ev0.elapsed_time(ev1) / reps
+
+
+def mfma_ceiling_leg(reps: int = 20):
+    """Measured matrix-core ceiling: the GEMM's wave tile (8 x 8 accumulators of 16x16x32 bf16 MFMAs,
+    four waves per CU, all CUs) with every operand in registers and non-zero pseudo-random values;
+    launches as long as the roofline GEMM's, timed the same way (sustained, power-limited rate)."""
+    import ctypes as C
+    lib = Bn.lib()
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    sink = torch.empty(n_cu * 256, dtype=torch.float32, device=DEV)
+    fl = C.c_double(0.0)
+    iters = 640
+
+    def call():
+        rc = lib.cf_probe_mfma_bf16(n_cu, iters, _vp(sink), C.byref(fl), _st())
+        assert rc == 0, rc
+
+    ms = back_to_back_ms(call, reps)
+    return {"TFLOPs": round(fl.value / ms / 1e9, 1), "avg_launch_ms": round(ms, 4), "blocks": n_cu, "iters": iters,
+            "kernel": "cf::mfma_probe_kernel (register-resident 16x16x32 bf16 MFMA loop, no LDS, no global traffic)"}
+
+
+def copy_ceiling_leg(reps: int = 10):
+    """Measured HBM ceiling: a plain 1 GiB -> 1 GiB device copy (bytes read + bytes written per second)."""
+    lib = Bn.lib()
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device=DEV)
+    dst = torch.empty(n, dtype=torch.uint8, device=DEV)
+    src.fill_(3)
+
+    def call():
+        rc = lib.cf_probe_copy(_vp(src), _vp(dst), n, _st())
+        assert rc == 0, rc
+
+    ms = back_to_back_ms(call, reps)
+    del src, dst
+    return {"GBps": round(2.0 * n / ms / 1e6, 1), "avg_launch_ms": round(ms, 4), "bytes_copied": n,
+            "frac_of_8TBps": round(2.0 * n / ms / 1e6 / 8000, 4), "kernel": "cf::copy_probe_kernel"}
+
+
 def roofline_leg(shape: WL.LayerShape, n_k: int, reps: int = 20):
     """Dominant kernel: the parameter-gradient GEMM dW = X_kept^T * dY_kept (the
     contraction runs over the kept tokens) at the layer's largest shape, the FFN
@@ -141,28 +205,24 @@ def roofline_leg(shape: WL.LayerShape, n_k: int, reps: int = 20):
 
     # one event pair around `reps` back-to-back launches: the mean then holds the kernel and the
     # few microseconds between two kernels of a stream, not a host round trip per launch
-    for _ in range(3):
-        call_raw()
-    torch.cuda.synchronize()
-    ev0 = torch.cuda.Event(enable_timing=True)
-    ev1 = torch.cuda.Event(enable_timing=True)
-    ev0.record()
-    for _ in range(reps):
-        call_raw()
-    ev1.record()
-    ev1.synchronize()
-    avg = ev0.elapsed_time(ev1) / reps
+    avg = back_to_back_ms(call_raw, reps)
     flops = 2.0 * n_k * shape.F * shape.H
     ach = flops / (avg * 1e-3) / 1e12
     # HBM bytes per launch of this kernel, from the two counter runs summarised under profiles/
     traffic = None
+    traffic_source = None
     tpath = os.path.join(ROOT, "profiles", "gemm_tn_dw_8b_hbm_traffic.txt")
     if os.path.exists(tpath) and (n_k, shape.F, shape.H) == (4096, 14336, 4096):
         for line in open(tpath):
             if line.strip().startswith("traffic_bytes_per_launch:"):
                 traffic = int(line.split(":")[1])
+                # a stored figure of an earlier profiler run of this same command, not of this run
+                traffic_source = "profiles/gemm_tn_dw_8b_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)"
+    ceil = mfma_ceiling_leg(reps)
     return {"bound": "mfma", "achieved": round(ach, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-            "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
+            "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": traffic, "traffic_source": traffic_source,
+            "ceiling_measured": ceil["TFLOPs"], "frac_of_ceiling": round(ach / ceil["TFLOPs"], 4),
+            "ceiling": ceil,
             "kernel": "cf::gemm_bf16_kernel<1> (TN): dW[F,H] = X_kept^T dY_kept",
             "flops_per_launch": flops, "avg_launch_ms": round(avg, 4), "launches": reps}
 
@@ -174,52 +234,94 @@ def parts_leg(shape: WL.LayerShape, sv, W, dy, mask: np.ndarray, mask_dev, reps:
     out = {}
     n_k = int(mask.sum())
     T, H, F, Nq, Nkv = shape.T, shape.H, shape.F, shape.Nq, shape.Nkv
-    mean = lambda fn: float(np.mean(event_times(fn, reps)))
-    # A1 keep index (no host copy: sync=False)
-    ms = mean(lambda: Bn.build_keep_index(mask_dev, sync=False))
+    import ctypes as C
+    lib = Bn.lib()
+    copyc = copy_ceiling_leg()
+    out["hbm_copy_ceiling"] = copyc
+    hbm = lambda nbytes, ms: {"ms": round(ms, 4), "GBps": round(nbytes / ms / 1e6, 1), "bound": "hbm",
+                              "frac_of_8TBps": round(nbytes / ms / 1e6 / 8000, 4),
+                              "frac_of_copy_ceiling": round(nbytes / ms / 1e6 / copyc["GBps"], 4)}
+
+    # A1 keep index: raw C calls on pre-allocated buffers (no allocation, no host copy in the timed window)
+    def index_call(mask_t):
+        Bq, Sq = mask_t.shape
+        idx_t = torch.empty(Bq * Sq, dtype=torch.int32, device=DEV)
+        cu_t = torch.empty(Bq + 1, dtype=torch.int32, device=DEV)
+        n_t = torch.empty(1, dtype=torch.int32, device=DEV)
+        wsb = lib.cf_index_workspace_bytes(Bq * Sq)
+        ws_t = torch.empty(wsb, dtype=torch.uint8, device=DEV)
+
+        def call():
+            rc = lib.cf_build_keep_index(_vp(mask_t), Bq, Sq, _vp(idx_t), _vp(cu_t), _vp(n_t), None, _vp(ws_t), wsb, _st())
+            assert rc == 0, rc
+        return call, (idx_t, cu_t, n_t, ws_t)
+
+    call, keep1 = index_call(mask_dev)
+    ms = back_to_back_ms(call, reps)
     out["A1_keep_index"] = {"ms": round(ms, 4), "tokens": T}
     big = torch.from_numpy((np.random.default_rng(1).random((4096, 4096)) < 0.5).astype(np.uint8)).to(DEV)
-    ms = mean(lambda: Bn.build_keep_index(big, sync=False))
     nb = int(big.sum().item())
-    out["A1_keep_index_16M_tokens"] = {"ms": round(ms, 4), "GBps": round((big.numel() + 4 * nb) / ms / 1e6, 1),
-                                       "bound": "hbm", "frac_of_8TBps": round((big.numel() + 4 * nb) / ms / 1e6 / 8000, 4)}
-    del big
+    call, keep2 = index_call(big)
+    ms = back_to_back_ms(call, reps)
+    out["A1_keep_index_16M_tokens"] = hbm(big.numel() + 4 * nb + 4 * (big.shape[0] + 1), ms)
+    del big, keep2
     # A2 gather
     idx, cu, _, _ = Bn.build_keep_index(mask_dev)
     dst = torch.empty((n_k, H), dtype=dy.dtype, device=DEV)
-    ms = mean(lambda: Bn.gather_rows(dy, idx, n_k, out=dst))
+
+    def gather_call(src_t, idx_t, n_rows, dst_t):
+        def call():
+            rc = lib.cf_gather_rows(_vp(src_t), src_t.shape[0], src_t.shape[1], Bn.CF_BF16, _vp(idx_t), n_rows,
+                                    _vp(dst_t), _st())
+            assert rc == 0, rc
+        return call
+
+    ms = back_to_back_ms(gather_call(dy, idx, n_k, dst), reps)
     out["A2_gather_dy"] = {"ms": round(ms, 4), "GBps": round(2.0 * n_k * H * 2 / ms / 1e6, 1)}
     src = torch.empty((131072, 4096), dtype=torch.bfloat16, device=DEV)      # 1 GiB
     src.normal_()
     bm = torch.from_numpy((np.random.default_rng(2).random((1, 131072)) < 0.5).astype(np.uint8)).to(DEV)
     bidx, _, _, bn = Bn.build_keep_index(bm)
     bdst = torch.empty((bn, 4096), dtype=torch.bfloat16, device=DEV)
-    ms = mean(lambda: Bn.gather_rows(src, bidx, bn, out=bdst))
-    gb = 2.0 * bn * 4096 * 2 / ms / 1e6
-    out["A2_gather_1GiB_source"] = {"ms": round(ms, 4), "GBps": round(gb, 1), "bound": "hbm",
-                                    "frac_of_8TBps": round(gb / 8000, 4)}
+    ms = back_to_back_ms(gather_call(src, bidx, bn, bdst), reps)
+    out["A2_gather_1GiB_source"] = hbm(2.0 * bn * 4096 * 2 + 4.0 * bn, ms)
     del src, bdst
     # A3 reduced linear backward at the FFN shape
     xk = torch.randn((n_k, F), device=DEV).to(dy.dtype)
     dyk = torch.randn((n_k, H), device=DEV).to(dy.dtype)
-    lib = Bn.lib()
-    import ctypes as C
     dxo = torch.empty((n_k, F), dtype=dy.dtype, device=DEV)
     dwo = torch.empty((F, H), dtype=dy.dtype, device=DEV)
-    vp = lambda t: C.c_void_p(t.data_ptr())
-    st = lambda: C.c_void_p(torch.cuda.current_stream().cuda_stream)
     fl = 2.0 * n_k * F * H
-    ms = mean(lambda: lib.cf_linear_bwd_reduced(None, vp(dyk), vp(W["wd"]), n_k, F, H, Bn.CF_BF16, vp(dxo), None, 0.0, st()))
-    out["A3_dx_ffn"] = {"ms": round(ms, 4), "TFLOPs": round(fl / ms / 1e9, 1), "frac_of_peak": round(fl / ms / 1e9 / PEAK_BF16_TFLOPS, 4)}
-    ms = mean(lambda: lib.cf_linear_bwd_reduced(vp(xk), vp(dyk), None, n_k, F, H, Bn.CF_BF16, None, vp(dwo), 0.0, st()))
-    out["A3_dw_ffn"] = {"ms": round(ms, 4), "TFLOPs": round(fl / ms / 1e9, 1), "frac_of_peak": round(fl / ms / 1e9 / PEAK_BF16_TFLOPS, 4)}
+
+    def lin(xp, wp, dxp, dwp):
+        def call():
+            rc = lib.cf_linear_bwd_reduced(xp, _vp(dyk), wp, n_k, F, H, Bn.CF_BF16, dxp, dwp, 0.0, _st())
+            assert rc == 0, rc
+        return call
+
+    mm = lambda ms: {"ms": round(ms, 4), "TFLOPs": round(fl / ms / 1e9, 1),
+                     "frac_of_peak": round(fl / ms / 1e9 / PEAK_BF16_TFLOPS, 4)}
+    out["A3_dx_ffn"] = mm(back_to_back_ms(lin(None, _vp(W["wd"]), _vp(dxo), None), 2 * reps))
+    out["A3_dw_ffn"] = mm(back_to_back_ms(lin(_vp(xk), None, None, _vp(dwo)), 2 * reps))
     del xk, dxo, dwo
-    # A5 filtered attention backward
+    # A5 filtered attention backward (raw call, pre-allocated outputs and workspace)
     desc = Bn.make_desc(shape.B, shape.S, H, shape.Hq, shape.Hkv, shape.d, F, shape.dtype)
     qk = Bn.gather_rows(sv["q"], idx, n_k)
     ok = Bn.gather_rows(sv["attn_out"], idx, n_k)
     dok = torch.randn((n_k, Nq), device=DEV).to(dy.dtype)
-    ms = mean(lambda: Bn.attn_bwd_filtered(desc, qk, sv["k"], sv["v"], ok, sv["lse"], dok, idx, cu, n_k))
+    dq = torch.empty((n_k, Nq), dtype=dy.dtype, device=DEV)
+    dk = torch.empty((n_k, Nkv), dtype=dy.dtype, device=DEV)
+    dv = torch.empty((n_k, Nkv), dtype=dy.dtype, device=DEV)
+    awsb = lib.cf_attn_workspace_bytes(C.byref(desc), n_k)
+    aws = torch.empty(max(awsb, 256), dtype=torch.uint8, device=DEV)
+
+    def attn_call():
+        rc = lib.cf_attn_bwd_filtered(C.byref(desc), _vp(qk), _vp(sv["k"]), _vp(sv["v"]), _vp(ok), _vp(sv["lse"]),
+                                      _vp(dok), _vp(idx), _vp(cu), n_k, _vp(dq), _vp(dk), _vp(dv), _vp(aws),
+                                      aws.numel(), _st())
+        assert rc == 0, rc
+
+    ms = back_to_back_ms(attn_call, 2 * reps)
     fa = attn_alg_flops(shape, mask)
     out["A5_attn_bwd_filtered"] = {"ms": round(ms, 4), "algorithmic_TFLOPs": round(fa / ms / 1e9, 1),
                                    "frac_of_peak": round(fa / ms / 1e9 / PEAK_BF16_TFLOPS, 4)}

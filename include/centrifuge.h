@@ -234,6 +234,21 @@ cf_status cf_layer_bwd_lora(const cf_layer_desc* desc, const cf_saved* saved, co
                             cf_lora_grads* grads, int32_t* idx_out, int32_t* cu_kept_out,
                             int32_t* n_kept_host, void* ws, size_t ws_bytes, cf_stream stream);
 
+/* ---- measurement probes (for the rooflines of Sec. 3.2's GEMMs and of the gather / row-local
+ * kernels; not part of the method) ------------------------------------------------------------
+ * cf_probe_mfma_bf16: n_blocks blocks of four waves; every wave runs `iters` passes over an 8 x 8
+ *   grid of 16x16x32 bf16 MFMA accumulators (the GEMM kernels' wave tile) with all operands in
+ *   registers and pseudo-random non-zero operand values: no LDS, no global traffic.  sink: device,
+ *   n_blocks*256 floats, overwritten (keeps the work alive).  *flops_out (host, nullable) receives
+ *   the flop count of the launch.  Timing it gives the matrix cores' sustained rate on this chip
+ *   under its power limit: the measured ceiling that the GEMM kernels are compared with.
+ * cf_probe_copy: dst[0..bytes) = src[0..bytes) (device pointers, 16-byte aligned, bytes % 16 == 0,
+ *   no overlap): a plain streaming copy, the measured HBM ceiling (bytes read + bytes written per
+ *   second) for the bandwidth-bound kernels, and the reference that scales profiler byte counters. */
+cf_status cf_probe_mfma_bf16(int32_t n_blocks, int32_t iters, float* sink, double* flops_out,
+                             cf_stream stream);
+cf_status cf_probe_copy(const void* src, void* dst, size_t bytes, cf_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,7 @@ EXPORTS = (
     "cf_status_str", "cf_version", "cf_index_workspace_bytes", "cf_build_keep_index", "cf_gather_rows",
     "cf_linear_bwd_reduced", "cf_attn_workspace_bytes", "cf_attn_bwd_filtered",
     "cf_layer_workspace_bytes", "cf_layer_bwd_filtered", "cf_layer_bwd_compact", "cf_layer_bwd_dense",
-    "cf_lora_workspace_bytes", "cf_layer_bwd_lora",
+    "cf_lora_workspace_bytes", "cf_layer_bwd_lora", "cf_probe_mfma_bf16", "cf_probe_copy",
 )
 
 
@@ -111,6 +111,10 @@ def lib() -> C.CDLL:
     L.cf_layer_bwd_lora.restype = C.c_int
     L.cf_layer_bwd_lora.argtypes = [C.POINTER(LayerDesc), C.POINTER(Saved), C.POINTER(Weights), C.POINTER(Lora), vp,
                                     vp, C.POINTER(LoraGrads), vp, vp, C.POINTER(i32), vp, sz, vp]
+    L.cf_probe_mfma_bf16.restype = C.c_int
+    L.cf_probe_mfma_bf16.argtypes = [i32, i32, vp, C.POINTER(C.c_double), vp]
+    L.cf_probe_copy.restype = C.c_int
+    L.cf_probe_copy.argtypes = [vp, vp, sz, vp]
     _lib = L
     return L
 

@@ -1,0 +1,103 @@
+// Measurement probes: what this chip sustains when a kernel does nothing but the bound
+// operation.  They give the reduced GEMMs (Sec. 3.2) and the gather / row-local kernels a
+// MEASURED ceiling next to the published peaks (2.5 PFLOP/s dense bf16, 8 TB/s HBM):
+//
+//   mfma probe: the GEMM's inner product shape (a 128x128 wave tile = 8 x 8 accumulators of
+//               16x16x32 bf16 MFMAs, four waves per block, one block per CU) with every operand
+//               resident in registers: no LDS traffic, no global traffic, no address arithmetic.
+//               Operands are pseudo-random non-zero values (an all-zero operand draws far less
+//               power than real data and overstates the ceiling of a power-limited chip).
+//   copy probe: dst[i] = src[i] in 16-byte words, four independent loads in flight per lane.
+#include "common.h"
+#include "mfma_util.h"
+
+namespace cf {
+
+__device__ __forceinline__ unsigned probe_hash(unsigned x) {
+    x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+    return x;
+}
+
+// eight bf16 values in (-2, 2), none zero, different in every lane and fragment
+__device__ __forceinline__ bf16x8_t probe_fragment(unsigned seed) {
+    u32x4_t w;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const unsigned h = probe_hash(seed * 4u + e);
+        const float lo = ((float)(h & 0xFFFFu) + 1.0f) * (1.0f / 32768.0f) - 1.0f;
+        const float hi = ((float)(h >> 16) + 1.0f) * (1.0f / 32768.0f) - 1.0f;
+        w[e] = pack_bf16x2(lo == 0.f ? 0.5f : 2.f * lo, hi == 0.f ? -0.5f : 2.f * hi);
+    }
+    return __builtin_bit_cast(bf16x8_t, w);
+}
+
+__global__ __launch_bounds__(256) void mfma_probe_kernel(float* __restrict__ sink, int iters) {
+    const unsigned tid = blockIdx.x * 256u + threadIdx.x;
+    bf16x8_t a[8], b[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        a[i] = probe_fragment(tid * 16u + i);
+        b[i] = probe_fragment(tid * 16u + 8u + i);
+    }
+    f32x4_t acc[8][8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(b[j]), "v"(a[i]));
+    }
+    asm volatile("s_nop 15\n\ts_nop 15");        // the last MFMAs' results are still on the way (see gemm.hip)
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) s += acc[i][j][0] + acc[i][j][3];
+    sink[tid] = s;
+}
+
+__global__ __launch_bounds__(256) void copy_probe_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
+                                                         size_t n16) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const uint4 v0 = src[i], v1 = src[i + stride], v2 = src[i + 2 * stride], v3 = src[i + 3 * stride];
+        dst[i] = v0; dst[i + stride] = v1; dst[i + 2 * stride] = v2; dst[i + 3 * stride] = v3;
+    }
+    for (; i < n16; i += stride) dst[i] = src[i];
+}
+
+}  // namespace cf
+
+using namespace cf;
+
+extern "C" {
+
+cf_status cf_probe_mfma_bf16(int32_t n_blocks, int32_t iters, float* sink, double* flops_out, cf_stream stream) {
+    if (!sink) return CF_ERR_NULL;
+    if (n_blocks <= 0 || n_blocks > 65536 || iters <= 0 || ((uintptr_t)sink % 4) != 0) return CF_ERR_SHAPE;
+    mfma_probe_kernel<<<n_blocks, 256, 0, reinterpret_cast<hipStream_t>(stream)>>>(sink, iters);
+    if (hipGetLastError() != hipSuccess) return CF_ERR_HIP;
+    // 4 waves x 64 MFMAs of 16x16x32 (2*16*16*32 flop) per iteration and block
+    if (flops_out) *flops_out = (double)n_blocks * 4.0 * 64.0 * 16384.0 * (double)iters;
+    return CF_OK;
+}
+
+cf_status cf_probe_copy(const void* src, void* dst, size_t bytes, cf_stream stream) {
+    if (!src || !dst) return CF_ERR_NULL;
+    if (bytes == 0 || bytes % 16 != 0 || ((uintptr_t)src % 16) != 0 || ((uintptr_t)dst % 16) != 0) return CF_ERR_SHAPE;
+    const size_t n16 = bytes / 16;
+    const size_t want = (n16 + 4 * 256 - 1) / (4 * 256);
+    const unsigned grid = (unsigned)(want < 1 ? 1 : (want > 16384 ? 16384 : want));
+    copy_probe_kernel<<<grid, 256, 0, reinterpret_cast<hipStream_t>(stream)>>>(
+        static_cast<const uint4*>(src), static_cast<uint4*>(dst), n16);
+    return hipGetLastError() == hipSuccess ? CF_OK : CF_ERR_HIP;
+}
+
+}  // extern "C"

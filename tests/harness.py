@@ -23,6 +23,9 @@ GRADS = ("dwq", "dwk", "dwv", "dwo", "dwg", "dwu", "dwd", "dg1", "dg2")
 
 # tolerances of the benchmark contract: relative Frobenius error per gradient tensor
 TOL = {"bf16": 2e-2, "f32": 1e-4}
+# per-row / per-column bound (see line_err): a single wrong row, column or tile edge of a large
+# tensor hardly moves the Frobenius norm of the whole tensor, but it moves its own row's
+TOL_LINE = {"bf16": 5e-2, "f32": 1e-3}
 
 
 def rel_fro(got: np.ndarray, ref: np.ndarray) -> float:
@@ -32,6 +35,25 @@ def rel_fro(got: np.ndarray, ref: np.ndarray) -> float:
     if den == 0.0:
         return float(np.linalg.norm(got))
     return float(np.linalg.norm(got - ref) / den)
+
+
+def line_err(got: np.ndarray, ref: np.ndarray) -> float:
+    """Worst row and worst column of a matrix: max over rows of
+    ||got_row - ref_row|| / max(||ref_row||, median row norm), the same over columns, the larger of
+    the two.  The median in the denominator keeps rows that are (nearly) zero in the reference from
+    blowing the ratio up."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if ref.ndim != 2 or ref.size == 0:
+        return rel_fro(got, ref)
+    worst = 0.0
+    for axis in (1, 0):
+        num = np.sqrt(np.sum((got - ref) ** 2, axis=axis))
+        den = np.sqrt(np.sum(ref ** 2, axis=axis))
+        floor = float(np.median(den))
+        den = np.maximum(den, floor if floor > 0.0 else 1.0)
+        worst = max(worst, float(np.max(num / den)))
+    return worst
 
 
 def quantize(a: np.ndarray, dtype: str) -> np.ndarray:
@@ -105,18 +127,26 @@ class Problem:
 
 
 def check_layer(problem: Problem, got: dict, ref: dict, idx: np.ndarray | None, tol: float):
-    """Compare GPU gradients with the oracle's.  idx None: dense dx."""
-    errs = {}
+    """Compare GPU gradients with the oracle's.  idx None: dense dx.  Every tensor must meet the
+    relative Frobenius tolerance `tol` and, row by row and column by column, the looser line bound."""
+    errs, lines = {}, {}
     for name in GRADS:
-        errs[name] = rel_fro(to_np(got[name]), ref[name])
+        g = to_np(got[name])
+        errs[name] = rel_fro(g, ref[name])
+        lines[name] = line_err(g, ref[name])
     dx = to_np(got["dx"])
     if idx is None:
-        errs["dx"] = rel_fro(dx, ref["dx"])
+        rdx = ref["dx"]
     else:
-        errs["dx"] = rel_fro(dx, ref["dx"][idx])
+        rdx = ref["dx"][idx]
         dead = np.ones(ref["dx"].shape[0], dtype=bool)
         dead[idx] = False
         assert np.all(ref["dx"][dead] == 0.0)
+    errs["dx"] = rel_fro(dx, rdx)
+    lines["dx"] = line_err(dx, rdx)
     bad = {k: v for k, v in errs.items() if not (v <= tol)}
     assert not bad, "relative Frobenius error above %g: %s (all: %s)" % (tol, bad, errs)
+    tol_line = TOL_LINE[problem.dtype]
+    bad = {k: v for k, v in lines.items() if not (v <= tol_line)}
+    assert not bad, "worst row/column error above %g: %s (all: %s)" % (tol_line, bad, lines)
     return errs

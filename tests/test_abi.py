@@ -23,7 +23,7 @@ def L():
 def _declared_symbols():
     text = open(os.path.join(ROOT, "include", "centrifuge.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(cf_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(cf_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_header_symbols_are_exported(L):

@@ -68,8 +68,10 @@ def test_config1_tinyllama_full():
     _check_main_grad(plan, p, sv, W, dy)
 
 
-def test_config2_llama3b_ratio07():
-    _run(2, rho=0.7)
+@pytest.mark.parametrize("rho", [1.0, 0.7, 0.5, 0.3])
+def test_config2_llama3b_keep_ratios(rho):
+    """The keep-ratio sweep of the 3B shape: 0.7 and 0.3 give kept counts that are no tile multiple."""
+    _run(2, rho=rho)
 
 
 def test_config3_llama8b_spans_and_dense():

@@ -155,7 +155,7 @@ def test_linear_dw_accumulate_and_empty(dtype):
 # A5 filtered attention backward
 # ---------------------------------------------------------------------------
 
-def _attn_case(dtype, B, S, Hq, Hkv, d, mask, seed):
+def _attn_case(dtype, B, S, Hq, Hkv, d, mask, seed, f8=np.float64):
     rng = np.random.default_rng(seed)
     T = B * S
     q = Hn.quantize(rng.standard_normal((T, Hq * d)), dtype)
@@ -163,7 +163,6 @@ def _attn_case(dtype, B, S, Hq, Hkv, d, mask, seed):
     v = Hn.quantize(rng.standard_normal((T, Hkv * d)), dtype)
     da = Hn.quantize(rng.standard_normal((T, Hq * d)), dtype)
     kw = dict(B=B, S=S, Hq=Hq, Hkv=Hkv, d=d)
-    f8 = np.float64
     a, lse = O.attn_fwd(q.astype(f8), k.astype(f8), v.astype(f8), scale=1 / math.sqrt(d), **kw)
     a = Hn.quantize(a, dtype)
     lse = lse.astype(np.float32)
@@ -181,6 +180,11 @@ def _attn_case(dtype, B, S, Hq, Hkv, d, mask, seed):
             Hn.rel_fro(Hn.to_np(dv), rdv[ridx]))
     say("  rel err dq %.3e dk %.3e dv %.3e (n_kept %d)" % (errs + (n,)))
     assert max(errs) <= Hn.TOL[dtype]
+    # row by row and column by column: a wrong tail row or tile edge cannot hide in the norm of the tensor
+    lines = (Hn.line_err(Hn.to_np(dq), rdq[ridx]), Hn.line_err(Hn.to_np(dk), rdk[ridx]),
+             Hn.line_err(Hn.to_np(dv), rdv[ridx]))
+    say("  worst row/column dq %.3e dk %.3e dv %.3e" % lines)
+    assert max(lines) <= Hn.TOL_LINE[dtype]
     return errs
 
 
@@ -215,6 +219,24 @@ def test_attn_bwd_filtered_degenerate_masks(dtype):
     m[1, 0] = 1                        # only the first token of the middle sequence
     m[2, 5:70] = 1                     # one contiguous span
     _attn_case(dtype, B, S, Hq, Hkv, d, m, seed=3)
+
+
+LONG_ATTN_CASES = [
+    # S, Hq, Hkv, d, mask kind: long sequences reach the unmasked steady-state steps of both kernels,
+    # the span and ragged masks their tile edges; few heads keep the oracle's S x S matrices affordable
+    (4096, 4, 2, 128, "spans"), (4096, 4, 1, 64, "ragged"), (8192, 2, 1, 128, "ragged"),
+    (8192, 2, 2, 64, "spans"), (16384, 2, 1, 128, "topk"),
+]
+
+
+@pytest.mark.parametrize("S,Hq,Hkv,d,kind", LONG_ATTN_CASES)
+def test_attn_bwd_filtered_long_context(S, Hq, Hkv, d, kind):
+    say("attn long bf16 S=%d Hq=%d Hkv=%d d=%d %s" % (S, Hq, Hkv, d, kind))
+    rng = np.random.default_rng(S + d + Hq)
+    shape = WL.LayerShape("attn_long", B=1, S=S, H=8, Hq=Hq, Hkv=Hkv, d=d, F=8, dtype="bf16", rho=0.5,
+                          mask_kind=kind)
+    mask = WL.make_mask(shape, rng)
+    _attn_case("bf16", 1, S, Hq, Hkv, d, mask, seed=S + 7 * d, f8=np.float32 if S > 4096 else np.float64)
 
 
 def test_attn_fp32_small_head_dims():
@@ -449,6 +471,45 @@ def test_layer_stack_of_two_shares_one_index():
     for k in keep:
         a, b = (plan2.grads[k][:n], keep[k][:n]) if k == "dx" else (plan2.grads[k], keep[k])
         assert torch.equal(a, b), k
+
+
+def test_layer_stack_of_eight_error_growth_over_depth():
+    """Eight different layers chained through the compact entry point: the top layer builds the index,
+    every layer below takes the compact dx of the layer above (the library's own, with its rounding)
+    as upstream gradient.  The oracle runs the same chain in float64 on full-length tensors.  The
+    relative error of every layer's outputs against the chained oracle is printed and must stay
+    within the single-layer tolerance: rounding errors handed down the stack do not blow up."""
+    depth = 8
+    shape = WL.LayerShape("stack8", B=2, S=288, H=256, Hq=4, Hkv=2, d=64, F=640, dtype="bf16")
+    say("layer stack of eight")
+    probs = [Hn.Problem(shape, 300 + l, "independent", rho=0.5) for l in range(depth)]
+    mask_np = probs[0].mask
+    ridx = np.flatnonzero(mask_np.reshape(-1))
+    plans = [Bn.LayerBackward(shape_p.desc(), device=DEV) for shape_p in probs[:2]]
+    dev = [p.device_tensors(DEV) for p in probs]
+    worst = []
+    ref_dy = probs[0].dy.astype(np.float64)
+    n = None
+    for l in range(depth):
+        sv, W, dy, mask = dev[l]
+        plan = plans[l & 1]
+        if l == 0:
+            n = plan.filtered(sv, W, dy, mask)
+        else:
+            plan.compact(sv, W, plans[(l - 1) & 1].grads["dx"][:n], plans[0].idx, plans[0].cu_kept, n)
+        torch.cuda.synchronize()
+        probs[l].mask = mask_np
+        probs[l].dy = ref_dy
+        ref = probs[l].oracle()
+        got = dict(plan.grads)
+        got["dx"] = got["dx"][:n]
+        errs = Hn.check_layer(probs[l], got, ref, ridx, Hn.TOL["bf16"])
+        worst.append(max(errs.values()))
+        say("  layer %d below the top: dx %.2e worst tensor %.2e" % (l, errs["dx"], worst[-1]))
+        ref_dy = np.asarray(ref["dx"], dtype=np.float64)       # full length, zero on filtered rows
+    assert max(worst) <= Hn.TOL["bf16"]
+    # no blow-up: the deepest layer is within a small factor of the top one
+    assert worst[-1] <= 4.0 * worst[0] + 1e-3
 
 
 @pytest.mark.parametrize("dtype,mode", [("f32", "consistent"), ("bf16", "independent")])

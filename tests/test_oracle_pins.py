@@ -338,6 +338,49 @@ def test_attention_forward_and_dense_backward_match_torch_autograd():
     assert np.allclose(lse, torch.logsumexp(sc, dim=-1).numpy(), rtol=1e-12, atol=1e-12)
 
 
+def _torch_llama_block(x, W, B, S, Hq, Hkv, d, eps, rope=None):
+    """A pre-norm Llama decoder block written with torch modules' functional forms, independently
+    of the oracle: RMSNorm -> q, k, v projections -> (rotary) -> causal grouped-query attention ->
+    output projection + residual -> RMSNorm -> SwiGLU FFN + residual."""
+    F = torch.nn.functional
+    H = x.shape[1]
+    rms = lambda t, g: F.rms_norm(t, (H,), weight=g, eps=eps)
+    h1 = rms(x, W["g1"])
+    heads = lambda t, n: t.view(B, S, n, d).permute(0, 2, 1, 3)
+    q, k, v = heads(h1 @ W["wq"], Hq), heads(h1 @ W["wk"], Hkv), heads(h1 @ W["wv"], Hkv)
+    if rope is not None:
+        cos, sin = (torch.cat([torch.tensor(t, dtype=x.dtype)] * 2, dim=-1) for t in rope)     # [S, d]
+        rot = lambda t: torch.cat([-t[..., d // 2:], t[..., :d // 2]], dim=-1)
+        q, k = q * cos + rot(q) * sin, k * cos + rot(k) * sin
+    G = Hq // Hkv
+    a = F.scaled_dot_product_attention(q, k.repeat_interleave(G, dim=1), v.repeat_interleave(G, dim=1),
+                                       is_causal=True)
+    a = a.permute(0, 2, 1, 3).reshape(B * S, Hq * d)
+    r = x + a @ W["wo"]
+    h2 = rms(r, W["g2"])
+    return r + (F.silu(h2 @ W["wg"]) * (h2 @ W["wu"])) @ W["wd"]
+
+
+@pytest.mark.parametrize("rope", [False, True])
+def test_layer_forward_and_dense_backward_match_torch_autograd_of_a_llama_block(rope):
+    """Pins the COMPOSITION of the layer (pre-norm order, the two residuals, where the rotation
+    sits): finite differences only tie layer_bwd to layer_fwd, this ties both to a decoder block
+    assembled from torch's own rms_norm / scaled_dot_product_attention / silu."""
+    c, W, x, dy, _ = _tiny_problem(21, S=10)
+    tables = WL.rope_tables(c["S"], c["d"]) if rope else None
+    y, sv = O.layer_fwd(x, W, rope=tables, **_kw(c))
+    g = O.layer_bwd(sv, W, dy, None, rope=tables, **_kw(c))
+    tW = {k: torch.tensor(v, requires_grad=True) for k, v in W.items()}
+    tx = torch.tensor(x, requires_grad=True)
+    ty = _torch_llama_block(tx, tW, c["B"], c["S"], c["Hq"], c["Hkv"], c["d"], 1e-5, rope=tables)
+    assert _relerr(y, ty.detach().numpy()) < 1e-12
+    ty.backward(torch.tensor(dy))
+    assert _relerr(g["dx"], tx.grad.numpy()) < 1e-11
+    for name in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g1", "g2"):
+        key = "d" + name
+        assert _relerr(g[key], tW[name].grad.numpy()) < 1e-11, name
+
+
 def test_attention_row_identities():
     q, k, v, da, _, kw = _attn_problem(12)
     B, S, Hq, Hkv, d = kw["B"], kw["S"], kw["Hq"], kw["Hkv"], kw["d"]
