@@ -133,6 +133,18 @@ cf_status cf_build_keep_index(const uint8_t* mask, int32_t B, int32_t S,
                               int32_t* idx, int32_t* cu_kept, int32_t* n_kept_dev,
                               int32_t* n_kept_host, void* ws, size_t ws_bytes, cf_stream stream);
 
+/* The keep-index build for callers that cannot allocate device memory or carry a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc).  Same
+ * arguments and results as cf_build_keep_index without the workspace and without the host copy:
+ * the per-block counts live in a device array built into the library (16 KiB per GPU, held until
+ * the process ends), nothing is allocated, freed or copied to the host and the stream is not
+ * synchronised.  At most 2^24 tokens (B*S); more returns CF_ERR_UNSUPPORTED before any launch.
+ * All calls on one GPU share that array: calls that overlap on one GPU (two streams, two host
+ * threads) race and must be serialised by the caller. */
+cf_status cf_build_keep_index_static(const uint8_t* mask, int32_t B, int32_t S,
+                                     int32_t* idx, int32_t* cu_kept, int32_t* n_kept_dev,
+                                     cf_stream stream);
+
 /* ---- A2: row gather (Sec. 3.2: remove the filtered rows of saved tensors) --
  * dst[j,:] = src[idx[j],:] for j < n_rows.  src is [src_rows, cols], dst is
  * [n_rows, cols]; cols*sizeof(elt) must be a multiple of 4.  idx entries must lie

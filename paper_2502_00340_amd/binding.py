@@ -20,7 +20,8 @@ _STATUS = {0: "CF_OK", 1: "CF_ERR_NULL", 2: "CF_ERR_SHAPE", 3: "CF_ERR_DTYPE", 4
            5: "CF_ERR_UNSUPPORTED", 6: "CF_ERR_HIP"}
 
 EXPORTS = (
-    "cf_status_str", "cf_version", "cf_index_workspace_bytes", "cf_build_keep_index", "cf_gather_rows",
+    "cf_status_str", "cf_version", "cf_index_workspace_bytes", "cf_build_keep_index",
+    "cf_build_keep_index_static", "cf_gather_rows",
     "cf_linear_bwd_reduced", "cf_attn_workspace_bytes", "cf_attn_bwd_filtered",
     "cf_layer_workspace_bytes", "cf_layer_bwd_filtered", "cf_layer_bwd_compact", "cf_layer_bwd_dense",
     "cf_lora_workspace_bytes", "cf_layer_bwd_lora", "cf_probe_mfma_bf16", "cf_probe_copy",
@@ -86,6 +87,8 @@ def lib() -> C.CDLL:
     L.cf_index_workspace_bytes.argtypes = [i64]
     L.cf_build_keep_index.restype = C.c_int
     L.cf_build_keep_index.argtypes = [vp, i32, i32, vp, vp, vp, C.POINTER(i32), vp, sz, vp]
+    L.cf_build_keep_index_static.restype = C.c_int
+    L.cf_build_keep_index_static.argtypes = [vp, i32, i32, vp, vp, vp, vp]
     L.cf_gather_rows.restype = C.c_int
     L.cf_gather_rows.argtypes = [vp, i64, i64, i32, vp, i32, vp, vp]
     L.cf_linear_bwd_reduced.restype = C.c_int
@@ -181,6 +184,15 @@ def build_keep_index(mask: torch.Tensor, sync: bool = True):
                                      C.byref(n_host) if sync else None, _ptr(ws), wsb, _stream()),
            "cf_build_keep_index")
     return idx, cu, n_dev, (int(n_host.value) if sync else None)
+
+
+def build_keep_index_static(mask: torch.Tensor, idx: torch.Tensor, cu_kept: torch.Tensor, n_kept_dev: torch.Tensor):
+    """cf_build_keep_index_static: every buffer is the caller's, nothing is allocated or read back."""
+    assert mask.dtype == torch.uint8 and mask.is_cuda and mask.dim() == 2 and mask.is_contiguous()
+    B, S = mask.shape
+    assert idx.dtype == torch.int32 and idx.numel() >= B * S and cu_kept.numel() >= B + 1
+    _check(lib().cf_build_keep_index_static(_ptr(mask), B, S, _ptr(idx), _ptr(cu_kept), _ptr(n_kept_dev),
+                                            _stream()), "cf_build_keep_index_static")
 
 
 def gather_rows(src: torch.Tensor, idx: torch.Tensor, n_rows: int, out: torch.Tensor | None = None):

@@ -455,6 +455,17 @@ cf_status cf_build_keep_index(const uint8_t* mask, int32_t B, int32_t S, int32_t
     return CF_OK;
 }
 
+cf_status cf_build_keep_index_static(const uint8_t* mask, int32_t B, int32_t S, int32_t* idx,
+                                     int32_t* cu_kept, int32_t* n_kept_dev, cf_stream stream) {
+    if (!mask || !idx || !cu_kept) return CF_ERR_NULL;
+    if (B <= 0 || S <= 0 || (int64_t)B * S > ((int64_t)1 << 30)) return CF_ERR_SHAPE;
+    if (misaligned(idx, 4) || misaligned(cu_kept, 4) || (n_kept_dev && misaligned(n_kept_dev, 4)))
+        return CF_ERR_SHAPE;
+    if ((int64_t)B * S > IDX_STATIC_MAX_TOKENS) return CF_ERR_UNSUPPORTED;    // beyond the built-in scratch
+    CF_HIP(launch_keep_index_static(mask, B, S, idx, cu_kept, n_kept_dev, as_stream(stream)));
+    return CF_OK;
+}
+
 cf_status cf_gather_rows(const void* src, int64_t src_rows, int64_t cols, int32_t dtype,
                          const int32_t* idx, int32_t n_rows, void* dst, cf_stream stream) {
     if (!src || !idx || !dst) return CF_ERR_NULL;

@@ -104,6 +104,11 @@ static inline size_t dtype_size(int dtype) { return dtype == CF_F32 ? 4 : 2; }
 size_t index_ws_bytes(int64_t n_tokens);
 hipError_t launch_keep_index(const uint8_t* mask, int B, int S, int32_t* idx, int32_t* cu_kept,
                              int32_t* n_kept_dev, void* ws, hipStream_t st);
+// the same with the per-block counts in a device array of the library's own (no workspace, no
+// allocation); at most IDX_STATIC_MAX_TOKENS tokens
+static constexpr int64_t IDX_STATIC_MAX_TOKENS = (int64_t)1 << 24;
+hipError_t launch_keep_index_static(const uint8_t* mask, int B, int S, int32_t* idx, int32_t* cu_kept,
+                                    int32_t* n_kept_dev, hipStream_t st);
 hipError_t launch_gather(const void* src, int64_t cols_bytes, const int32_t* idx, int n_rows,
                          void* dst, hipStream_t st);
 

@@ -172,6 +172,33 @@ hipError_t launch_keep_index(const uint8_t* mask, int B, int S, int32_t* idx, in
 }
 
 // ---------------------------------------------------------------------------
+// The same index build for callers that cannot allocate or hand in a workspace: the per-block
+// counts live in a file-scope device array.  Every GPU holds its own copy of the array at its own
+// address; host code never uses the array's name as a pointer but looks its address up once per
+// device (with that device current) and passes that pointer to the kernels.  The kernels write
+// every entry they later read (block b's count, b < number of blocks), so nothing has to be
+// cleared between calls; calls that overlap on one GPU share the array and race.
+// ---------------------------------------------------------------------------
+static __device__ __align__(256) int32_t scratch[IDX_STATIC_MAX_TOKENS / IDX_CHUNK];
+
+hipError_t launch_keep_index_static(const uint8_t* mask, int B, int S, int32_t* idx, int32_t* cu_kept,
+                                    int32_t* n_kept_dev, hipStream_t st) {
+    static std::atomic<void*> scratch_ptr[64];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    void* ptr = scratch_ptr[dev].load(std::memory_order_acquire);
+    if (ptr == nullptr) {
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (ptr == nullptr) return hipErrorInvalidSymbol;
+        scratch_ptr[dev].store(ptr, std::memory_order_release);
+    }
+    return launch_keep_index(mask, B, S, idx, cu_kept, n_kept_dev, ptr, st);
+}
+
+// ---------------------------------------------------------------------------
 // gather: dst[j,:] = src[idx[j],:], rows copied as 16-byte (or 4-byte) words
 // ---------------------------------------------------------------------------
 

@@ -67,6 +67,16 @@ def test_keep_index_argument_errors(L):
     assert f(FAKE, 1 << 20, 1 << 20, FAKE, FAKE, None, C.byref(n), FAKE, 1 << 30, None) == 2
 
 
+def test_static_keep_index_argument_errors(L):
+    f = L.cf_build_keep_index_static
+    assert f(None, 2, 8, FAKE, FAKE, None, None) == 1
+    assert f(FAKE, 2, 8, None, FAKE, None, None) == 1
+    assert f(FAKE, 0, 8, FAKE, FAKE, None, None) == 2
+    assert f(FAKE, 2, 8, C.c_void_p(0x10002), FAKE, None, None) == 2
+    assert f(FAKE, 1, (1 << 24) + 1, FAKE, FAKE, None, None) == 5      # beyond the built-in scratch
+    assert f(FAKE, 4097, 4096, FAKE, FAKE, None, None) == 5
+
+
 def test_gather_argument_errors(L):
     f = L.cf_gather_rows
     assert f(None, 4, 8, 1, FAKE, 2, FAKE, None) == 1
