@@ -435,6 +435,9 @@ def main():
     ap.add_argument("--no-sweep", action="store_true", help="skip the keep-ratio sweep")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-parts", action="store_true", help="skip the per-part timings")
+    ap.add_argument("--only-roofline", action="store_true",
+                    help="run the roofline leg alone (the dominant GEMM and the measured MFMA ceiling) and print it; "
+                         "the short command that the profiler counter runs use")
     ap.add_argument("--lora", action="store_true", help="also time the LoRA-adapted layer backward (rank 64)")
     ap.add_argument("--main-grad", action="store_true",
                     help="also time the layer with fp32 main-gradient accumulation of the parameter gradients")
@@ -453,6 +456,10 @@ def main():
     Bn.lib()        # fail loudly if the HIP library is missing
 
     shape = WL.CONFIGS[a.config]
+    if a.only_roofline:
+        n_k = shape.B * WL.topk_count(shape.rho, shape.S)
+        print(json.dumps({"roofline": roofline_leg(shape, n_k), "hbm_copy_ceiling": copy_ceiling_leg()}), flush=True)
+        return
     log("config %d %s: generating inputs" % (a.config, shape.name))
     W, sv, dy, mask, rng = make_inputs(shape, WL.config_seed(a.config))
     mask_dev = torch.from_numpy(mask).to(DEV)
