@@ -271,7 +271,7 @@ def parts_leg(shape: WL.LayerShape, sv, W, dy, mask: np.ndarray, mask_dev, reps:
 
     def gather_call(src_t, idx_t, n_rows, dst_t):
         def call():
-            rc = lib.cf_gather_rows(_vp(src_t), src_t.shape[0], src_t.shape[1], Bn.CF_BF16, _vp(idx_t), n_rows,
+            rc = lib.cf_gather_rows(_vp(src_t), src_t.shape[0], src_t.shape[1], Bn.CF_BF16, _vp(idx_t), None, n_rows,
                                     _vp(dst_t), _st())
             assert rc == 0, rc
         return call
@@ -341,7 +341,7 @@ def context_sweep_leg(base: WL.LayerShape, steps: int, warmup: int):
         md = torch.from_numpy(mask).to(DEV)
         desc = Bn.make_desc(shape.B, shape.S, shape.H, shape.Hq, shape.Hkv, shape.d, shape.F, shape.dtype)
         plan = Bn.LayerBackward(desc, device=DEV)
-        t_f = time_steps(lambda: plan.filtered(sv, W, dy, md), steps, warmup)
+        t_f = time_steps(lambda: plan.filtered_async(sv, W, dy, md), steps, warmup)
         t_d = time_steps(lambda: plan.dense(sv, W, dy), steps, warmup)
         out["by_context"][str(S)] = {"B": shape.B, "filtered_ms": round(t_f * 1e3, 4), "dense_ms": round(t_d * 1e3, 4),
                                      "speedup": round(t_d / t_f, 4)}
@@ -350,7 +350,7 @@ def context_sweep_leg(base: WL.LayerShape, steps: int, warmup: int):
             for rho in (0.1, 0.2, 0.3, 0.4, 0.5, 0.6, 0.7, 0.8, 0.9, 1.0):
                 m = WL.mask_topk(rng, shape.B, shape.S, rho)
                 mdd = torch.from_numpy(m).to(DEV)
-                t = time_steps(lambda: plan.filtered(sv, W, dy, mdd), steps, warmup)
+                t = time_steps(lambda: plan.filtered_async(sv, W, dy, mdd), steps, warmup)
                 out["by_ratio"]["%.1f" % rho] = {"ms": round(t * 1e3, 4), "speedup": round(t_d / t, 4)}
         del plan, W, sv, dy
         torch.cuda.empty_cache()
@@ -374,24 +374,24 @@ def main_grad_leg(desc, sv, W, dy, mask_dev, steps: int, warmup: int):
     """The same layer with fp32 main-gradient buffers that every call adds to (gradient
     accumulation over micro-batches): each dW element is read and written as fp32."""
     plan = Bn.LayerBackward(desc, device=DEV, main_grad=True)
-    t_f = time_steps(lambda: plan.filtered(sv, W, dy, mask_dev), steps, warmup)
+    t_f = time_steps(lambda: plan.filtered_async(sv, W, dy, mask_dev), steps, warmup)
     t_d = time_steps(lambda: plan.dense(sv, W, dy), steps, warmup)
     return {"filtered_ms": round(t_f * 1e3, 4), "dense_ms": round(t_d * 1e3, 4), "speedup": round(t_d / t_f, 4)}
 
 
 def stack_leg(desc, sv, W, dy, mask_dev, layers: int, steps: int, warmup: int):
     """A stack of `layers` identical layers (Sec. 3.2: once the first gradient is reduced all
-    later ones are): the top layer builds the index (one host read of N_k), every layer below takes
-    the compact dx of the layer above and the shared index through cf_layer_bwd_compact without
-    synchronising.  The layers reuse one set of saved tensors and weights: the timing is that of
+    later ones are): the top layer builds the index, every layer below takes the compact dx of the
+    layer above, the shared index and the device-side count through cf_layer_bwd_compact_dev; the
+    host never reads N_k and nothing synchronises.  The layers reuse one set of saved tensors and weights: the timing is that of
     the kernels, not of a model's memory footprint."""
     plans = [Bn.LayerBackward(desc, device=DEV) for _ in range(2)]      # ping-pong: dx of one is dy of the next
 
     def run_filtered():
-        n = plans[0].filtered(sv, W, dy, mask_dev)
+        plans[0].filtered_async(sv, W, dy, mask_dev)
         for l in range(1, layers):
             src, dst = plans[(l - 1) & 1], plans[l & 1]
-            dst.compact(sv, W, src.grads["dx"], plans[0].idx, plans[0].cu_kept, n)
+            dst.compact_dev(sv, W, src.grads["dx"], plans[0].idx, plans[0].cu_kept, plans[0].n_kept_dev)
 
     def run_dense():
         plans[0].dense(sv, W, dy)
@@ -468,10 +468,16 @@ def main():
     n_k = int(mask.sum())
 
     log("timing filtered backward (n_kept=%d of %d)" % (n_k, shape.T))
-    t_f = time_steps(lambda: plan.filtered(sv, W, dy, mask_dev), a.steps, a.warmup)
-    ev_f = event_times(lambda: plan.filtered(sv, W, dy, mask_dev), a.steps, 0)
-    # the same with N_k known beforehand (top-k keeps a fixed count): no host read, no synchronisation
+    # cf_layer_bwd_filtered never synchronises (every kernel reads N_k on the device): K calls are
+    # enqueued back to back, bracketed by the two synchronisations of time_steps
+    t_f = time_steps(lambda: plan.filtered_async(sv, W, dy, mask_dev), a.steps, a.warmup)
+    assert plan.n_kept() == n_k
+    ev_f = event_times(lambda: plan.filtered_async(sv, W, dy, mask_dev), a.steps, 0)
+    # the same composed from the single-purpose calls by a caller that knows N_k beforehand (top-k keeps
+    # a fixed count): index build, gather of the upstream gradient, compact call with the host count
     t_k = time_steps(lambda: plan.filtered_known(sv, W, dy, mask_dev, n_k), a.steps, a.warmup)
+    # and with the host waiting for N_k after every call
+    t_w = time_steps(lambda: plan.filtered(sv, W, dy, mask_dev), a.steps, a.warmup)
     log("timing dense backward")
     t_d = time_steps(lambda: plan.dense(sv, W, dy), a.steps, a.warmup)
     flops_f = layer_alg_flops(shape, mask)
@@ -482,7 +488,7 @@ def main():
         for rho in (1.0, 0.7, 0.5, 0.3):
             m = WL.mask_topk(rng, shape.B, shape.S, rho)
             md = torch.from_numpy(m).to(DEV)
-            t = time_steps(lambda: plan.filtered(sv, W, dy, md), a.steps, a.warmup)
+            t = time_steps(lambda: plan.filtered_async(sv, W, dy, md), a.steps, a.warmup)
             sweep["%.1f" % rho] = {"ms": round(t * 1e3, 4), "speedup_vs_dense": round(t_d / t, 4),
                                    "kept_tokens_per_s": round(int(m.sum()) / t, 1),
                                    "tflops": round(layer_alg_flops(shape, m) / t / 1e12, 1)}
@@ -541,6 +547,7 @@ def main():
                    "n_kept": n_k, "tokens": shape.T},
         "speedup_vs_dense": round(t_d / t_f, 4),
         "ms_per_step_count_known": round(t_k * 1e3, 4),
+        "ms_per_step_host_reads_count_every_step": round(t_w * 1e3, 4),
         "dense_ms_per_step": round(t_d * 1e3, 4),
         "median_ms_per_step_events": round(float(np.median(ev_f)), 4),
         "algorithmic_tflops": round(tfl, 1), "mfma_frac_of_peak_layer": round(tfl / PEAK_BF16_TFLOPS, 4),

@@ -25,11 +25,16 @@
  *   - dtype CF_BF16: bfloat16 storage, fp32 accumulation and fp32 row
  *     statistics; CF_F32: fp32 everywhere (check mode, not tuned).  LSE is
  *     always fp32.  In CF_BF16 mode H, Hq*d, Hkv*d and F must be multiples of
- *     8 and d must be 64 or 128; in CF_F32 mode they must be multiples of 4 and
- *     d <= 256.
+ *     8 and d must be 64 or 128 (another multiple of 8 returns CF_ERR_UNSUPPORTED);
+ *     in CF_F32 mode they must be multiples of 4 and d <= 256.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *     Calls enqueue work and return without synchronising, except where a
- *     host result is requested (n_kept_host) -- see each function.
+ *     Calls enqueue work and return without synchronising; the two exceptions
+ *     (cf_build_keep_index with a host pointer, cf_layer_bwd_lora with a mask) say so.
+ *   - The number of kept tokens N_k is a DEVICE value after the index build.  Calls
+ *     that take `n_kept_dev` + `max_kept` read it there: max_kept is the upper bound
+ *     that buffers and launches are sized for, the kernels work on min(N_k, max_kept)
+ *     rows, and nothing waits for the host.  Calls that take a plain `n_kept` are for
+ *     callers that know the count (a fixed keep ratio, or after reading it back).
  *   - Errors: argument errors are detected on the host before anything is
  *     launched and reported as a cf_status; nothing is written in that case.
  *     A HIP runtime failure is reported as CF_ERR_HIP.
@@ -146,11 +151,12 @@ cf_status cf_build_keep_index_static(const uint8_t* mask, int32_t B, int32_t S,
                                      cf_stream stream);
 
 /* ---- A2: row gather (Sec. 3.2: remove the filtered rows of saved tensors) --
- * dst[j,:] = src[idx[j],:] for j < n_rows.  src is [src_rows, cols], dst is
- * [n_rows, cols]; cols*sizeof(elt) must be a multiple of 4.  idx entries must lie
- * in [0, src_rows) (not checked: they live on the device). */
+ * dst[j,:] = src[idx[j],:] for j < min(N_k, max_kept), N_k = *n_kept_dev (device; NULL: exactly
+ * max_kept rows).  src is [src_rows, cols], dst has room for max_kept rows; cols*sizeof(elt) must be
+ * a multiple of 4.  idx entries must lie in [0, src_rows) (not checked: they live on the device). */
 cf_status cf_gather_rows(const void* src, int64_t src_rows, int64_t cols, int32_t dtype,
-                         const int32_t* idx, int32_t n_rows, void* dst, cf_stream stream);
+                         const int32_t* idx, const int32_t* n_kept_dev, int32_t max_kept, void* dst,
+                         cf_stream stream);
 
 /* ---- A3: dimension-reduced linear backward (Sec. 3.2, the two GEMM types) ---
  * For Y = X*W with W [in,out]:
@@ -180,35 +186,46 @@ cf_status cf_attn_bwd_filtered(const cf_layer_desc* desc, const void* q_kept, co
                                void* ws, size_t ws_bytes, cf_stream stream);
 
 /* ---- whole layer -----------------------------------------------------------
- * cf_layer_bwd_filtered: mask -> keep index -> row gathers -> all reduced GEMMs,
- * row-local backward ops (SwiGLU, RMSNorm, residuals; Sec. 3.2 "G (.) g") and the
- * filtered attention backward.  dy_full is the upstream gradient on all T rows
- * (rows of filtered tokens are ignored).  Outputs: grads->dx compact [N_k,H] (the
- * row-sparse gradient for the layer below), all parameter gradients; idx_out
- * [T] / cu_kept_out [B+1] (device, nullable) receive the keep index;
- * n_kept_host (host, required; page-locked memory makes the copy cheaper) receives N_k.
- * The call synchronises the stream
- * once, right after the index build, to size the remaining launches.
- * cf_layer_bwd_dense: the same kernels with every token kept and no index or
- * gather; dx is [T,H].
+ * cf_layer_bwd_filtered: mask -> keep index -> all reduced GEMMs, row-local backward ops (SwiGLU,
+ * RMSNorm, residuals; Sec. 3.2 "G (.) g") and the filtered attention backward.  No tensor is gathered
+ * by a kernel of its own: the kept rows of dy_full, gate, up, r, x are read through the index by the
+ * kernels that consume them, and those of attn_out and q are copied by the attention backward's
+ * row-statistics pass.  dy_full is the upstream gradient on all T rows (rows of filtered tokens are
+ * ignored).  Outputs: grads->dx compact [N_k,H] (the row-sparse gradient for the layer below), all
+ * parameter gradients; idx_out [T] / cu_kept_out [B+1] / n_kept_dev_out [1] (device, each nullable)
+ * receive the keep index and N_k; n_kept_host (HOST, nullable; page-locked memory keeps the copy
+ * asynchronous) receives N_k once the stream has reached that point: read it after synchronising.
+ * The call itself never synchronises: every kernel reads N_k on the device.
+ *   max_kept: upper bound of N_k that the workspace and grads->dx are sized for; 0 or a value above
+ *   T means T, which is always sufficient.  A caller that knows its keep ratio saves workspace.  If
+ *   the mask keeps more than max_kept tokens the call processes the first max_kept kept tokens only
+ *   and the result is not the layer's gradient: compare the N_k read back with max_kept.
+ * cf_layer_bwd_dense: the same kernels with every token kept and no index; dx is [T,H].
  * cf_layer_bwd_compact: a layer BELOW the one whose call built the keep index
  * (Sec. 3.2: once the first gradient is reduced, every later gradient is; Sec. 3.1:
  * the sparsity is handed on to all front layers).  dy_kept [n_kept,H] is the compact
  * dx of the layer above; idx [n_kept] and cu_kept [B+1] (device) are the index that
  * call returned and n_kept its N_k.  Saved activations are still full length.
  * Outputs as for the filtered call.  Nothing is copied to the host and the stream is
- * not synchronised, so a stack of layers costs one synchronisation in total.
- * ws must hold cf_layer_workspace_bytes(desc, max_kept) bytes; max_kept = T is
- * always sufficient (for the compact call: max_kept >= n_kept). */
+ * not synchronised.
+ * cf_layer_bwd_compact_dev: the same for a caller that has not read N_k back: n_kept_dev is the
+ * device count the filtered call returned and max_kept the bound it was given, so a whole stack of
+ * layers runs without a single synchronisation.
+ * ws must hold cf_layer_workspace_bytes(desc, max_kept) bytes (compact call: max_kept >= n_kept). */
 size_t cf_layer_workspace_bytes(const cf_layer_desc* desc, int32_t max_kept);
 cf_status cf_layer_bwd_filtered(const cf_layer_desc* desc, const cf_saved* saved,
                                 const cf_weights* w, const void* dy_full, const uint8_t* mask,
-                                cf_grads* grads, int32_t* idx_out, int32_t* cu_kept_out,
-                                int32_t* n_kept_host, void* ws, size_t ws_bytes, cf_stream stream);
+                                int32_t max_kept, cf_grads* grads, int32_t* idx_out,
+                                int32_t* cu_kept_out, int32_t* n_kept_dev_out, int32_t* n_kept_host,
+                                void* ws, size_t ws_bytes, cf_stream stream);
 cf_status cf_layer_bwd_compact(const cf_layer_desc* desc, const cf_saved* saved,
                                const cf_weights* w, const void* dy_kept, const int32_t* idx,
                                const int32_t* cu_kept, int32_t n_kept, cf_grads* grads,
                                void* ws, size_t ws_bytes, cf_stream stream);
+cf_status cf_layer_bwd_compact_dev(const cf_layer_desc* desc, const cf_saved* saved,
+                                   const cf_weights* w, const void* dy_kept, const int32_t* idx,
+                                   const int32_t* cu_kept, const int32_t* n_kept_dev, int32_t max_kept,
+                                   cf_grads* grads, void* ws, size_t ws_bytes, cf_stream stream);
 cf_status cf_layer_bwd_dense(const cf_layer_desc* desc, const cf_saved* saved,
                              const cf_weights* w, const void* dy_full, cf_grads* grads,
                              void* ws, size_t ws_bytes, cf_stream stream);
@@ -237,8 +254,11 @@ typedef struct {
 } cf_lora_grads;
 
 /* cf_layer_bwd_lora: the filtered layer backward of a LoRA-adapted layer.  Arguments as for
- * cf_layer_bwd_filtered; mask == NULL means "every token kept" (no index, no gather, no host
- * synchronisation: the dense LoRA backward of the same library, and n_kept_host may be NULL).
+ * cf_layer_bwd_filtered (without max_kept), but with a mask this call does synchronise the stream
+ * once, right after the index build, to read N_k into *n_kept_host (required then) and size its
+ * launches (the split-K launches of the rank-r products are planned on the host).  mask == NULL means
+ * "every token kept" (no index, no gather, no host synchronisation: the dense LoRA backward of the
+ * same library, and n_kept_host may be NULL).
  * ws must hold cf_lora_workspace_bytes(desc, rank, max_kept) bytes. */
 size_t cf_lora_workspace_bytes(const cf_layer_desc* desc, int32_t rank, int32_t max_kept);
 cf_status cf_layer_bwd_lora(const cf_layer_desc* desc, const cf_saved* saved, const cf_weights* w,

@@ -23,7 +23,8 @@ EXPORTS = (
     "cf_status_str", "cf_version", "cf_index_workspace_bytes", "cf_build_keep_index",
     "cf_build_keep_index_static", "cf_gather_rows",
     "cf_linear_bwd_reduced", "cf_attn_workspace_bytes", "cf_attn_bwd_filtered",
-    "cf_layer_workspace_bytes", "cf_layer_bwd_filtered", "cf_layer_bwd_compact", "cf_layer_bwd_dense",
+    "cf_layer_workspace_bytes", "cf_layer_bwd_filtered", "cf_layer_bwd_compact", "cf_layer_bwd_compact_dev",
+    "cf_layer_bwd_dense",
     "cf_lora_workspace_bytes", "cf_layer_bwd_lora", "cf_probe_mfma_bf16", "cf_probe_copy",
 )
 
@@ -90,7 +91,7 @@ def lib() -> C.CDLL:
     L.cf_build_keep_index_static.restype = C.c_int
     L.cf_build_keep_index_static.argtypes = [vp, i32, i32, vp, vp, vp, vp]
     L.cf_gather_rows.restype = C.c_int
-    L.cf_gather_rows.argtypes = [vp, i64, i64, i32, vp, i32, vp, vp]
+    L.cf_gather_rows.argtypes = [vp, i64, i64, i32, vp, vp, i32, vp, vp]
     L.cf_linear_bwd_reduced.restype = C.c_int
     L.cf_linear_bwd_reduced.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, f32, vp]
     L.cf_attn_workspace_bytes.restype = sz
@@ -101,8 +102,11 @@ def lib() -> C.CDLL:
     L.cf_layer_workspace_bytes.restype = sz
     L.cf_layer_workspace_bytes.argtypes = [C.POINTER(LayerDesc), i32]
     L.cf_layer_bwd_filtered.restype = C.c_int
-    L.cf_layer_bwd_filtered.argtypes = [C.POINTER(LayerDesc), C.POINTER(Saved), C.POINTER(Weights), vp, vp,
-                                        C.POINTER(Grads), vp, vp, C.POINTER(i32), vp, sz, vp]
+    L.cf_layer_bwd_filtered.argtypes = [C.POINTER(LayerDesc), C.POINTER(Saved), C.POINTER(Weights), vp, vp, i32,
+                                        C.POINTER(Grads), vp, vp, vp, C.POINTER(i32), vp, sz, vp]
+    L.cf_layer_bwd_compact_dev.restype = C.c_int
+    L.cf_layer_bwd_compact_dev.argtypes = [C.POINTER(LayerDesc), C.POINTER(Saved), C.POINTER(Weights), vp, vp, vp,
+                                           vp, i32, C.POINTER(Grads), vp, sz, vp]
     L.cf_layer_bwd_compact.restype = C.c_int
     L.cf_layer_bwd_compact.argtypes = [C.POINTER(LayerDesc), C.POINTER(Saved), C.POINTER(Weights), vp, vp, vp,
                                        i32, C.POINTER(Grads), vp, sz, vp]
@@ -195,13 +199,16 @@ def build_keep_index_static(mask: torch.Tensor, idx: torch.Tensor, cu_kept: torc
                                             _stream()), "cf_build_keep_index_static")
 
 
-def gather_rows(src: torch.Tensor, idx: torch.Tensor, n_rows: int, out: torch.Tensor | None = None):
+def gather_rows(src: torch.Tensor, idx: torch.Tensor, n_rows: int, out: torch.Tensor | None = None,
+                n_kept_dev: torch.Tensor | None = None):
+    """n_kept_dev None: exactly n_rows rows.  Otherwise min(*n_kept_dev, n_rows) rows are copied (the
+    count is read on the device) and `out` has room for n_rows."""
     assert src.is_cuda and src.dim() == 2 and src.is_contiguous() and idx.dtype == torch.int32
     rows, cols = src.shape
     if out is None:
         out = torch.empty((n_rows, cols), dtype=src.dtype, device=src.device)
-    _check(lib().cf_gather_rows(_ptr(src), rows, cols, _dtype_code(src), _ptr(idx), n_rows, _ptr(out),
-                                _stream()), "cf_gather_rows")
+    _check(lib().cf_gather_rows(_ptr(src), rows, cols, _dtype_code(src), _ptr(idx), _ptr(n_kept_dev), n_rows,
+                                _ptr(out), _stream()), "cf_gather_rows")
     return out
 
 
@@ -269,7 +276,8 @@ class LayerBackward:
             raise CfError(2, "cf_layer_workspace_bytes")
         self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=self.device)
         self._g = Grads(*([self.grads[n].data_ptr() for n in GRAD_NAMES] + [1 if main_grad else 0]))
-        # N_k comes back through page-locked host memory: the copy needs no staging buffer
+        self.n_kept_dev = torch.zeros(1, dtype=torch.int32, device=self.device)
+        # N_k comes back through page-locked host memory: the copy is asynchronous
         self._n_host = torch.empty(1, dtype=torch.int32).pin_memory()
 
     def _pack(self, saved: dict, weights: dict):
@@ -278,34 +286,54 @@ class LayerBackward:
         w = Weights(*[weights[n].data_ptr() for n in _WEIGHTS])
         return sv, w
 
-    def filtered(self, saved: dict, weights: dict, dy: torch.Tensor, mask: torch.Tensor) -> int:
-        """Runs cf_layer_bwd_filtered; results land in self.grads (dx: first N_k rows), self.idx,
-        self.cu_kept.  Returns N_k."""
+    def filtered_async(self, saved: dict, weights: dict, dy: torch.Tensor, mask: torch.Tensor) -> None:
+        """Enqueues cf_layer_bwd_filtered and returns at once: nothing is read back and the stream is
+        not synchronised.  Results land in self.grads (dx: first N_k rows), self.idx, self.cu_kept,
+        self.n_kept_dev; the page-locked word behind n_kept() holds N_k once the stream has run."""
         sv, w = self._pack(saved, weights)
         self._n_host[0] = -1
         _check(lib().cf_layer_bwd_filtered(C.byref(self.desc), C.byref(sv), C.byref(w), _ptr(dy), _ptr(mask),
-                                           C.byref(self._g), _ptr(self.idx), _ptr(self.cu_kept),
+                                           self.max_kept, C.byref(self._g), _ptr(self.idx), _ptr(self.cu_kept),
+                                           _ptr(self.n_kept_dev),
                                            C.cast(self._n_host.data_ptr(), C.POINTER(C.c_int32)), _ptr(self.ws),
                                            self.ws_bytes, _stream()),
                "cf_layer_bwd_filtered")
+
+    def n_kept(self) -> int:
+        """N_k of the last filtered call (synchronises the current stream)."""
+        torch.cuda.current_stream().synchronize()
         return int(self._n_host[0])
 
+    def filtered(self, saved: dict, weights: dict, dy: torch.Tensor, mask: torch.Tensor) -> int:
+        """filtered_async, then waits for the stream and returns N_k."""
+        self.filtered_async(saved, weights, dy, mask)
+        return self.n_kept()
+
     def filtered_known(self, saved: dict, weights: dict, dy: torch.Tensor, mask: torch.Tensor, n_kept: int) -> None:
-        """The filtered backward when the caller knows N_k beforehand (a fixed keep ratio: top-k per
-        sequence gives N_k = B*k): cf_build_keep_index without the host copy, cf_gather_rows of the
-        upstream gradient, cf_layer_bwd_compact.  Nothing is read back and the stream is never
-        synchronised.  n_kept must be the number of non-zero mask bytes."""
+        """The filtered backward composed from the single-purpose calls by a caller that knows N_k
+        beforehand (a fixed keep ratio: top-k per sequence gives N_k = B*k): cf_build_keep_index
+        without the host copy, cf_gather_rows of the upstream gradient, cf_layer_bwd_compact with the
+        host count.  n_kept must be the number of non-zero mask bytes."""
         if not hasattr(self, "_index_ws"):
             wsb = lib().cf_index_workspace_bytes(self.desc.B * self.desc.S)
             self._index_ws = torch.empty(wsb, dtype=torch.uint8, device=self.device)
-            self._n_dev = torch.empty(1, dtype=torch.int32, device=self.device)
             self._dy_kept = torch.empty((self.desc.B * self.desc.S, self.desc.H), dtype=dy.dtype, device=self.device)
         _check(lib().cf_build_keep_index(_ptr(mask), self.desc.B, self.desc.S, _ptr(self.idx), _ptr(self.cu_kept),
-                                         _ptr(self._n_dev), None, _ptr(self._index_ws), self._index_ws.numel(),
+                                         _ptr(self.n_kept_dev), None, _ptr(self._index_ws), self._index_ws.numel(),
                                          _stream()), "cf_build_keep_index")
-        _check(lib().cf_gather_rows(_ptr(dy), dy.shape[0], dy.shape[1], _dtype_code(dy), _ptr(self.idx), n_kept,
+        _check(lib().cf_gather_rows(_ptr(dy), dy.shape[0], dy.shape[1], _dtype_code(dy), _ptr(self.idx), None, n_kept,
                                     _ptr(self._dy_kept), _stream()), "cf_gather_rows")
         self.compact(saved, weights, self._dy_kept, self.idx, self.cu_kept, n_kept)
+
+    def compact_dev(self, saved: dict, weights: dict, dy_kept: torch.Tensor, idx: torch.Tensor,
+                    cu_kept: torch.Tensor, n_kept_dev: torch.Tensor) -> None:
+        """cf_layer_bwd_compact_dev: a layer below the index-building one, with the count still on the
+        device (no host read anywhere in the stack)."""
+        sv, w = self._pack(saved, weights)
+        _check(lib().cf_layer_bwd_compact_dev(C.byref(self.desc), C.byref(sv), C.byref(w), _ptr(dy_kept), _ptr(idx),
+                                              _ptr(cu_kept), _ptr(n_kept_dev), self.max_kept, C.byref(self._g),
+                                              _ptr(self.ws), self.ws_bytes, _stream()),
+               "cf_layer_bwd_compact_dev")
 
     def compact(self, saved: dict, weights: dict, dy_kept: torch.Tensor, idx: torch.Tensor,
                 cu_kept: torch.Tensor, n_kept: int) -> None:

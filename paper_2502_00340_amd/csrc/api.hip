@@ -10,15 +10,16 @@ namespace cf {
 hipError_t launch_attn_bwd_ref(const cf_layer_desc& L, float scale, const void* q_kept,
                                const void* k_full, const void* v_full, const float* lse_full,
                                const void* do_kept, const float* Drow, const int32_t* idx,
-                               const int32_t* cu_kept, int n_kept, void* dq_kept, void* dk_kept,
+                               const int32_t* cu_kept, RowCount rows, void* dq_kept, void* dk_kept,
                                void* dv_kept, hipStream_t st);
 bool attn_mfma_supported(const cf_layer_desc& L);
 size_t attn_mfma_partial_bytes(const cf_layer_desc& L, int n_kept);
 hipError_t launch_attn_bwd_mfma(const cf_layer_desc& L, float scale, const void* q_kept,
                                 const void* k_full, const void* v_full, const void* o_kept,
                                 const float* lse_full, const void* do_kept, float* stat,
-                                const int32_t* idx, const int32_t* cu_kept, int n_kept, void* dq_kept,
-                                void* dk_kept, void* dv_kept, float* partials, hipStream_t st);
+                                const int32_t* idx, const int32_t* cu_kept, RowCount rows, void* dq_kept,
+                                void* dk_kept, void* dv_kept, float* partials, hipStream_t st,
+                                const void* o_full = nullptr, const void* q_full = nullptr);
 }  // namespace cf
 
 using namespace cf;
@@ -49,7 +50,11 @@ cf_status check_attn_desc(const cf_layer_desc* L) {
     if ((int64_t)L->B * L->S > (int64_t)1 << 30) return CF_ERR_SHAPE;
     if (L->Hq % L->Hkv != 0) return CF_ERR_SHAPE;
     if (L->dtype == CF_BF16) {
-        if (L->d != 64 && L->d != 128) return CF_ERR_SHAPE;
+        if (L->d % 8 != 0) return CF_ERR_SHAPE;
+        if (L->d != 64 && L->d != 128) return CF_ERR_UNSUPPORTED;      // a valid head size this build has no kernel for
+        // the matrix-core attention kernels address K, V (per sequence) and Q, dO (per sequence's kept
+        // rows) with 32-bit byte offsets
+        if ((int64_t)L->S * L->Hq * L->d * 2 >= ((int64_t)1 << 32)) return CF_ERR_UNSUPPORTED;
     } else {
         if (!pow2(L->d) || L->d < 4 || L->d > 256) return CF_ERR_SHAPE;
     }
@@ -140,41 +145,54 @@ LayerWs carve_layer(const cf_layer_desc& L, int max_kept, void* ws) {
     return w;
 }
 
+// o_full / q_full (nullable): the attention output and the queries at full length; the row-statistics
+// pass then copies their kept rows (through idx) into the writable buffers o_kept / q_kept.
 cf_status attn_dispatch(const cf_layer_desc& L, const void* q_kept, const void* k_full,
                         const void* v_full, const void* o_kept, const float* lse_full,
-                        const void* do_kept, const int32_t* idx, const int32_t* cu_kept, int n_kept,
-                        void* dq_kept, void* dk_kept, void* dv_kept, void* attn_ws, hipStream_t st) {
+                        const void* do_kept, const int32_t* idx, const int32_t* cu_kept, RowCount rows,
+                        void* dq_kept, void* dk_kept, void* dv_kept, void* attn_ws, hipStream_t st,
+                        const void* o_full = nullptr, const void* q_full = nullptr) {
+    const int n_kept = rows.n;
     if (n_kept <= 0) return CF_OK;
     const float scale = eff_scale(L);
     float* Drow = static_cast<float*>(attn_ws);
     float* partials = reinterpret_cast<float*>(static_cast<unsigned char*>(attn_ws) + attn_drow_bytes(L, n_kept));
     if (attn_mfma_supported(L)) {
         CF_HIP(launch_attn_bwd_mfma(L, scale, q_kept, k_full, v_full, o_kept, lse_full, do_kept, Drow, idx,
-                                    cu_kept, n_kept, dq_kept, dk_kept, dv_kept, partials, st));
+                                    cu_kept, rows, dq_kept, dk_kept, dv_kept, partials, st, o_full, q_full));
     } else {
-        CF_HIP(launch_attn_rowdot(L.dtype, do_kept, o_kept, n_kept, L.Hq, L.d, Drow, st));
+        CF_HIP(launch_attn_rowdot(L.dtype, do_kept, o_full ? o_full : o_kept, rows, L.Hq, L.d, Drow, st,
+                                  o_full ? idx : nullptr, const_cast<void*>(o_kept), q_full,
+                                  const_cast<void*>(q_kept)));
         CF_HIP(launch_attn_bwd_ref(L, scale, q_kept, k_full, v_full, lse_full, do_kept, Drow, idx,
-                                   cu_kept, n_kept, dq_kept, dk_kept, dv_kept, st));
+                                   cu_kept, rows, dq_kept, dk_kept, dv_kept, st));
     }
     return CF_OK;
 }
 
-// Everything after the keep index is known.  N rows are live; idx == nullptr
-// means the dense backward (row j is token j).
+// Everything after the keep index is launched.  rows: the live rows (a host count, or a device count
+// with its upper bound); idx == nullptr means the dense backward (row j is token j).
+// dy: the upstream gradient, compact [rows,H] when dy_is_full == false; when dy_is_full it is the
+// full-length [T,H] tensor and its kept rows are read through idx (by the first GEMM's A-tile loads
+// and by the SwiGLU pass, which also leaves the compact copy in w.dy_k for the GEMM that contracts
+// over the kept tokens).
 cf_status layer_core(const cf_layer_desc& L, const cf_saved& sv, const cf_weights& W,
-                     const void* dy_rows /*[N,H] compact*/, const int32_t* idx,
-                     const int32_t* cu_kept, int N, cf_grads& G, const LayerWs& w, hipStream_t st) {
+                     const void* dy, bool dy_is_full, const int32_t* idx,
+                     const int32_t* cu_kept, RowCount rows, cf_grads& G, const LayerWs& w, hipStream_t st) {
     const int dt = L.dtype;
     const size_t e = dtype_size(dt);
+    const int N = rows.n;
+    const int32_t* nd = rows.dev;
     const int H = L.H, F = L.F, Nq = L.Hq * L.d, Nkv = L.Hkv * L.d;
+    const int64_t T = (int64_t)L.B * L.S;
     // main-gradient mode: the nine parameter gradients are fp32 buffers that this call adds to
     const bool mg = G.main_grad != 0;
     auto dw_gemm = [&](const void* A, const void* B, void* C, int M, int Ncols) {
         GemmSeg s{A, B, N};
-        return launch_gemm(dt, 1, &s, 1, C, M, Ncols, mg ? 1.f : 0.f, st, 1.f, nullptr, 0, mg);
+        return launch_gemm(dt, 1, &s, 1, C, M, Ncols, mg ? 1.f : 0.f, st, 1.f, nullptr, 0, mg, nd);
     };
 
-    if (N == 0) {   // nothing kept: every gradient is zero, dx has no rows
+    if (N == 0) {   // nothing kept (known to the host): every gradient is zero, dx has no rows
         if (mg) return CF_OK;
         void* outs[9] = {G.dwq, G.dwk, G.dwv, G.dwo, G.dwg, G.dwu, G.dwd, G.dg1, G.dg2};
         size_t sz[9] = {(size_t)H * Nq, (size_t)H * Nkv, (size_t)H * Nkv, (size_t)Nq * H,
@@ -182,65 +200,64 @@ cf_status layer_core(const cf_layer_desc& L, const cf_saved& sv, const cf_weight
         for (int i = 0; i < 9; ++i) CF_HIP(launch_fill_zero(outs[i], sz[i] * e, st));
         return CF_OK;
     }
-
-    const void* a_rows = sv.attn_out;
-    const void* q_rows = sv.q;
-    if (idx) {
-        CF_HIP(launch_gather(sv.attn_out, (int64_t)Nq * e, idx, N, w.a_k, st));
-        CF_HIP(launch_gather(sv.q, (int64_t)Nq * e, idx, N, w.q_k, st));
-        a_rows = w.a_k;
-        q_rows = w.q_k;
-    }
+    if (dy_is_full && !idx) return CF_ERR_NULL;
 
     // ---- SwiGLU FFN: y = r + act*Wd --------------------------------------------
     // d_act = dy * Wd^T first; one pass over it then yields d_gate, d_up and act (the SwiGLU
     // product, rebuilt for dWd), so gate and up are read once
     void* d_act = w.bufF1;
     {   // [N,F] = [N,H] x [F,H]^T
-        GemmSeg s{dy_rows, W.wd, H};
-        CF_HIP(launch_gemm(dt, 0, &s, 1, d_act, N, F, 0.f, st));
+        GemmSeg s{dy, W.wd, H};
+        CF_HIP(launch_gemm(dt, 0, &s, 1, d_act, N, F, 0.f, st, 1.f, nullptr, 0, false, nd,
+                           dy_is_full ? idx : nullptr, dy_is_full ? T : 0));
     }
     void* d_gate = w.bufF1;   // in place over d_act
     void* d_up = w.bufF0;
     void* act = w.bufF2;
-    CF_HIP(launch_swiglu_bwd(dt, d_act, sv.gate, sv.up, idx, N, F, d_gate, d_up, act, st));
+    const void* dy_rows = dy_is_full ? w.dy_k : dy;
+    CF_HIP(launch_swiglu_bwd(dt, d_act, sv.gate, sv.up, idx, rows, F, d_gate, d_up, act, st,
+                             dy_is_full ? dy : nullptr, H, dy_is_full ? w.dy_k : nullptr));
     CF_HIP(dw_gemm(act, dy_rows, G.dwd, F, H));     // dWd = act^T * dy           [F,H]
 
     void* h2 = w.bufHa;
-    CF_HIP(launch_rmsnorm_fwd(dt, sv.r, W.g2, idx, N, H, L.rms_eps, h2, st));
+    CF_HIP(launch_rmsnorm_fwd(dt, sv.r, W.g2, idx, rows, H, L.rms_eps, h2, st));
     CF_HIP(dw_gemm(h2, d_gate, G.dwg, H, F));
     CF_HIP(dw_gemm(h2, d_up, G.dwu, H, F));
     void* dh2 = w.bufHb;
     {   // dh2 = d_gate*Wg^T + d_up*Wu^T   [N,H], contraction over F twice
         GemmSeg s[2] = {{d_gate, W.wg, F}, {d_up, W.wu, F}};
-        CF_HIP(launch_gemm(dt, 0, s, 2, dh2, N, H, 0.f, st));
+        CF_HIP(launch_gemm(dt, 0, s, 2, dh2, N, H, 0.f, st, 1.f, nullptr, 0, false, nd));
     }
     // dr = dy + rmsnorm_bwd(dh2; r, g2);  dg2
-    CF_HIP(launch_rmsnorm_bwd(dt, dh2, sv.r, W.g2, idx, dy_rows, N, H, L.rms_eps, w.dr, w.dg_partial,
+    CF_HIP(launch_rmsnorm_bwd(dt, dh2, sv.r, W.g2, idx, dy_rows, rows, H, L.rms_eps, w.dr, w.dg_partial,
                               G.dg2, st, mg));
 
     // ---- attention block: r = x + attn_out*Wo ------------------------------------
-    CF_HIP(dw_gemm(a_rows, w.dr, G.dwo, Nq, H));          // dWo = a^T * dr      [Nq,H]
     {
         GemmSeg s2{w.dr, W.wo, H};                        // da = dr * Wo^T      [N,Nq]
-        CF_HIP(launch_gemm(dt, 0, &s2, 1, w.da, N, Nq, 0.f, st));
+        CF_HIP(launch_gemm(dt, 0, &s2, 1, w.da, N, Nq, 0.f, st, 1.f, nullptr, 0, false, nd));
     }
-    cf_status as = attn_dispatch(L, q_rows, sv.k, sv.v, a_rows, sv.lse, w.da, idx, cu_kept, N, w.dq,
-                                 w.dk, w.dv, w.attn_ws, st);
+    // the attention backward's row-statistics pass reads attn_out and q through idx and leaves their
+    // compact copies in w.a_k, w.q_k (no gather kernel)
+    const void* a_rows = idx ? w.a_k : sv.attn_out;
+    const void* q_rows = idx ? w.q_k : sv.q;
+    cf_status as = attn_dispatch(L, q_rows, sv.k, sv.v, a_rows, sv.lse, w.da, idx, cu_kept, rows, w.dq,
+                                 w.dk, w.dv, w.attn_ws, st, idx ? sv.attn_out : nullptr, idx ? sv.q : nullptr);
     if (as != CF_OK) return as;
+    CF_HIP(dw_gemm(a_rows, w.dr, G.dwo, Nq, H));          // dWo = a^T * dr      [Nq,H]
 
     if (sv.rope_cos) {      // transposed rotation of dq and dk at the original positions of the kept rows
-        CF_HIP(launch_rope_bwd(dt, w.dq, idx, N, L.Hq, L.d, L.S, sv.rope_cos, sv.rope_sin, st));
-        CF_HIP(launch_rope_bwd(dt, w.dk, idx, N, L.Hkv, L.d, L.S, sv.rope_cos, sv.rope_sin, st));
+        CF_HIP(launch_rope_bwd(dt, w.dq, idx, rows, L.Hq, L.d, L.S, sv.rope_cos, sv.rope_sin, st));
+        CF_HIP(launch_rope_bwd(dt, w.dk, idx, rows, L.Hkv, L.d, L.S, sv.rope_cos, sv.rope_sin, st));
     }
     void* h1 = w.bufHa;
-    CF_HIP(launch_rmsnorm_fwd(dt, sv.x, W.g1, idx, N, H, L.rms_eps, h1, st));
+    CF_HIP(launch_rmsnorm_fwd(dt, sv.x, W.g1, idx, rows, H, L.rms_eps, h1, st));
     {   // dWq, dWk, dWv = h1^T * dq, dk, dv: one launch when the column groups fall on tile boundaries
         const int Ng[3] = {Nq, Nkv, Nkv};
-        if (N > 0 && gemm_tn_groups_supported(dt, N, 3, Ng)) {
+        if (gemm_tn_groups_supported(dt, N, 3, Ng)) {
             const void* Bg[3] = {w.dq, w.dk, w.dv};
             void* Cg[3] = {G.dwq, G.dwk, G.dwv};
-            CF_HIP(launch_gemm_tn_groups(h1, N, H, 3, Bg, Cg, Ng, st, mg ? 1.f : 0.f, mg));
+            CF_HIP(launch_gemm_tn_groups(h1, N, H, 3, Bg, Cg, Ng, st, mg ? 1.f : 0.f, mg, nd));
         } else {
             CF_HIP(dw_gemm(h1, w.dq, G.dwq, H, Nq));
             CF_HIP(dw_gemm(h1, w.dk, G.dwk, H, Nkv));
@@ -250,10 +267,10 @@ cf_status layer_core(const cf_layer_desc& L, const cf_saved& sv, const cf_weight
     void* dh1 = w.bufHb;
     {   // dh1 = dq*Wq^T + dk*Wk^T + dv*Wv^T
         GemmSeg s[3] = {{w.dq, W.wq, Nq}, {w.dk, W.wk, Nkv}, {w.dv, W.wv, Nkv}};
-        CF_HIP(launch_gemm(dt, 0, s, 3, dh1, N, H, 0.f, st));
+        CF_HIP(launch_gemm(dt, 0, s, 3, dh1, N, H, 0.f, st, 1.f, nullptr, 0, false, nd));
     }
     // dx = dr + rmsnorm_bwd(dh1; x, g1);  dg1
-    CF_HIP(launch_rmsnorm_bwd(dt, dh1, sv.x, W.g1, idx, w.dr, N, H, L.rms_eps, G.dx, w.dg_partial,
+    CF_HIP(launch_rmsnorm_bwd(dt, dh1, sv.x, W.g1, idx, w.dr, rows, H, L.rms_eps, G.dx, w.dg_partial,
                               G.dg1, st, mg));
     return CF_OK;
 }
@@ -326,6 +343,7 @@ cf_status layer_core_lora(const cf_layer_desc& L, const cf_saved& sv, const cf_w
     const int dt = L.dtype;
     const size_t e = dtype_size(dt);
     const int H = L.H, F = L.F, Nq = L.Hq * L.d, Nkv = L.Hkv * L.d, R = A.rank;
+    const RowCount rows{N, nullptr};        // this entry point reads the count back before it launches
     if (N == 0) {
         void* outs[8] = {G.daq, G.dbq, G.dak, G.dbk, G.dav, G.dbv, G.dao, G.dbo};
         size_t sz[8] = {(size_t)H * R, (size_t)R * Nq, (size_t)H * R, (size_t)R * Nkv,
@@ -336,8 +354,8 @@ cf_status layer_core_lora(const cf_layer_desc& L, const cf_saved& sv, const cf_w
     const void* a_rows = sv.attn_out;
     const void* q_rows = sv.q;
     if (idx) {
-        CF_HIP(launch_gather(sv.attn_out, (int64_t)Nq * e, idx, N, w.a_k, st));
-        CF_HIP(launch_gather(sv.q, (int64_t)Nq * e, idx, N, w.q_k, st));
+        CF_HIP(launch_gather(sv.attn_out, (int64_t)Nq * e, idx, rows, w.a_k, st));
+        CF_HIP(launch_gather(sv.q, (int64_t)Nq * e, idx, rows, w.q_k, st));
         a_rows = w.a_k;
         q_rows = w.q_k;
     }
@@ -349,13 +367,13 @@ cf_status layer_core_lora(const cf_layer_desc& L, const cf_saved& sv, const cf_w
     }
     void* d_gate = w.bufF1;
     void* d_up = w.bufF0;
-    CF_HIP(launch_swiglu_bwd(dt, d_act, sv.gate, sv.up, idx, N, F, d_gate, d_up, nullptr, st));
+    CF_HIP(launch_swiglu_bwd(dt, d_act, sv.gate, sv.up, idx, rows, F, d_gate, d_up, nullptr, st));
     void* dh2 = w.bufHb;
     {
         GemmSeg s[2] = {{d_gate, W.wg, F}, {d_up, W.wu, F}};
         CF_HIP(launch_gemm(dt, 0, s, 2, dh2, N, H, 0.f, st));
     }
-    CF_HIP(launch_rmsnorm_bwd(dt, dh2, sv.r, W.g2, idx, dy_rows, N, H, L.rms_eps, w.dr, w.dg_partial,
+    CF_HIP(launch_rmsnorm_bwd(dt, dh2, sv.r, W.g2, idx, dy_rows, rows, H, L.rms_eps, w.dr, w.dg_partial,
                               lw.dg_scratch, st));
     // ---- adapted O projection: input a [N,Nq], output gradient dr [N,H]
     cf_status ps = lora_proj(dt, a_rows, w.dr, A.ao, A.bo, N, Nq, H, R, A.scale, lw.to, G.dao, G.dbo, lw, st);
@@ -364,16 +382,16 @@ cf_status layer_core_lora(const cf_layer_desc& L, const cf_saved& sv, const cf_w
         GemmSeg s[2] = {{w.dr, W.wo, H}, {lw.to, A.ao, R}};
         CF_HIP(launch_gemm(dt, 0, s, 2, w.da, N, Nq, 0.f, st));
     }
-    cf_status as = attn_dispatch(L, q_rows, sv.k, sv.v, a_rows, sv.lse, w.da, idx, cu_kept, N, w.dq,
+    cf_status as = attn_dispatch(L, q_rows, sv.k, sv.v, a_rows, sv.lse, w.da, idx, cu_kept, rows, w.dq,
                                  w.dk, w.dv, w.attn_ws, st);
     if (as != CF_OK) return as;
     if (sv.rope_cos) {
-        CF_HIP(launch_rope_bwd(dt, w.dq, idx, N, L.Hq, L.d, L.S, sv.rope_cos, sv.rope_sin, st));
-        CF_HIP(launch_rope_bwd(dt, w.dk, idx, N, L.Hkv, L.d, L.S, sv.rope_cos, sv.rope_sin, st));
+        CF_HIP(launch_rope_bwd(dt, w.dq, idx, rows, L.Hq, L.d, L.S, sv.rope_cos, sv.rope_sin, st));
+        CF_HIP(launch_rope_bwd(dt, w.dk, idx, rows, L.Hkv, L.d, L.S, sv.rope_cos, sv.rope_sin, st));
     }
     // ---- adapted Q, K, V projections: input h1 [N,H]
     void* h1 = w.bufHa;
-    CF_HIP(launch_rmsnorm_fwd(dt, sv.x, W.g1, idx, N, H, L.rms_eps, h1, st));
+    CF_HIP(launch_rmsnorm_fwd(dt, sv.x, W.g1, idx, rows, H, L.rms_eps, h1, st));
     ps = lora_proj(dt, h1, w.dq, A.aq, A.bq, N, H, Nq, R, A.scale, lw.tq, G.daq, G.dbq, lw, st);
     if (ps != CF_OK) return ps;
     ps = lora_proj(dt, h1, w.dk, A.ak, A.bk, N, H, Nkv, R, A.scale, lw.tk, G.dak, G.dbk, lw, st);
@@ -387,7 +405,7 @@ cf_status layer_core_lora(const cf_layer_desc& L, const cf_saved& sv, const cf_w
         GemmSeg s2[3] = {{lw.tq, A.aq, R}, {lw.tk, A.ak, R}, {lw.tv, A.av, R}};
         CF_HIP(launch_gemm(dt, 0, s2, 3, dh1, N, H, 1.f, st));
     }
-    CF_HIP(launch_rmsnorm_bwd(dt, dh1, sv.x, W.g1, idx, w.dr, N, H, L.rms_eps, G.dx, w.dg_partial,
+    CF_HIP(launch_rmsnorm_bwd(dt, dh1, sv.x, W.g1, idx, w.dr, rows, H, L.rms_eps, G.dx, w.dg_partial,
                               lw.dg_scratch, st));
     return CF_OK;
 }
@@ -467,16 +485,18 @@ cf_status cf_build_keep_index_static(const uint8_t* mask, int32_t B, int32_t S, 
 }
 
 cf_status cf_gather_rows(const void* src, int64_t src_rows, int64_t cols, int32_t dtype,
-                         const int32_t* idx, int32_t n_rows, void* dst, cf_stream stream) {
+                         const int32_t* idx, const int32_t* n_kept_dev, int32_t max_kept, void* dst,
+                         cf_stream stream) {
     if (!src || !idx || !dst) return CF_ERR_NULL;
     cf_status s = check_dtype(dtype);
     if (s != CF_OK) return s;
-    if (src_rows <= 0 || cols <= 0 || n_rows < 0) return CF_ERR_SHAPE;
+    if (src_rows <= 0 || cols <= 0 || max_kept < 0) return CF_ERR_SHAPE;
     const int64_t row_bytes = cols * (int64_t)dtype_size(dtype);
-    if (row_bytes % 4 != 0 || misaligned(src, 4) || misaligned(dst, 4) || misaligned(idx, 4))
+    if (row_bytes % 4 != 0 || misaligned(src, 4) || misaligned(dst, 4) || misaligned(idx, 4) ||
+        (n_kept_dev && misaligned(n_kept_dev, 4)))
         return CF_ERR_SHAPE;
     if (row_bytes / 4 > INT32_MAX) return CF_ERR_SHAPE;
-    CF_HIP(launch_gather(src, row_bytes, idx, n_rows, dst, as_stream(stream)));
+    CF_HIP(launch_gather(src, row_bytes, idx, RowCount{max_kept, n_kept_dev}, dst, as_stream(stream)));
     return CF_OK;
 }
 
@@ -537,7 +557,7 @@ cf_status cf_attn_bwd_filtered(const cf_layer_desc* desc, const void* q_kept, co
     if (!ws || misaligned(ws, 256) || ws_bytes < cf_attn_workspace_bytes(desc, n_kept))
         return CF_ERR_WORKSPACE;
     return attn_dispatch(*desc, q_kept, k_full, v_full, o_kept, lse_full, do_kept, idx, cu_kept,
-                         n_kept, dq_kept, dk_kept, dv_kept, ws, as_stream(stream));
+                         RowCount{n_kept, nullptr}, dq_kept, dk_kept, dv_kept, ws, as_stream(stream));
 }
 
 size_t cf_layer_workspace_bytes(const cf_layer_desc* desc, int32_t max_kept) {
@@ -546,37 +566,34 @@ size_t cf_layer_workspace_bytes(const cf_layer_desc* desc, int32_t max_kept) {
 }
 
 cf_status cf_layer_bwd_filtered(const cf_layer_desc* desc, const cf_saved* saved, const cf_weights* w,
-                                const void* dy_full, const uint8_t* mask, cf_grads* grads,
-                                int32_t* idx_out, int32_t* cu_kept_out, int32_t* n_kept_host, void* ws,
-                                size_t ws_bytes, cf_stream stream) {
+                                const void* dy_full, const uint8_t* mask, int32_t max_kept, cf_grads* grads,
+                                int32_t* idx_out, int32_t* cu_kept_out, int32_t* n_kept_dev_out,
+                                int32_t* n_kept_host, void* ws, size_t ws_bytes, cf_stream stream) {
     cf_status s = check_layer_desc(desc);
     if (s != CF_OK) return s;
     s = check_layer_ptrs(saved, w, dy_full, grads);
     if (s != CF_OK) return s;
     s = check_rope(desc, saved);
     if (s != CF_OK) return s;
-    if (!mask || !n_kept_host) return CF_ERR_NULL;
-    if ((idx_out && misaligned(idx_out, 4)) || (cu_kept_out && misaligned(cu_kept_out, 4)))
+    if (!mask) return CF_ERR_NULL;
+    if ((idx_out && misaligned(idx_out, 4)) || (cu_kept_out && misaligned(cu_kept_out, 4)) ||
+        (n_kept_dev_out && misaligned(n_kept_dev_out, 4)))
         return CF_ERR_SHAPE;
     const int T = desc->B * desc->S;
+    if (max_kept < 0) return CF_ERR_SHAPE;
+    if (max_kept == 0 || max_kept > T) max_kept = T;
     if (!ws || misaligned(ws, 256)) return CF_ERR_WORKSPACE;
-    // the kept count is not known yet: the workspace must at least hold the index part,
-    // and after the count is known it must hold the layout for that count
-    LayerWs w0 = carve_layer(*desc, 0, ws);
-    if (ws_bytes < w0.total) return CF_ERR_WORKSPACE;
-    hipStream_t st = as_stream(stream);
-    int32_t* idx = idx_out ? idx_out : w0.idx;
-    int32_t* cu = cu_kept_out ? cu_kept_out : w0.cu_kept;
-    CF_HIP(launch_keep_index(mask, desc->B, desc->S, idx, cu, w0.n_kept_dev, w0.index_ws, st));
-    CF_HIP(hipMemcpyAsync(n_kept_host, w0.n_kept_dev, sizeof(int32_t), hipMemcpyDeviceToHost, st));
-    CF_HIP(hipStreamSynchronize(st));
-    const int N = *n_kept_host;
-    if (N < 0 || N > T) return CF_ERR_HIP;
-    LayerWs wk = carve_layer(*desc, N, ws);
+    LayerWs wk = carve_layer(*desc, max_kept, ws);
     if (ws_bytes < wk.total) return CF_ERR_WORKSPACE;
-    if (N > 0)
-        CF_HIP(launch_gather(dy_full, (int64_t)desc->H * dtype_size(desc->dtype), idx, N, wk.dy_k, st));
-    return layer_core(*desc, *saved, *w, wk.dy_k, idx, cu, N, *grads, wk, st);
+    hipStream_t st = as_stream(stream);
+    int32_t* idx = idx_out ? idx_out : wk.idx;
+    int32_t* cu = cu_kept_out ? cu_kept_out : wk.cu_kept;
+    int32_t* n_dev = n_kept_dev_out ? n_kept_dev_out : wk.n_kept_dev;
+    CF_HIP(launch_keep_index(mask, desc->B, desc->S, idx, cu, n_dev, wk.index_ws, st));
+    // the count stays on the device: every later kernel reads it there, nothing waits for the host
+    if (n_kept_host)
+        CF_HIP(hipMemcpyAsync(n_kept_host, n_dev, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    return layer_core(*desc, *saved, *w, dy_full, true, idx, cu, RowCount{max_kept, n_dev}, *grads, wk, st);
 }
 
 cf_status cf_layer_bwd_compact(const cf_layer_desc* desc, const cf_saved* saved, const cf_weights* w,
@@ -596,7 +613,30 @@ cf_status cf_layer_bwd_compact(const cf_layer_desc* desc, const cf_saved* saved,
     if (!ws || misaligned(ws, 256)) return CF_ERR_WORKSPACE;
     LayerWs wk = carve_layer(*desc, n_kept, ws);
     if (ws_bytes < wk.total) return CF_ERR_WORKSPACE;
-    return layer_core(*desc, *saved, *w, dy_kept, idx, cu_kept, n_kept, *grads, wk, as_stream(stream));
+    return layer_core(*desc, *saved, *w, dy_kept, false, idx, cu_kept, RowCount{n_kept, nullptr}, *grads, wk,
+                      as_stream(stream));
+}
+
+cf_status cf_layer_bwd_compact_dev(const cf_layer_desc* desc, const cf_saved* saved, const cf_weights* w,
+                                   const void* dy_kept, const int32_t* idx, const int32_t* cu_kept,
+                                   const int32_t* n_kept_dev, int32_t max_kept, cf_grads* grads, void* ws,
+                                   size_t ws_bytes, cf_stream stream) {
+    cf_status s = check_layer_desc(desc);
+    if (s != CF_OK) return s;
+    s = check_layer_ptrs(saved, w, dy_kept, grads);
+    if (s != CF_OK) return s;
+    s = check_rope(desc, saved);
+    if (s != CF_OK) return s;
+    if (!idx || !cu_kept || !n_kept_dev) return CF_ERR_NULL;
+    if (misaligned(idx, 4) || misaligned(cu_kept, 4) || misaligned(n_kept_dev, 4)) return CF_ERR_SHAPE;
+    const int T = desc->B * desc->S;
+    if (max_kept < 0) return CF_ERR_SHAPE;
+    if (max_kept == 0 || max_kept > T) max_kept = T;
+    if (!ws || misaligned(ws, 256)) return CF_ERR_WORKSPACE;
+    LayerWs wk = carve_layer(*desc, max_kept, ws);
+    if (ws_bytes < wk.total) return CF_ERR_WORKSPACE;
+    return layer_core(*desc, *saved, *w, dy_kept, false, idx, cu_kept, RowCount{max_kept, n_kept_dev}, *grads,
+                      wk, as_stream(stream));
 }
 
 cf_status cf_layer_bwd_dense(const cf_layer_desc* desc, const cf_saved* saved, const cf_weights* w,
@@ -612,7 +652,8 @@ cf_status cf_layer_bwd_dense(const cf_layer_desc* desc, const cf_saved* saved, c
     if (!ws || misaligned(ws, 256)) return CF_ERR_WORKSPACE;
     LayerWs wk = carve_layer(*desc, T, ws);
     if (ws_bytes < wk.total) return CF_ERR_WORKSPACE;
-    return layer_core(*desc, *saved, *w, dy_full, nullptr, nullptr, T, *grads, wk, as_stream(stream));
+    return layer_core(*desc, *saved, *w, dy_full, false, nullptr, nullptr, RowCount{T, nullptr}, *grads, wk,
+                      as_stream(stream));
 }
 
 size_t cf_lora_workspace_bytes(const cf_layer_desc* desc, int32_t rank, int32_t max_kept) {
@@ -667,7 +708,8 @@ cf_status cf_layer_bwd_lora(const cf_layer_desc* desc, const cf_saved* saved, co
     LoraWs lw = carve_lora(*desc, lora->rank, N, ws);
     if (ws_bytes < lw.total) return CF_ERR_WORKSPACE;
     if (N > 0)
-        CF_HIP(launch_gather(dy_full, (int64_t)desc->H * dtype_size(desc->dtype), idx, N, lw.base.dy_k, st));
+        CF_HIP(launch_gather(dy_full, (int64_t)desc->H * dtype_size(desc->dtype), idx, RowCount{N, nullptr},
+                             lw.base.dy_k, st));
     return layer_core_lora(*desc, *saved, *w, *lora, lw.base.dy_k, idx, cu, N, *grads, lw, st);
 }
 

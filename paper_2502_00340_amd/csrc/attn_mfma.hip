@@ -50,9 +50,24 @@ struct AttnParams {
     const int32_t *idx, *cu_kept;
     bf16_t *dq_kept, *dk_kept, *dv_kept;
     float *dk_part, *dv_part;      // [G][n_kept][Hkv*d] fp32 per-query-head partials (G > 1 only)
-    int B, S, Hq, Hkv, n_kept;
+    int B, S, Hq, Hkv;
+    int n_kept;                    // rows that the compact buffers are laid out for (the stride of stat and of the partials)
+    const int32_t* n_dev;          // nullable: the live row count on the device, at most n_kept
     float scale;
 };
+
+// Compact rows [begin, end) of sequence b.  The prefix counts are clamped to the live row count, so a
+// mask that keeps more tokens than the buffers were sized for cannot send a block past their end.
+__device__ __forceinline__ void seq_range(const AttnParams& p, int b, int& begin, int& end) {
+    if (p.cu_kept == nullptr) {
+        begin = b * p.S;
+        end = (b + 1) * p.S;
+        return;
+    }
+    const int n = live_rows(p.n_kept, p.n_dev);
+    begin = min(p.cu_kept[b], n);
+    end = min(p.cu_kept[b + 1], n);
+}
 
 // 16-byte chunk swizzle of a [rows][D] bf16 tile: makes both the row-fragment
 // reads (16 consecutive rows, same chunk) and the transpose reads (4 rows x 4
@@ -141,8 +156,8 @@ __global__ __launch_bounds__(256, 2) void attn_dq_kernel(AttnParams p) {
     const int slot = lane & 31, hh = lane >> 5;
     const int h = blockIdx.x % p.Hq, b = blockIdx.x / p.Hq, g = h / (p.Hq / p.Hkv);
     const int Nq = p.Hq * D, Nkv = p.Hkv * D;
-    const int seq_begin = p.cu_kept ? p.cu_kept[b] : b * p.S;
-    const int seq_end = p.cu_kept ? p.cu_kept[b + 1] : (b + 1) * p.S;
+    int seq_begin, seq_end;
+    seq_range(p, b, seq_begin, seq_end);
     const int cnt = seq_end - seq_begin;
     const int qt = gridDim.y - 1 - blockIdx.y;        // heaviest (latest) query tiles first
     if (qt * 128 >= cnt) return;
@@ -280,8 +295,8 @@ __global__ __launch_bounds__(256, 1) void attn_dkv_kernel(AttnParams p) {
     const int G = p.Hq / p.Hkv;
     const int h = blockIdx.x % p.Hq, b = blockIdx.x / p.Hq, g = h / G;
     const int Nq = p.Hq * D, Nkv = p.Hkv * D;
-    const int seq_begin = p.cu_kept ? p.cu_kept[b] : b * p.S;
-    const int seq_end = p.cu_kept ? p.cu_kept[b + 1] : (b + 1) * p.S;
+    int seq_begin, seq_end;
+    seq_range(p, b, seq_begin, seq_end);
     const int cnt = seq_end - seq_begin;
     const int kt = blockIdx.y;                      // early key tiles see the most queries: heaviest first
     if (kt * 128 >= cnt) return;
@@ -537,10 +552,12 @@ __global__ __launch_bounds__(256, 1) void attn_dkv_kernel(AttnParams p) {
 // dk = scale * sum_g dk_part[g], dv = sum_g dv_part[g]   (fixed order: deterministic)
 __global__ __launch_bounds__(256) void attn_dkv_reduce_kernel(const float* __restrict__ dk_part,
                                                               const float* __restrict__ dv_part, int G,
-                                                              int64_t n_elems, float scale,
+                                                              int n_max, const int32_t* __restrict__ n_dev, int Nkv,
+                                                              float scale,
                                                               bf16_t* __restrict__ dk, bf16_t* __restrict__ dv) {
+    const int64_t n_elems = (int64_t)n_max * Nkv;                       // stride between two heads' partials
     const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
-    if (i >= n_elems) return;
+    if (i >= (int64_t)live_rows(n_max, n_dev) * Nkv) return;
     float sk[8], sv[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) { sk[e] = 0.f; sv[e] = 0.f; }
@@ -562,11 +579,19 @@ __global__ __launch_bounds__(256) void attn_dkv_reduce_kernel(const float* __res
 // stat[0][h][j] = log2(e) * LSE(b, h, position of kept row j); stat[1][h][j] = D = sum_c dO*O of
 // (row j, head h): the row terms of the FlashAttention backward, laid out so that the 64 rows a
 // dK/dV block needs per step are contiguous.  d/8 lanes share one (row, head).
+// o_full / q_full (nullable, need idx): the attention output and the queries are still stored full
+// length; the pass reads their kept rows through idx and writes the compact copies o_out / q_out
+// that the parameter-gradient GEMM of the output projection and the attention kernels' tile loads
+// use (the gathers of the two tensors folded into this read).
 __global__ __launch_bounds__(256) void attn_stats_kernel(const bf16_t* __restrict__ do_kept,
-                                                         const bf16_t* __restrict__ o_kept,
+                                                         const bf16_t* __restrict__ o_rows,
                                                          const float* __restrict__ lse_full,
-                                                         const int32_t* __restrict__ idx, int n_kept,
-                                                         int Hq, int d, int S, float* __restrict__ stat) {
+                                                         const int32_t* __restrict__ idx, int n_max,
+                                                         const int32_t* __restrict__ n_dev,
+                                                         int Hq, int d, int S, float* __restrict__ stat,
+                                                         const bf16_t* __restrict__ o_full, bf16_t* __restrict__ o_out,
+                                                         const bf16_t* __restrict__ q_full, bf16_t* __restrict__ q_out) {
+    const int n_kept = live_rows(n_max, n_dev);
     const int lanes = d / 8;
     const int64_t total = (int64_t)n_kept * Hq * lanes;
     const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -576,7 +601,21 @@ __global__ __launch_bounds__(256) void attn_stats_kernel(const bf16_t* __restric
         const int part = (int)(gid % lanes);
         float a[8], b[8];
         Vec<bf16_t>::load(do_kept + pair * d + part * 8, a);
-        Vec<bf16_t>::load(o_kept + pair * d + part * 8, b);
+        if (o_full != nullptr) {
+            const int64_t src = ((int64_t)idx[pair / Hq] * Hq + pair % Hq) * d + part * 8;
+            const uint4 ov = *reinterpret_cast<const uint4*>(o_full + src);
+            *reinterpret_cast<uint4*>(o_out + pair * d + part * 8) = ov;
+            if (q_full != nullptr)
+                *reinterpret_cast<uint4*>(q_out + pair * d + part * 8) = *reinterpret_cast<const uint4*>(q_full + src);
+            const unsigned w[4] = {ov.x, ov.y, ov.z, ov.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                b[2 * i] = __uint_as_float(w[i] << 16);
+                b[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+            }
+        } else {
+            Vec<bf16_t>::load(o_rows + pair * d + part * 8, b);
+        }
 #pragma unroll
         for (int e = 0; e < 8; ++e) s += a[e] * b[e];
     }
@@ -585,8 +624,8 @@ __global__ __launch_bounds__(256) void attn_stats_kernel(const bf16_t* __restric
         const int j = (int)(pair / Hq), h = (int)(pair % Hq);
         const int64_t tok = idx ? idx[j] : j;
         const int64_t bb = tok / S, pos = tok - bb * S;
-        stat[(int64_t)h * n_kept + j] = lse_full[(bb * Hq + h) * S + pos] * LOG2E;
-        stat[(int64_t)(Hq + h) * n_kept + j] = s;
+        stat[(int64_t)h * n_max + j] = lse_full[(bb * Hq + h) * S + pos] * LOG2E;
+        stat[(int64_t)(Hq + h) * n_max + j] = s;
     }
 }
 
@@ -601,8 +640,8 @@ size_t attn_mfma_partial_bytes(const cf_layer_desc& L, int n_kept) {
 }
 
 template <int D>
-static hipError_t launch_t(const AttnParams& p, const bf16_t* o_kept, const float* lse_full, float* stat,
-                           int n_kept, hipStream_t st) {
+static hipError_t launch_t(const AttnParams& p, const bf16_t* o_rows, const float* lse_full, float* stat,
+                           const bf16_t* o_full, bf16_t* o_out, const bf16_t* q_full, bf16_t* q_out, hipStream_t st) {
     constexpr int smem_dq = 2 * 2 * 64 * D * 2;
     constexpr int smem_dkv = 4 * (2 * 64 * D * 2 + 512);
     static std::atomic<uint64_t> lds_ok_dq{0}, lds_ok_dkv{0};
@@ -610,10 +649,12 @@ static hipError_t launch_t(const AttnParams& p, const bf16_t* o_kept, const floa
     if (e != hipSuccess) return e;
     e = allow_dynamic_lds(reinterpret_cast<const void*>(&attn_dkv_kernel<D>), smem_dkv, lds_ok_dkv);
     if (e != hipSuccess) return e;
+    const int n_kept = p.n_kept;        // grids cover the upper bound of the row count
     {
         const int64_t total = (int64_t)n_kept * p.Hq * (D / 8);
-        attn_stats_kernel<<<(int)((total + 255) / 256), 256, 0, st>>>(p.do_kept, o_kept, lse_full, p.idx, n_kept,
-                                                                     p.Hq, D, p.S, stat);
+        attn_stats_kernel<<<(int)((total + 255) / 256), 256, 0, st>>>(p.do_kept, o_rows, lse_full, p.idx, n_kept,
+                                                                     p.n_dev, p.Hq, D, p.S, stat, o_full, o_out,
+                                                                     q_full, q_out);
     }
     const int max_per_seq = n_kept < p.S ? n_kept : p.S;
     const int tiles = ceil_div(max_per_seq, 128);
@@ -622,26 +663,37 @@ static hipError_t launch_t(const AttnParams& p, const bf16_t* o_kept, const floa
     if (p.Hq != p.Hkv) {
         const int64_t n_elems = (int64_t)n_kept * p.Hkv * D;
         attn_dkv_reduce_kernel<<<ceil_div(n_elems / 8, 256), 256, 0, st>>>(p.dk_part, p.dv_part, p.Hq / p.Hkv,
-                                                                          n_elems, p.scale, p.dk_kept, p.dv_kept);
+                                                                          n_kept, p.n_dev, p.Hkv * D, p.scale,
+                                                                          p.dk_kept, p.dv_kept);
     }
     return hipGetLastError();
 }
 
+// o_full / q_full (both nullable, need idx): attention output and queries at full length; their kept
+// rows are then copied to o_kept / q_kept (which must be writable buffers) by the row-statistics pass.
 hipError_t launch_attn_bwd_mfma(const cf_layer_desc& L, float scale, const void* q_kept,
                                 const void* k_full, const void* v_full, const void* o_kept,
                                 const float* lse_full, const void* do_kept, float* stat,
-                                const int32_t* idx, const int32_t* cu_kept, int n_kept, void* dq_kept,
-                                void* dk_kept, void* dv_kept, float* partials, hipStream_t st) {
+                                const int32_t* idx, const int32_t* cu_kept, RowCount rows, void* dq_kept,
+                                void* dk_kept, void* dv_kept, float* partials, hipStream_t st,
+                                const void* o_full, const void* q_full) {
     AttnParams p;
+    const int n_kept = rows.n;
     p.q_kept = (const bf16_t*)q_kept; p.k_full = (const bf16_t*)k_full; p.v_full = (const bf16_t*)v_full;
     p.do_kept = (const bf16_t*)do_kept; p.stat = stat; p.idx = idx;
     p.cu_kept = cu_kept; p.dq_kept = (bf16_t*)dq_kept; p.dk_kept = (bf16_t*)dk_kept;
     p.dv_kept = (bf16_t*)dv_kept; p.B = L.B; p.S = L.S; p.Hq = L.Hq; p.Hkv = L.Hkv; p.scale = scale;
     p.n_kept = n_kept;
+    p.n_dev = rows.dev;
     p.dk_part = partials;
     p.dv_part = partials ? partials + (size_t)n_kept * L.Hq * L.d : nullptr;
-    if (L.d == 64) return launch_t<64>(p, (const bf16_t*)o_kept, lse_full, stat, n_kept, st);
-    return launch_t<128>(p, (const bf16_t*)o_kept, lse_full, stat, n_kept, st);
+    bf16_t* o_out = o_full ? (bf16_t*)const_cast<void*>(o_kept) : nullptr;
+    bf16_t* q_out = q_full ? (bf16_t*)const_cast<void*>(q_kept) : nullptr;
+    if (L.d == 64)
+        return launch_t<64>(p, (const bf16_t*)o_kept, lse_full, stat, (const bf16_t*)o_full, o_out,
+                            (const bf16_t*)q_full, q_out, st);
+    return launch_t<128>(p, (const bf16_t*)o_kept, lse_full, stat, (const bf16_t*)o_full, o_out,
+                         (const bf16_t*)q_full, q_out, st);
 }
 
 }  // namespace cf

@@ -25,9 +25,10 @@ __global__ __launch_bounds__(256) void attn_dq_ref_kernel(
     const T* __restrict__ q_kept, const T* __restrict__ k_full, const T* __restrict__ v_full,
     const float* __restrict__ lse_full, const T* __restrict__ do_kept, const float* __restrict__ Drow,
     const int32_t* __restrict__ idx, const int32_t* __restrict__ cu_kept, int B, int S, int Hq,
-    int Hkv, int d, float scale, T* __restrict__ dq_kept) {
+    int Hkv, int d, float scale, int n_max, const int32_t* __restrict__ n_dev, T* __restrict__ dq_kept) {
     __shared__ float qs[256], dos[256], dss[256], red[256];
     const int j = blockIdx.x, h = blockIdx.y, g = h / (Hq / Hkv);
+    if (j >= live_rows(n_max, n_dev)) return;
     const int tid = threadIdx.x;
     const int b = seq_of_row(cu_kept, B, S, j);
     const int row = idx ? idx[j] : j;
@@ -79,13 +80,16 @@ __global__ __launch_bounds__(256) void attn_dkv_ref_kernel(
     const T* __restrict__ q_kept, const T* __restrict__ k_full, const T* __restrict__ v_full,
     const float* __restrict__ lse_full, const T* __restrict__ do_kept, const float* __restrict__ Drow,
     const int32_t* __restrict__ idx, const int32_t* __restrict__ cu_kept, int B, int S, int Hq,
-    int Hkv, int d, float scale, int n_kept, T* __restrict__ dk_kept, T* __restrict__ dv_kept) {
+    int Hkv, int d, float scale, int n_max, const int32_t* __restrict__ n_dev, T* __restrict__ dk_kept,
+    T* __restrict__ dv_kept) {
     __shared__ float ks[256], vs[256], ps[256], dss[256], redk[256], redv[256];
     const int j = blockIdx.x, g = blockIdx.y, G = Hq / Hkv;
     const int tid = threadIdx.x;
+    const int n_live = live_rows(n_max, n_dev);
+    if (j >= n_live) return;
     const int b = seq_of_row(cu_kept, B, S, j);
     const int rowj = idx ? idx[j] : j;
-    const int end = cu_kept ? cu_kept[b + 1] : (b + 1) * S;   // kept rows of this sequence end here
+    const int end = cu_kept ? min(cu_kept[b + 1], n_live) : (b + 1) * S;   // kept rows of this sequence end here
     const int Nq = Hq * d, Nkv = Hkv * d;
     if (tid < d) {
         ks[tid] = to_f32<T>(k_full[(int64_t)rowj * Nkv + g * d + tid]);
@@ -140,27 +144,28 @@ template <typename T>
 static hipError_t launch_ref_t(const cf_layer_desc& L, float scale, const void* q_kept,
                                const void* k_full, const void* v_full, const float* lse_full,
                                const void* do_kept, const float* Drow, const int32_t* idx,
-                               const int32_t* cu_kept, int n_kept, void* dq_kept, void* dk_kept,
+                               const int32_t* cu_kept, RowCount rows, void* dq_kept, void* dk_kept,
                                void* dv_kept, hipStream_t st) {
+    const int n_kept = rows.n;      // grids cover the upper bound of the row count
     attn_dq_ref_kernel<T><<<dim3(n_kept, L.Hq), 256, 0, st>>>(
         (const T*)q_kept, (const T*)k_full, (const T*)v_full, lse_full, (const T*)do_kept, Drow, idx,
-        cu_kept, L.B, L.S, L.Hq, L.Hkv, L.d, scale, (T*)dq_kept);
+        cu_kept, L.B, L.S, L.Hq, L.Hkv, L.d, scale, n_kept, rows.dev, (T*)dq_kept);
     attn_dkv_ref_kernel<T><<<dim3(n_kept, L.Hkv), 256, 0, st>>>(
         (const T*)q_kept, (const T*)k_full, (const T*)v_full, lse_full, (const T*)do_kept, Drow, idx,
-        cu_kept, L.B, L.S, L.Hq, L.Hkv, L.d, scale, n_kept, (T*)dk_kept, (T*)dv_kept);
+        cu_kept, L.B, L.S, L.Hq, L.Hkv, L.d, scale, n_kept, rows.dev, (T*)dk_kept, (T*)dv_kept);
     return hipGetLastError();
 }
 
 hipError_t launch_attn_bwd_ref(const cf_layer_desc& L, float scale, const void* q_kept,
                                const void* k_full, const void* v_full, const float* lse_full,
                                const void* do_kept, const float* Drow, const int32_t* idx,
-                               const int32_t* cu_kept, int n_kept, void* dq_kept, void* dk_kept,
+                               const int32_t* cu_kept, RowCount rows, void* dq_kept, void* dk_kept,
                                void* dv_kept, hipStream_t st) {
     if (L.dtype == CF_F32)
         return launch_ref_t<float>(L, scale, q_kept, k_full, v_full, lse_full, do_kept, Drow, idx,
-                                   cu_kept, n_kept, dq_kept, dk_kept, dv_kept, st);
+                                   cu_kept, rows, dq_kept, dk_kept, dv_kept, st);
     return launch_ref_t<bf16_t>(L, scale, q_kept, k_full, v_full, lse_full, do_kept, Drow, idx,
-                                cu_kept, n_kept, dq_kept, dk_kept, dv_kept, st);
+                                cu_kept, rows, dq_kept, dk_kept, dv_kept, st);
 }
 
 }  // namespace cf

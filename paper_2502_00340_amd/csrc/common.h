@@ -98,6 +98,20 @@ static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; 
 static inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 static inline size_t dtype_size(int dtype) { return dtype == CF_F32 ? 4 : 2; }
 
+// Number of live rows of a launch (kept tokens).  dev == nullptr: exactly n, known to the host.
+// Otherwise the count lives on the device (the index build earlier on the same stream wrote it) and
+// n is only its upper bound: it sizes grids and buffer strides, and every kernel works on
+// min(*dev, n) rows, so no launch has to wait for the host to learn the count.
+struct RowCount {
+    int n;
+    const int32_t* dev;
+};
+__device__ __forceinline__ int live_rows(int n, const int32_t* dev) {
+    if (dev == nullptr) return n;
+    const int v = *dev;
+    return v < 0 ? 0 : (v < n ? v : n);
+}
+
 // ---- internal launchers (one per translation unit) --------------------------
 
 // index.hip
@@ -109,29 +123,35 @@ hipError_t launch_keep_index(const uint8_t* mask, int B, int S, int32_t* idx, in
 static constexpr int64_t IDX_STATIC_MAX_TOKENS = (int64_t)1 << 24;
 hipError_t launch_keep_index_static(const uint8_t* mask, int B, int S, int32_t* idx, int32_t* cu_kept,
                                     int32_t* n_kept_dev, hipStream_t st);
-hipError_t launch_gather(const void* src, int64_t cols_bytes, const int32_t* idx, int n_rows,
+hipError_t launch_gather(const void* src, int64_t cols_bytes, const int32_t* idx, RowCount rows,
                          void* dst, hipStream_t st);
 
 // rowlocal.hip
-// act (nullable) also receives silu(gate)*up; d_gate may alias d_act
+// act (nullable) also receives silu(gate)*up; d_gate may alias d_act.  copy_src (nullable, needs idx):
+// a full-length [.., copy_cols] tensor whose kept rows the same launch copies to copy_dst
+// [n_rows, copy_cols] (the compact upstream gradient that the parameter-gradient GEMM contracts over).
 hipError_t launch_swiglu_bwd(int dtype, const void* d_act, const void* gate, const void* up,
-                             const int32_t* idx, int n_rows, int F, void* d_gate, void* d_up,
-                             void* act, hipStream_t st);
+                             const int32_t* idx, RowCount rows, int F, void* d_gate, void* d_up,
+                             void* act, hipStream_t st, const void* copy_src = nullptr, int copy_cols = 0,
+                             void* copy_dst = nullptr);
 hipError_t launch_rmsnorm_fwd(int dtype, const void* x, const void* g, const int32_t* idx,
-                              int n_rows, int H, float eps, void* h, hipStream_t st);
+                              RowCount rows, int H, float eps, void* h, hipStream_t st);
 // dx_out = res + rmsnorm_bwd(dh; x, g); dg_partial is [rmsnorm_bwd_blocks(n_rows), H] fp32 scratch.
 // dg_acc_f32: dg_out is fp32 [H] and the gain gradient is added to it instead of written.
 int rmsnorm_bwd_blocks(int n_rows);
 hipError_t launch_rmsnorm_bwd(int dtype, const void* dh, const void* x, const void* g,
-                              const int32_t* idx, const void* res, int n_rows, int H, float eps,
+                              const int32_t* idx, const void* res, RowCount rows, int H, float eps,
                               void* dx_out, float* dg_partial, void* dg_out, hipStream_t st,
                               bool dg_acc_f32 = false);
 // g[j, h*d + i] (in place, [n_rows, heads*d]): transposed rotary rotation at position idx[j] % S
 // (idx null: j % S); cos, sin are [S, d/2] fp32
-hipError_t launch_rope_bwd(int dtype, void* g, const int32_t* idx, int n_rows, int heads, int d, int S,
+hipError_t launch_rope_bwd(int dtype, void* g, const int32_t* idx, RowCount rows, int heads, int d, int S,
                            const float* cos, const float* sin, hipStream_t st);
-hipError_t launch_attn_rowdot(int dtype, const void* da, const void* a, int n_rows, int Hq, int d,
-                              float* D, hipStream_t st);
+// D[j,h] = sum_c da[j,h*d+c] * a[row,h*d+c], row = a_idx ? a_idx[j] : j; with a_idx the same launch also
+// writes the compact copies a_out[j,:] = a[row,:] and (q_src non-null) q_out[j,:] = q_src[row,:]
+hipError_t launch_attn_rowdot(int dtype, const void* da, const void* a, RowCount rows, int Hq, int d,
+                              float* D, hipStream_t st, const int32_t* a_idx = nullptr, void* a_out = nullptr,
+                              const void* q_src = nullptr, void* q_out = nullptr);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st);
 // dst [cols, rows] = src [rows, cols]^T  (small matrices: the low-rank adapters)
 hipError_t launch_transpose(int dtype, const void* src, int rows, int cols, void* dst, hipStream_t st);
@@ -147,18 +167,23 @@ struct GemmSeg {
 //   mode 1 ("TN"): A_seg [K,M], B_seg [K,N]      (C = A^T * B)
 // c_f32 (bf16 dtype only): C is an fp32 matrix (a main-gradient buffer) and the accumulators are
 // added to beta*C without rounding to bf16.
+// n_dev (nullable): the kept-token count on the device; then the kept-token dimension of the product
+// (M in mode 0, the K of segment 0 in mode 1) is only an upper bound and the kernel uses
+// min(*n_dev, bound).  a_idx (nullable, mode 0, segment 0): row m of A is row a_idx[m] of a longer
+// matrix (the gather of the upstream gradient folded into the A-tile loads); a_rows = rows of that matrix.
 // splitk_ws (device, splitk_bytes, 16-byte aligned, may be null): scratch that lets a bf16 product
 // with one segment, few output tiles and a long K run as a split-K launch (fp32 parts summed in a
 // fixed order by a second kernel).
 hipError_t launch_gemm(int dtype, int mode, const GemmSeg* segs, int nseg, void* C, int M, int N,
                        float beta, hipStream_t st, float alpha = 1.0f, void* splitk_ws = nullptr,
-                       size_t splitk_bytes = 0, bool c_f32 = false);
+                       size_t splitk_bytes = 0, bool c_f32 = false, const int32_t* n_dev = nullptr,
+                       const int32_t* a_idx = nullptr, int64_t a_rows = 0);
 
 // One TN launch for up to three products that share A [K,M]: C_j [M,Ng[j]] = A^T * B_j [K,Ng[j]].
 // bf16 only, every Ng[j] a multiple of 256 (gemm_tn_groups_supported says whether it applies).
 bool gemm_tn_groups_supported(int dtype, int K, int ngroups, const int* Ng);
 hipError_t launch_gemm_tn_groups(const void* A, int K, int M, int ngroups, const void* const* Bg,
                                  void* const* Cg, const int* Ng, hipStream_t st, float beta = 0.f,
-                                 bool c_f32 = false);
+                                 bool c_f32 = false, const int32_t* n_dev = nullptr);
 
 }  // namespace cf

@@ -97,7 +97,63 @@ struct GemmArgs {
     const void* Bg[3];
     void* Cg[3];
     int Ng[3];
+    // Kept-token count on the device (nullable).  When set, the kept-token dimension handed in by the
+    // host (M in mode NT, K[0] in mode TN) is only an upper bound: every block reads the count, takes
+    // min(count, bound) for that dimension and, in mode NT, plans the tiles itself (plan_launch).
+    const int32_t* n_dev;
+    // Mode NT, segment 0 (nullable): row m of A is row a_idx[m] of a matrix with a_rows rows (the
+    // gather of the upstream gradient's kept rows, folded into the A-tile loads).
+    const int32_t* a_idx;
+    int64_t a_rows;
 };
+
+// How the tiles of the last, partial round are cut.  The cost of a round of sub-tiles
+// relative to a round of 256x256 tiles is more than its share of the flops (smaller
+// tiles move more operand bytes per flop); the figures are measured on MI355X at K = 4096.
+// Returns the launch's length in rounds of 256x256 tiles.
+// A round of 256x192 tiles costs 0.94 of a round of 256x256 tiles although it has 0.75 of the
+// flops: the chip is power-limited under these kernels, so the 192 CUs that a 16 x 12 tile output
+// occupies clock higher than all 256 do (measured: 412 GFLOP in 354 us on 192 CUs, 333 us on 256).
+static constexpr double kCost192 = 0.94;
+__host__ __device__ inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+__host__ __device__ inline double plan_tiles(int tiles, int n_cu, int& n_full, int& sub) {
+    n_full = tiles / n_cu * n_cu;
+    const int rem = tiles - n_full;
+    sub = 1;
+    if (rem == 0) return n_full / n_cu;
+    double best = 1e30;
+    for (int c = 0; c < 3; ++c) {
+        const double cost = c == 0 ? 1.0 : (c == 1 ? 0.6 : 0.4);
+        const int cut = 1 << c;
+        const double t = (double)cdiv(rem * cut, n_cu) * cost;
+        if (t < best - 1e-9) {
+            best = t;
+            sub = cut;
+        }
+    }
+    return n_full / n_cu + best;
+}
+
+// Tile plan of a bf16 launch with n_cu blocks: sets n_full, sub, tile_n; returns the number of work
+// items.  The host plans a launch whose sizes it knows; with a device-side count every block runs
+// the same code on the count it read, so both give the same tiles for the same sizes.
+__host__ __device__ inline int plan_launch(int M, int N, int mode, bool c_f32, int ngroups, int n_cu,
+                                           int& n_full, int& sub, int& tile_n) {
+    const int tiles = cdiv(M, 256) * cdiv(N, 256);
+    const double rounds = plan_tiles(tiles, n_cu, n_full, sub);
+    int items = n_full + (tiles - n_full) * sub;
+    tile_n = 256;
+    if (mode == 0 && !c_f32 && ngroups == 1) {
+        // 256x192 tiles instead, when they fill the CUs better (an output of 16 x 12 tiles of
+        // 256x256 leaves a quarter of the CUs idle; as 16 x 16 tiles of 256x192 it is one full round)
+        const int tiles192 = cdiv(M, 256) * cdiv(N, 192);
+        if (cdiv(tiles192, n_cu) * kCost192 < rounds - 1e-9) {
+            tile_n = 192;
+            items = tiles192;
+        }
+    }
+    return items;
+}
 
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4_t;
 typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8_t;
@@ -162,8 +218,11 @@ struct TileRef {
 // own, and its stores drain under the next tile's MFMAs.  SPLIT: the block contracts only k in
 // [kbeg, kend) of the single segment and stores its fp32 accumulators, unscaled, to `part_out`
 // ([M, N] fp32); a second kernel adds the parts up.
+// Mx, K0x: the live values of g.M and g.K[0] (they differ from the launch arguments when the
+// kept-token count is read on the device).
 template <int MODE, int TM, int TN, bool SPLIT, bool CF32, typename Next>
-__device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef first, Next next_tile, unsigned char* smem,
+__device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const int Mx, const int K0x, const TileRef first,
+                                           Next next_tile, unsigned char* smem,
                                            const int kbeg = 0, const int kend = 0, float* part_out = nullptr) {
     constexpr int BM = 64 * TM, BN = 64 * TN, KB = 32, STAGE = GEMM_STAGE_BYTES;
     constexpr int A_BYTES = BM * KB * 2;                // B tile follows the A tile inside a stage
@@ -203,17 +262,19 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
         const int m0 = ld.m0, n0 = ld.n0;
         const bf16_t* A = static_cast<const bf16_t*>(s == 1 ? g.A[1] : (s == 2 ? g.A[2] : g.A[0]));
         const bf16_t* B = static_cast<const bf16_t*>(s == 1 ? g.B[1] : (s == 2 ? g.B[2] : ld.B0));
-        const int Kraw = s == 1 ? g.K[1] : (s == 2 ? g.K[2] : g.K[0]);
+        const int Kraw = s == 1 ? g.K[1] : (s == 2 ? g.K[2] : K0x);
         Kseg = live ? Kraw : 0;
         const int64_t K = Kraw;
+        const bool gatherA = MODE == 0 && s == 0 && g.a_idx != nullptr;
         if (MODE == 0) {
-            rsA = make_rsrc(A + (int64_t)m0 * K, ((int64_t)g.M - m0) * K * 2);
+            // gathered A: the descriptor spans the whole source matrix and a lane's offset starts at its source row
+            rsA = gatherA ? make_rsrc(A, g.a_rows * K * 2) : make_rsrc(A + (int64_t)m0 * K, ((int64_t)Mx - m0) * K * 2);
             rsB = make_rsrc(B + (int64_t)n0 * K, ((int64_t)ld.N - n0) * K * 2);
             ldA = ldB = (unsigned)K * 2u;
         } else {
-            rsA = make_rsrc(A + m0, (K * g.M - m0) * 2);
+            rsA = make_rsrc(A + m0, (K * Mx - m0) * 2);
             rsB = make_rsrc(B + n0, (K * ld.N - n0) * 2);
-            ldA = (unsigned)g.M * 2u;
+            ldA = (unsigned)Mx * 2u;
             ldB = (unsigned)ld.N * 2u;
         }
         // The per-lane parts below never change, but they are cheap to rebuild and registers are
@@ -229,12 +290,16 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
             if (MODE == 0) {
                 const unsigned row = (4 * i + wave) * 16 + (ln >> 2);
                 vbase[u] = row * (isA ? ldA : ldB) + lc_nt * 16u;
+                if (isA && gatherA) {       // rows past M carry an out-of-range offset; the index is read for live rows only
+                    const int m = m0 + (int)row;
+                    vbase[u] = m < Mx ? (unsigned)g.a_idx[m] * ldA + lc_nt * 16u : OOB_FAST;
+                }
             } else {
                 const int cpr = (isA ? BM : BN) / 8;
                 const int qq = (4 * i + wave) * 64 + ln;
                 const int kr = qq / cpr;
                 const int c = (qq % cpr) ^ ((kr & 3) << 2);
-                const bool ok = (isA ? m0 : n0) + c * 8 < (isA ? g.M : ld.N);
+                const bool ok = (isA ? m0 : n0) + c * 8 < (isA ? Mx : ld.N);
                 vbase[u] = ok ? (unsigned)kr * (isA ? ldA : ldB) + c * 16u : OOB_FAST;
             }
         }
@@ -450,7 +515,7 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
 
     // pairs of K-steps, a segment with an odd number of K-steps padded with a zero K-step
     const int npairs = SPLIT ? (kend - kbeg + 2 * KB - 1) / (2 * KB)
-                             : (g.K[0] + 2 * KB - 1) / (2 * KB) + (g.K[1] + 2 * KB - 1) / (2 * KB) +
+                             : (K0x + 2 * KB - 1) / (2 * KB) + (g.K[1] + 2 * KB - 1) / (2 * KB) +
                                    (g.K[2] + 2 * KB - 1) / (2 * KB);
     // prologue of tile ld: K-steps 0, 1 and the first group of the loads of K-steps 2, 3
     auto start_tile = [&]() __attribute__((always_inline)) {
@@ -511,7 +576,7 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
             for (int j = 0; j < FN; ++j) {
                 const int m = m0 + wm * (32 * TM) + i * 16 + l16;
                 const int n = n0 + wn * (32 * TN) + j * 16 + 4 * g4;
-                if (m < g.M && n < ep.N) {                   // N is a multiple of 8
+                if (m < Mx && n < ep.N) {                   // N is a multiple of 8
                     float4 o;
                     o.x = acc[i][j][0]; o.y = acc[i][j][1]; o.z = acc[i][j][2]; o.w = acc[i][j][3];
                     *reinterpret_cast<float4*>(part_out + (int64_t)m * ep.N + n) = o;
@@ -558,7 +623,7 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
                     for (int q = 0; q < RB; ++q) {
                         const int m = m0 + h * (BM / 2) + rb + q * RPP;
                         old[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-                        if (beta != 0.f && m < g.M) old[q] = *reinterpret_cast<const float4*>(C + (int64_t)m * ep.N + n);
+                        if (beta != 0.f && m < Mx) old[q] = *reinterpret_cast<const float4*>(C + (int64_t)m * ep.N + n);
                     }
 #pragma unroll
                     for (int q = 0; q < RB; ++q)
@@ -566,7 +631,7 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
 #pragma unroll
                     for (int q = 0; q < RB; ++q) {
                         const int m = m0 + h * (BM / 2) + rb + q * RPP;
-                        if (m < g.M) {
+                        if (m < Mx) {
                             val[q].x += beta * old[q].x; val[q].y += beta * old[q].y;
                             val[q].z += beta * old[q].z; val[q].w += beta * old[q].w;
                             *reinterpret_cast<float4*>(C + (int64_t)m * ep.N + n) = val[q];
@@ -596,7 +661,7 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
         constexpr int NP = 32 / RPP, NV = CPR / RPP;        // passes per 32 rows; distinct swizzle phases
         unsigned char* stg = smem + GEMM_STAGES * STAGE + wave * 8192;
         const __amdgpu_buffer_rsrc_t rc =
-            __builtin_amdgcn_make_buffer_rsrc(ep.C, 0, (int)((int64_t)g.M * ep.N * 2), 0x00020000);
+            __builtin_amdgcn_make_buffer_rsrc(ep.C, 0, (int)((int64_t)Mx * ep.N * 2), 0x00020000);
         const float beta = g.beta;
         int ln = lane;                                      // as in open_segment: rebuilt per tile, not carried
         asm volatile("" : "+v"(ln));
@@ -658,10 +723,26 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& g, const TileRef firs
 // one block stay on one XCD (item id mod 8 = block id mod 8).
 template <int MODE, bool CF32>
 __device__ __forceinline__ void gemm_bf16_block(const GemmArgs& g, unsigned char* smem) {
-    const int tiles_m = (g.M + 255) / 256, tiles_n = (g.N + 255) / 256;
+    int Mx = g.M, K0x = g.K[0], n_full = g.n_full, sub = g.sub, tile_n = g.tile_n;
+    if (g.n_dev != nullptr) {
+        // the kept-token count is a device value: clamp the kept-token dimension to it and (NT: the
+        // output shape depends on it) plan the tiles here, as the host does for sizes it knows
+        int n = *g.n_dev;
+        n = __builtin_amdgcn_readfirstlane(n < 0 ? 0 : n);
+        if (MODE == 0) {
+            Mx = n < Mx ? n : Mx;
+            plan_launch(Mx, g.N, 0, g.c_f32 != 0, g.ngroups, (int)gridDim.x, n_full, sub, tile_n);
+            n_full = __builtin_amdgcn_readfirstlane(n_full);
+            sub = __builtin_amdgcn_readfirstlane(sub);
+            tile_n = __builtin_amdgcn_readfirstlane(tile_n);
+        } else {
+            K0x = n < K0x ? n : K0x;
+        }
+    }
+    const int tiles_m = (Mx + 255) / 256, tiles_n = (g.N + 255) / 256;
     const int stride = (int)gridDim.x;
     if constexpr (MODE == 0 && !CF32) {
-        if (g.tile_n == 192) {
+        if (tile_n == 192) {
             // tiles of 256x192, all of one kind: block b takes tiles b, b + gridDim.x, ...
             const int tiles_n192 = (g.N + 191) / 192, n_items = tiles_m * tiles_n192;
             int w = (int)blockIdx.x;
@@ -676,7 +757,7 @@ __device__ __forceinline__ void gemm_bf16_block(const GemmArgs& g, unsigned char
             };
             TileRef t;
             tile(w, t);
-            gemm_tiles<MODE, 4, 3, false, false>(g, t, [&](TileRef& nx) __attribute__((always_inline)) {
+            gemm_tiles<MODE, 4, 3, false, false>(g, Mx, K0x, t, [&](TileRef& nx) __attribute__((always_inline)) {
                 w += stride;
                 if (w >= n_items) return false;
                 tile(w, nx);
@@ -685,22 +766,22 @@ __device__ __forceinline__ void gemm_bf16_block(const GemmArgs& g, unsigned char
             return;
         }
     }
-    const int n_items = g.n_full + (tiles_m * tiles_n - g.n_full) * g.sub;
+    const int n_items = n_full + (tiles_m * tiles_n - n_full) * sub;
     // item -> tile; false when a sub-tile lies outside the matrix
     auto decode = [&](int w, TileRef& t) __attribute__((always_inline)) {
         int bm, bn, m0, n0;
-        if (w < g.n_full) {
-            tile_coords(xcd_order(w, g.n_full), tiles_m, tiles_n, bm, bn);
+        if (w < n_full) {
+            tile_coords(xcd_order(w, n_full), tiles_m, tiles_n, bm, bn);
             m0 = bm * 256;
             n0 = bn * 256;
         } else {
-            const int cut = g.sub;
-            const int j = xcd_order(w - g.n_full, n_items - g.n_full);
+            const int cut = sub;
+            const int j = xcd_order(w - n_full, n_items - n_full);
             const int part = j % cut;
-            tile_coords(g.n_full + j / cut, tiles_m, tiles_n, bm, bn);
+            tile_coords(n_full + j / cut, tiles_m, tiles_n, bm, bn);
             m0 = bm * 256 + (cut == 4 ? (part >> 1) * 128 : 0);
             n0 = bn * 256 + (cut == 4 ? (part & 1) * 128 : (cut == 2 ? part * 128 : 0));
-            if (m0 >= g.M || n0 >= g.N) return false;
+            if (m0 >= Mx || n0 >= g.N) return false;
         }
         t.B0 = g.B[0];
         t.C = g.C;
@@ -731,10 +812,10 @@ __device__ __forceinline__ void gemm_bf16_block(const GemmArgs& g, unsigned char
             if (decode(w, t)) return true;
         return false;
     };
-    if (w < g.n_full) {         // whole tiles
+    if (w < n_full) {         // whole tiles
         decode(w, t);
-        gemm_tiles<MODE, 4, 4, false, CF32>(g, t, [&](TileRef& nx) __attribute__((always_inline)) {
-            if (!advance(g.n_full)) return false;
+        gemm_tiles<MODE, 4, 4, false, CF32>(g, Mx, K0x, t, [&](TileRef& nx) __attribute__((always_inline)) {
+            if (!advance(n_full)) return false;
             nx = t;
             return true;
         }, smem);
@@ -749,9 +830,9 @@ __device__ __forceinline__ void gemm_bf16_block(const GemmArgs& g, unsigned char
         nx = t;
         return true;
     };
-    if (g.sub == 1) gemm_tiles<MODE, 4, 4, false, CF32>(g, t, next_sub, smem);
-    else if (g.sub == 2) gemm_tiles<MODE, 4, 2, false, CF32>(g, t, next_sub, smem);
-    else gemm_tiles<MODE, 2, 2, false, CF32>(g, t, next_sub, smem);
+    if (sub == 1) gemm_tiles<MODE, 4, 4, false, CF32>(g, Mx, K0x, t, next_sub, smem);
+    else if (sub == 2) gemm_tiles<MODE, 4, 2, false, CF32>(g, Mx, K0x, t, next_sub, smem);
+    else gemm_tiles<MODE, 2, 2, false, CF32>(g, Mx, K0x, t, next_sub, smem);
 }
 
 template <int MODE>
@@ -779,7 +860,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_splitk_kernel(GemmArgs g, float
     const int kbeg = (int)blockIdx.y * kchunk;
     const int kend = min(g.K[0], kbeg + kchunk);
     const TileRef t{m0, n0, g.N, g.B[0], g.C};
-    gemm_tiles<MODE, 2, 2, true, false>(g, t, [](TileRef&) { return false; }, smem, kbeg, kend,
+    gemm_tiles<MODE, 2, 2, true, false>(g, g.M, g.K[0], t, [](TileRef&) { return false; }, smem, kbeg, kend,
                                         partial + (int64_t)blockIdx.y * g.M * g.N);
 }
 
@@ -817,8 +898,14 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g) {
     __shared__ float As[16][64 + 4];
     __shared__ float Bs[16][64 + 4];
     const int tid = threadIdx.x;
-    const int tiles_m = (g.M + 63) / 64;
+    const int tiles_m = (g.M + 63) / 64;        // of the upper bound: the grid was sized for it
     const int m0 = (blockIdx.x % tiles_m) * 64, n0 = (blockIdx.x / tiles_m) * 64;
+    if (g.n_dev != nullptr) {
+        const int n = live_rows(MODE == 0 ? g.M : g.K[0], g.n_dev);
+        if (MODE == 0) g.M = n;
+        else g.K[0] = n;
+        if (m0 >= g.M) return;
+    }
     const int tx = tid & 15, ty = tid >> 4;
     float acc[4][4] = {};
     for (int s = 0; s < g.nseg; ++s) {
@@ -833,8 +920,10 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g) {
                 if (MODE == 0) { kk = e & 15; r = e >> 4; } else { r = e & 63; kk = e >> 6; }
                 const bool ka = k0 + kk < K;
                 float av = 0.f, bv = 0.f;
-                if (ka && m0 + r < g.M)
-                    av = MODE == 0 ? A[(int64_t)(m0 + r) * K + k0 + kk] : A[(int64_t)(k0 + kk) * g.M + m0 + r];
+                if (ka && m0 + r < g.M) {
+                    const int64_t arow = (MODE == 0 && s == 0 && g.a_idx != nullptr) ? g.a_idx[m0 + r] : m0 + r;
+                    av = MODE == 0 ? A[arow * K + k0 + kk] : A[(int64_t)(k0 + kk) * g.M + m0 + r];
+                }
                 if (ka && n0 + r < g.N)
                     bv = MODE == 0 ? B[(int64_t)(n0 + r) * K + k0 + kk] : B[(int64_t)(k0 + kk) * g.N + n0 + r];
                 As[kk][r] = av;
@@ -869,32 +958,6 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g) {
     }
 }
 
-
-// How the tiles of the last, partial round are cut.  The cost of a round of sub-tiles
-// relative to a round of 256x256 tiles is more than its share of the flops (smaller
-// tiles move more operand bytes per flop); the figures are measured on MI355X at K = 4096.
-// Returns the launch's length in rounds of 256x256 tiles.
-// A round of 256x192 tiles costs 0.94 of a round of 256x256 tiles although it has 0.75 of the
-// flops: the chip is power-limited under these kernels, so the 192 CUs that a 16 x 12 tile output
-// occupies clock higher than all 256 do (measured: 412 GFLOP in 354 us on 192 CUs, 333 us on 256).
-static constexpr double kCost192 = 0.94;
-static double plan_tiles(int tiles, int n_cu, int& n_full, int& sub) {
-    n_full = tiles / n_cu * n_cu;
-    const int rem = tiles - n_full;
-    sub = 1;
-    if (rem == 0) return n_full / n_cu;
-    const double cost[3] = {1.0, 0.6, 0.4};
-    const int cut[3] = {1, 2, 4};
-    double best = 1e30;
-    for (int c = 0; c < 3; ++c) {
-        const double t = (double)ceil_div((int64_t)rem * cut[c], n_cu) * cost[c];
-        if (t < best - 1e-9) {
-            best = t;
-            sub = cut[c];
-        }
-    }
-    return n_full / n_cu + best;
-}
 
 // CUs of the current device (cached per device ordinal; 256 if the query fails)
 static int compute_units() {
@@ -948,19 +1011,10 @@ static hipError_t launch_bf16(GemmArgs& g, hipStream_t st) {
     hipError_t e = g.c_f32 ? allow_dynamic_lds(reinterpret_cast<const void*>(&gemm_bf16_f32out_kernel<MODE>), GEMM_SMEM, lds_ok_f32)
                            : allow_dynamic_lds(reinterpret_cast<const void*>(&gemm_bf16_kernel<MODE>), GEMM_SMEM, lds_ok);
     if (e != hipSuccess) return e;
-    const int tiles = ceil_div(g.M, 256) * ceil_div(g.N, 256);
-    const double rounds = plan_tiles(tiles, compute_units(), g.n_full, g.sub);
-    int items = g.n_full + (tiles - g.n_full) * g.sub;
-    if (MODE == 0 && !g.c_f32 && g.ngroups == 1) {
-        // 256x192 tiles instead, when they fill the CUs better (an output of 16 x 12 tiles of
-        // 256x256 leaves a quarter of the CUs idle; as 16 x 16 tiles of 256x192 it is one full round)
-        const int tiles192 = ceil_div(g.M, 256) * ceil_div(g.N, 192);
-        if (ceil_div(tiles192, compute_units()) * kCost192 < rounds - 1e-9) {
-            g.tile_n = 192;
-            items = tiles192;
-        }
-    }
-    const int grid = std::min(items, compute_units());      // a block walks through its items
+    const int items = plan_launch(g.M, g.N, MODE, g.c_f32 != 0, g.ngroups, compute_units(), g.n_full, g.sub, g.tile_n);
+    // a block walks through its items; with a device-side count the blocks plan for themselves (for
+    // as many blocks as CUs) and those without an item leave at once
+    const int grid = g.n_dev != nullptr ? compute_units() : std::min(items, compute_units());
     if (g.c_f32) gemm_bf16_f32out_kernel<MODE><<<grid, 256, GEMM_SMEM, st>>>(g);
     else gemm_bf16_kernel<MODE><<<grid, 256, GEMM_SMEM, st>>>(g);
     return hipGetLastError();
@@ -968,8 +1022,9 @@ static hipError_t launch_bf16(GemmArgs& g, hipStream_t st) {
 
 hipError_t launch_gemm(int dtype, int mode, const GemmSeg* segs, int nseg, void* C, int M, int N,
                        float beta, hipStream_t st, float alpha, void* splitk_ws, size_t splitk_bytes,
-                       bool c_f32) {
+                       bool c_f32, const int32_t* n_dev, const int32_t* a_idx, int64_t a_rows) {
     if (M <= 0 || N <= 0) return hipSuccess;
+    if (a_idx != nullptr && (mode != 0 || a_rows <= 0)) return hipErrorInvalidValue;
     GemmArgs g;
     g.nseg = 0;
     for (int s = 0; s < nseg; ++s) {
@@ -984,6 +1039,10 @@ hipError_t launch_gemm(int dtype, int mode, const GemmSeg* segs, int nseg, void*
     g.c_f32 = (c_f32 && dtype == CF_BF16) ? 1 : 0;
     g.ngroups = 1;
     for (int j = 0; j < 3; ++j) { g.Bg[j] = nullptr; g.Cg[j] = nullptr; g.Ng[j] = 0; }
+    g.n_dev = n_dev; g.a_idx = a_idx; g.a_rows = a_rows;
+    // with a device-side count the kept-token dimension must be that of segment 0 (mode TN) and no
+    // segment may have been dropped
+    if (n_dev != nullptr && (g.nseg != nseg || (mode == 1 && nseg != 1))) return hipErrorInvalidValue;
     if (g.nseg == 0) {
         // empty contraction: C = beta*C; only beta in {0,1} is supported by the API
         if (beta == 0.f) return launch_fill_zero(C, (size_t)M * N * (c_f32 ? 4 : dtype_size(dtype)), st);
@@ -994,6 +1053,7 @@ hipError_t launch_gemm(int dtype, int mode, const GemmSeg* segs, int nseg, void*
         for (int s = 0; s < g.nseg; ++s)
             if ((int64_t)M * g.K[s] * 2 >= ((int64_t)1 << 31) || (int64_t)N * g.K[s] * 2 >= ((int64_t)1 << 31))
                 return hipErrorInvalidValue;
+        if (a_idx != nullptr && a_rows * g.K[0] * 2 >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
         if (((int64_t)M + 256) * N * 2 >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
     }
     if (dtype == CF_F32) {
@@ -1002,7 +1062,7 @@ hipError_t launch_gemm(int dtype, int mode, const GemmSeg* segs, int nseg, void*
         else gemm_f32_kernel<1><<<grid, 256, 0, st>>>(g);
         return hipGetLastError();
     }
-    if (splitk_ws != nullptr) {
+    if (splitk_ws != nullptr && n_dev == nullptr && a_idx == nullptr) {
         int kchunk = 0;
         const int parts = plan_splitk(g, compute_units(), splitk_bytes, kchunk);
         if (parts >= 2)
@@ -1020,7 +1080,8 @@ bool gemm_tn_groups_supported(int dtype, int K, int ngroups, const int* Ng) {
 }
 
 hipError_t launch_gemm_tn_groups(const void* A, int K, int M, int ngroups, const void* const* Bg,
-                                 void* const* Cg, const int* Ng, hipStream_t st, float beta, bool c_f32) {
+                                 void* const* Cg, const int* Ng, hipStream_t st, float beta, bool c_f32,
+                                 const int32_t* n_dev) {
     if (M <= 0) return hipSuccess;
     GemmArgs g;
     int N = 0;
@@ -1039,6 +1100,7 @@ hipError_t launch_gemm_tn_groups(const void* A, int K, int M, int ngroups, const
     for (int s = 1; s < 3; ++s) { g.A[s] = nullptr; g.B[s] = nullptr; g.K[s] = 0; }
     g.C = Cg[0]; g.M = M; g.N = N; g.beta = beta; g.alpha = 1.f; g.n_full = 0; g.sub = 1; g.tile_n = 256;
     g.c_f32 = c_f32 ? 1 : 0;
+    g.n_dev = n_dev; g.a_idx = nullptr; g.a_rows = 0;
     return launch_bf16<1>(g, st);
 }
 

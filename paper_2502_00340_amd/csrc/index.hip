@@ -205,9 +205,11 @@ hipError_t launch_keep_index_static(const uint8_t* mask, int B, int S, int32_t* 
 template <typename W>
 __global__ __launch_bounds__(256) void gather_rows_kernel(const W* __restrict__ src,
                                                           const int32_t* __restrict__ idx,
-                                                          int n_rows, int words_per_row,
+                                                          int n_max, const int32_t* __restrict__ n_dev,
+                                                          int words_per_row,
                                                           int lanes_per_row, int rows_per_block,
                                                           W* __restrict__ dst) {
+    const int n_rows = live_rows(n_max, n_dev);
     const int r = threadIdx.x / lanes_per_row;
     const int c0 = threadIdx.x % lanes_per_row;
     const int j = blockIdx.x * rows_per_block + r;
@@ -217,8 +219,9 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const W* __restrict__ 
     for (int c = c0; c < words_per_row; c += lanes_per_row) d[c] = s[c];
 }
 
-hipError_t launch_gather(const void* src, int64_t cols_bytes, const int32_t* idx, int n_rows,
+hipError_t launch_gather(const void* src, int64_t cols_bytes, const int32_t* idx, RowCount rows,
                          void* dst, hipStream_t st) {
+    const int n_rows = rows.n;          // the grid covers the upper bound; blocks past the live count leave at once
     if (n_rows <= 0) return hipSuccess;
     const bool vec16 = (cols_bytes % 16 == 0) && ((uintptr_t)src % 16 == 0) && ((uintptr_t)dst % 16 == 0);
     const int wbytes = vec16 ? 16 : 4;
@@ -228,11 +231,11 @@ hipError_t launch_gather(const void* src, int64_t cols_bytes, const int32_t* idx
     const int rpb = 256 / lanes;
     const int grid = ceil_div(n_rows, rpb);
     if (vec16)
-        gather_rows_kernel<uint4><<<grid, 256, 0, st>>>(static_cast<const uint4*>(src), idx, n_rows,
+        gather_rows_kernel<uint4><<<grid, 256, 0, st>>>(static_cast<const uint4*>(src), idx, n_rows, rows.dev,
                                                         words, lanes, rpb, static_cast<uint4*>(dst));
     else
         gather_rows_kernel<unsigned><<<grid, 256, 0, st>>>(static_cast<const unsigned*>(src), idx,
-                                                           n_rows, words, lanes, rpb,
+                                                           n_rows, rows.dev, words, lanes, rpb,
                                                            static_cast<unsigned*>(dst));
     return hipGetLastError();
 }

@@ -79,11 +79,12 @@ def test_static_keep_index_argument_errors(L):
 
 def test_gather_argument_errors(L):
     f = L.cf_gather_rows
-    assert f(None, 4, 8, 1, FAKE, 2, FAKE, None) == 1
-    assert f(FAKE, 4, 8, 7, FAKE, 2, FAKE, None) == 3
-    assert f(FAKE, 4, 0, 1, FAKE, 2, FAKE, None) == 2
-    assert f(FAKE, 4, 3, 0, FAKE, 2, FAKE, None) == 2        # 3 bf16 = 6 bytes per row
-    assert f(FAKE, 4, 8, 1, FAKE, -1, FAKE, None) == 2
+    assert f(None, 4, 8, 1, FAKE, None, 2, FAKE, None) == 1
+    assert f(FAKE, 4, 8, 7, FAKE, None, 2, FAKE, None) == 3
+    assert f(FAKE, 4, 0, 1, FAKE, None, 2, FAKE, None) == 2
+    assert f(FAKE, 4, 3, 0, FAKE, None, 2, FAKE, None) == 2        # 3 bf16 = 6 bytes per row
+    assert f(FAKE, 4, 8, 1, FAKE, None, -1, FAKE, None) == 2
+    assert f(FAKE, 4, 8, 1, FAKE, C.c_void_p(0x10002), 2, FAKE, None) == 2   # misaligned device count
 
 
 def test_linear_argument_errors(L):
@@ -107,7 +108,11 @@ def test_attention_argument_errors(L):
     assert f(None, *args, 4, FAKE, FAKE, FAKE, FAKE, 4096, None) == 1
     assert f(C.byref(d), None, *args[1:], 4, FAKE, FAKE, FAKE, FAKE, 4096, None) == 1
     assert f(C.byref(_desc(Hq=6, Hkv=4)), *args, 4, FAKE, FAKE, FAKE, FAKE, 4096, None) == 2
-    assert f(C.byref(_desc(dtype="bf16", d=96)), *args, 4, FAKE, FAKE, FAKE, FAKE, 4096, None) == 2
+    assert f(C.byref(_desc(dtype="bf16", d=96)), *args, 4, FAKE, FAKE, FAKE, FAKE, 4096, None) == 5   # no kernel for this head size
+    assert f(C.byref(_desc(dtype="bf16", d=100)), *args, 4, FAKE, FAKE, FAKE, FAKE, 4096, None) == 2
+    # 32-bit byte offsets inside one sequence's q rows: refused, not wrapped
+    assert f(C.byref(_desc(dtype="bf16", B=1, S=1 << 20, Hq=32, Hkv=8, d=128)), *args, 4, FAKE, FAKE, FAKE, FAKE,
+             4096, None) == 5
     assert f(C.byref(_desc(d=48)), *args, 4, FAKE, FAKE, FAKE, FAKE, 4096, None) == 2
     assert f(C.byref(d), *args, 257, FAKE, FAKE, FAKE, FAKE, 1 << 20, None) == 2   # n_kept > T
     assert f(C.byref(d), *args, 4, FAKE, FAKE, FAKE, None, 0, None) == 4
@@ -122,31 +127,41 @@ def test_layer_argument_errors(L):
     n = C.c_int32(0)
     f = L.cf_layer_bwd_filtered
     ok_ws = L.cf_layer_workspace_bytes(C.byref(d), 256)
-    assert f(None, C.byref(sv), C.byref(w), FAKE, FAKE, C.byref(g), None, None, C.byref(n), FAKE, ok_ws, None) == 1
-    assert f(C.byref(d), C.byref(sv), C.byref(w), FAKE, None, C.byref(g), None, None, C.byref(n), FAKE, ok_ws, None) == 1
-    assert f(C.byref(d), C.byref(sv), C.byref(w), FAKE, FAKE, C.byref(g), None, None, None, FAKE, ok_ws, None) == 1
+    tail = (None, None, None, C.byref(n), FAKE, ok_ws, None)     # idx_out, cu_out, n_dev_out, n_host, ws, bytes, stream
+    assert f(None, C.byref(sv), C.byref(w), FAKE, FAKE, 0, C.byref(g), *tail) == 1
+    assert f(C.byref(d), C.byref(sv), C.byref(w), FAKE, None, 0, C.byref(g), *tail) == 1                # no mask
+    assert f(C.byref(d), C.byref(sv), C.byref(w), FAKE, FAKE, -1, C.byref(g), *tail) == 2               # max_kept < 0
     sv_bad = Bn.Saved(*([0x10000] * 8 + [0, None, None]))
-    assert f(C.byref(d), C.byref(sv_bad), C.byref(w), FAKE, FAKE, C.byref(g), None, None, C.byref(n), FAKE, ok_ws, None) == 1
-    assert f(C.byref(d), C.byref(sv), C.byref(w), FAKE, FAKE, C.byref(g), None, None, C.byref(n), FAKE, 16, None) == 4
-    assert f(C.byref(_desc(H=250)), C.byref(sv), C.byref(w), FAKE, FAKE, C.byref(g), None, None, C.byref(n), FAKE, ok_ws, None) == 2
+    assert f(C.byref(d), C.byref(sv_bad), C.byref(w), FAKE, FAKE, 0, C.byref(g), *tail) == 1
+    assert f(C.byref(d), C.byref(sv), C.byref(w), FAKE, FAKE, 0, C.byref(g), None, None, None, C.byref(n), FAKE, 16, None) == 4
+    # a workspace sized for 128 kept tokens does not do for max_kept = T, but does for max_kept = 128
+    half_ws = L.cf_layer_workspace_bytes(C.byref(d), 128)
+    assert f(C.byref(d), C.byref(sv), C.byref(w), FAKE, FAKE, 0, C.byref(g), None, None, None, C.byref(n), FAKE, half_ws, None) == 4
+    assert f(C.byref(d), C.byref(sv), C.byref(w), FAKE, FAKE, 0, C.byref(g), C.c_void_p(0x10002), None, None, C.byref(n),
+             FAKE, ok_ws, None) == 2                                                                    # misaligned idx_out
+    assert f(C.byref(_desc(H=250)), C.byref(sv), C.byref(w), FAKE, FAKE, 0, C.byref(g), *tail) == 2
     sv_rope = Bn.Saved(*([0x10000] * 9 + [0x10000, None]))      # one rotary table without the other
-    assert f(C.byref(d), C.byref(sv_rope), C.byref(w), FAKE, FAKE, C.byref(g), None, None, C.byref(n), FAKE, ok_ws, None) == 1
+    assert f(C.byref(d), C.byref(sv_rope), C.byref(w), FAKE, FAKE, 0, C.byref(g), *tail) == 1
     # a [T,F] matrix of 2 GiB or more is beyond the bf16 GEMM's 32-bit offsets: refused up front
     big = _desc(dtype="bf16", B=64, S=8192, H=4096, Hq=32, Hkv=8, d=128, F=14336)
-    assert f(C.byref(big), C.byref(sv), C.byref(w), FAKE, FAKE, C.byref(g), None, None, C.byref(n), FAKE, ok_ws, None) == 5
+    assert f(C.byref(big), C.byref(sv), C.byref(w), FAKE, FAKE, 0, C.byref(g), *tail) == 5
     assert L.cf_layer_workspace_bytes(C.byref(big), 1024) == 0
     g_bad = Bn.Grads(*([0x10000] * 10 + [2]))                   # main_grad is 0 or 1
-    assert f(C.byref(d), C.byref(sv), C.byref(w), FAKE, FAKE, C.byref(g_bad), None, None, C.byref(n), FAKE, ok_ws, None) == 2
+    assert f(C.byref(d), C.byref(sv), C.byref(w), FAKE, FAKE, 0, C.byref(g_bad), *tail) == 2
     fc = L.cf_layer_bwd_compact
     assert fc(C.byref(d), C.byref(sv), C.byref(w), FAKE, None, FAKE, 4, C.byref(g), FAKE, ok_ws, None) == 1
     assert fc(C.byref(d), C.byref(sv), C.byref(w), None, FAKE, FAKE, 4, C.byref(g), FAKE, ok_ws, None) == 1
     assert fc(C.byref(d), C.byref(sv), C.byref(w), FAKE, FAKE, FAKE, 257, C.byref(g), FAKE, ok_ws, None) == 2   # n_kept > T
     assert fc(C.byref(d), C.byref(sv), C.byref(w), FAKE, FAKE, FAKE, -1, C.byref(g), FAKE, ok_ws, None) == 2
     assert fc(C.byref(d), C.byref(sv), C.byref(w), FAKE, FAKE, FAKE, 200, C.byref(g), FAKE, 4096, None) == 4
+    fv = L.cf_layer_bwd_compact_dev
+    assert fv(C.byref(d), C.byref(sv), C.byref(w), FAKE, FAKE, FAKE, None, 0, C.byref(g), FAKE, ok_ws, None) == 1   # no device count
+    assert fv(C.byref(d), C.byref(sv), C.byref(w), FAKE, FAKE, FAKE, FAKE, -3, C.byref(g), FAKE, ok_ws, None) == 2
+    assert fv(C.byref(d), C.byref(sv), C.byref(w), FAKE, FAKE, FAKE, FAKE, 0, C.byref(g), FAKE, half_ws, None) == 4
     fd = L.cf_layer_bwd_dense
     assert fd(C.byref(d), C.byref(sv), C.byref(w), None, C.byref(g), FAKE, ok_ws, None) == 1
     assert fd(C.byref(d), C.byref(sv), C.byref(w), FAKE, C.byref(g), FAKE, ok_ws - 256, None) == 4
-    assert fd(C.byref(_desc(dtype="bf16", d=32)), C.byref(sv), C.byref(w), FAKE, C.byref(g), FAKE, ok_ws, None) == 2
+    assert fd(C.byref(_desc(dtype="bf16", d=32)), C.byref(sv), C.byref(w), FAKE, C.byref(g), FAKE, ok_ws, None) == 5
 
 
 def test_lora_argument_errors(L):

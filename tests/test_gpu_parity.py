@@ -350,10 +350,74 @@ def test_layer_with_a_count_known_beforehand_never_synchronises():
     plan.filtered_known(sv, W, dy, mask, n)
     torch.cuda.synchronize()
     assert torch.equal(plan.idx[:n], ref.idx[:n]) and torch.equal(plan.cu_kept, ref.cu_kept)
-    assert int(plan._n_dev.item()) == n
+    assert int(plan.n_kept_dev.item()) == n
     for name in Hn.GRADS:
         assert torch.equal(plan.grads[name], ref.grads[name]), name
     assert torch.equal(plan.grads["dx"][:n], ref.grads["dx"][:n])
+
+
+def test_layer_device_side_count_with_a_tight_bound_and_a_stack_without_any_host_read():
+    """The filtered call reads N_k on the device.  (1) A workspace and launch bound of exactly N_k
+    (max_kept = N_k, the smallest legal one) gives bit for bit what the default bound T gives.
+    (2) A layer below takes the count from the device as well (cf_layer_bwd_compact_dev): the same
+    bits as cf_layer_bwd_compact with the host count.  Nothing is synchronised until the end."""
+    shape = SMALL_BF16_D128
+    say("layer device-side count %s" % shape.name)
+    p = Hn.Problem(shape, 62, "independent", rho=0.4)
+    low = Hn.Problem(shape, 63, "independent", mask=p.mask)
+    sv, W, dy, mask = p.device_tensors(DEV)
+    sv1, W1, _, _ = low.device_tensors(DEV)
+    n_true = int(p.mask.sum())
+    full = Bn.LayerBackward(p.desc(), device=DEV)                       # max_kept = T
+    tight = Bn.LayerBackward(p.desc(), device=DEV, max_kept=n_true)
+    assert tight.ws_bytes < full.ws_bytes
+    full.filtered_async(sv, W, dy, mask)
+    tight.filtered_async(sv, W, dy, mask)
+    lo_dev = Bn.LayerBackward(p.desc(), device=DEV)
+    lo_dev.compact_dev(sv1, W1, full.grads["dx"], full.idx, full.cu_kept, full.n_kept_dev)
+    n = full.n_kept()                                                   # the first synchronisation
+    assert n == n_true == tight.n_kept()
+    for name in Hn.GRADS:
+        assert torch.equal(full.grads[name], tight.grads[name]), name
+    assert torch.equal(full.grads["dx"][:n], tight.grads["dx"][:n])
+    assert torch.equal(full.idx[:n], tight.idx[:n])
+    lo_host = Bn.LayerBackward(p.desc(), device=DEV)
+    lo_host.compact(sv1, W1, full.grads["dx"][:n], full.idx, full.cu_kept, n)
+    torch.cuda.synchronize()
+    for name in Hn.GRADS:
+        assert torch.equal(lo_dev.grads[name], lo_host.grads[name]), name
+    assert torch.equal(lo_dev.grads["dx"][:n], lo_host.grads["dx"][:n])
+    # and the result is right
+    errs = Hn.check_layer(p, dict(full.grads, dx=full.grads["dx"][:n]), p.oracle(), np.flatnonzero(p.mask.reshape(-1)),
+                          Hn.TOL["bf16"])
+    say("  " + " ".join("%s=%.1e" % kv for kv in errs.items()))
+
+
+def test_layer_mask_that_keeps_more_than_max_kept_stays_inside_its_buffers():
+    """A caller's bound that the mask exceeds: the call processes the first max_kept kept tokens, writes
+    nothing outside buffers sized for max_kept, and reports the true count, which exposes the mistake."""
+    shape = WL.LayerShape("overflow", B=2, S=256, H=256, Hq=4, Hkv=2, d=64, F=384, dtype="bf16")
+    say("layer max_kept exceeded")
+    p = Hn.Problem(shape, 64, "independent", rho=0.5)
+    sv, W, dy, mask = p.device_tensors(DEV)
+    n_true = int(p.mask.sum())
+    bound = n_true - 37
+    plan = Bn.LayerBackward(p.desc(), device=DEV, max_kept=bound)
+    PAD = 4096
+    nbytes = plan.ws.numel()
+    buf = torch.full((nbytes + 2 * PAD,), 0xA5, dtype=torch.uint8, device=DEV)
+    plan.ws = buf[PAD:PAD + nbytes]
+    dxb = torch.full((bound * shape.H * 2 + 2 * PAD,), 0xA5, dtype=torch.uint8, device=DEV)
+    plan.grads["dx"] = dxb[PAD:PAD + bound * shape.H * 2].view(torch.bfloat16).view(bound, shape.H)
+    plan._g = Bn.Grads(*([plan.grads[n].data_ptr() for n in Bn.GRAD_NAMES] + [0]))
+    n = plan.filtered(sv, W, dy, mask)
+    assert n == n_true > bound
+    for b in (buf, dxb):
+        assert bool((b[:PAD] == 0xA5).all()) and bool((b[-PAD:] == 0xA5).all())
+    # the first `bound` kept tokens of a single sequence mask would be a legal problem of its own: here we only
+    # require finite outputs
+    assert bool(torch.isfinite(plan.grads["dx"].float()).all())
+    assert bool(torch.isfinite(plan.grads["dwd"].float()).all())
 
 
 MAIN_GRAD_SHAPES = [
