@@ -141,7 +141,7 @@ cf_status cf_build_keep_index(const uint8_t* mask, int32_t B, int32_t S,
 /* The keep-index build for callers that cannot allocate device memory or carry a workspace
  * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc).  Same
  * arguments and results as cf_build_keep_index without the workspace and without the host copy:
- * the per-block counts live in a device array built into the library (16 KiB per GPU, held until
+ * the per-span counts (one per 8192 tokens) live in a device array built into the library (8 KiB per GPU, held until
  * the process ends), nothing is allocated, freed or copied to the host and the stream is not
  * synchronised.  At most 2^24 tokens (B*S); more returns CF_ERR_UNSUPPORTED before any launch.
  * All calls on one GPU share that array: calls that overlap on one GPU (two streams, two host

@@ -54,7 +54,8 @@ cf_status check_attn_desc(const cf_layer_desc* L) {
         if (L->d != 64 && L->d != 128) return CF_ERR_UNSUPPORTED;      // a valid head size this build has no kernel for
         // the matrix-core attention kernels address K, V (per sequence) and Q, dO (per sequence's kept
         // rows) with 32-bit byte offsets
-        if ((int64_t)L->S * L->Hq * L->d * 2 >= ((int64_t)1 << 32)) return CF_ERR_UNSUPPORTED;
+        // (the loads run up to four 64-row steps past a sequence's end before the range check stops them)
+        if (((int64_t)L->S + 256) * L->Hq * L->d * 2 >= ((int64_t)1 << 32)) return CF_ERR_UNSUPPORTED;
     } else {
         if (!pow2(L->d) || L->d < 4 || L->d > 256) return CF_ERR_SHAPE;
     }

@@ -118,29 +118,9 @@ __device__ __forceinline__ bf16x8_t frag_tokens(const unsigned char* tile, int r
     return __builtin_bit_cast(bf16x8_t, both);
 }
 
-// ---------------------------------------------------------------------------
-// global -> LDS copy of a [64][D] tile whose rows are `row_stride` bytes apart in
-// memory; rows >= rows_valid are zero-filled through the descriptor's range check.
-// Wave w, load i fills LDS bytes [(4*i + w) KB, +1 KB) of the tile: 1 KB = 1024/(2D)
-// rows; the lane fetches the global chunk that belongs in its (swizzled) LDS slot.
-// ---------------------------------------------------------------------------
-template <int D>
-__device__ __forceinline__ void dma_tile(unsigned lds_tile /*uniform*/, i32x4_t rsrc, unsigned base_off,
-                                         unsigned row_stride, int rows_valid, int wave, int lane) {
-    constexpr int NCH = D / 8;                  // 16-byte chunks per row
-    constexpr int RPL = 64 / NCH;               // rows per 1 KB wave-load
-    constexpr int NLD = 64 / RPL / 4;           // wave-loads per wave per tile
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-        const int row = (4 * i + wave) * RPL + lane / NCH;
-        const int pc = lane % NCH;
-        const int g = (D == 128) ? (((row & 3) << 2) | ((row >> 2) & 3))
-                                 : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
-        const unsigned off = base_off + (unsigned)row * row_stride + (unsigned)((pc ^ g) << 4);
-        dma16(__builtin_amdgcn_readfirstlane(lds_tile + (4 * i + wave) * 1024), rsrc,
-              row < rows_valid ? off : 0xFFFFFFFFu);
-    }
-}
+// global -> LDS: a [64][D] tile goes in as 1 KB wave-loads (16 bytes per lane): wave w, load i fills
+// LDS bytes [(4*i + w) KB, +1 KB) of the tile, i.e. 1024/(2D) rows, and a lane fetches the global chunk
+// that belongs in its (swizzled) LDS slot.  Rows outside the source's descriptor range arrive as zeros.
 
 // ---------------------------------------------------------------------------
 // dQ kernel
@@ -184,12 +164,15 @@ __global__ __launch_bounds__(256, 2) void attn_dq_kernel(AttnParams p) {
     const int jlast = j0 + rows_in_tile - 1;
     const int maxpos = (p.idx ? p.idx[jlast] : jlast) - b * p.S;
     const int nkt = maxpos / 64 + 1;
-    int wave_maxpos = -1;
+    // positions of the wave's last and first query: key tiles past the former are skipped, key tiles
+    // that end at or before the latter are visible to every query of the wave and need no mask
+    int wave_maxpos = -1, wave_minpos = -1;
     {
         const int wrows = min(32, rows_in_tile - wave * 32);
         if (wrows > 0) {
             const int jw = j0 + wave * 32 + wrows - 1;
             wave_maxpos = (p.idx ? p.idx[jw] : jw) - b * p.S;
+            wave_minpos = (p.idx ? p.idx[j0 + wave * 32] : j0 + wave * 32) - b * p.S;
         }
     }
     const float scale2 = p.scale * LOG2E;
@@ -200,69 +183,96 @@ __global__ __launch_bounds__(256, 2) void attn_dq_kernel(AttnParams p) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[nt][v] = 0.f;
 
-    // K and V of this sequence and KV head: rows are Nkv*2 bytes apart
+    // K and V of this sequence and KV head: rows are Nkv*2 bytes apart.  A tile is loaded whole: rows past
+    // the last query's position are later keys of the same sequence (masked out below) or lie outside
+    // the descriptor's range (zeros).
     const i32x4_t rsK = make_rsrc(p.k_full + ((int64_t)b * p.S) * Nkv + g * D, ((int64_t)p.S * Nkv - g * D) * 2);
     const i32x4_t rsV = make_rsrc(p.v_full + ((int64_t)b * p.S) * Nkv + g * D, ((int64_t)p.S * Nkv - g * D) * 2);
     const unsigned lds0 = __builtin_amdgcn_readfirstlane(lds_addr_of(smem));
-    auto issue_kv = [&](int kt, int stage) {
-        const unsigned sk = lds0 + stage * 2 * TILE;
+    // per-lane offset of a tile's first load inside a 64-row tile (row * stride + swizzled chunk): it never
+    // changes, and load i lies 4*i*RPL rows further on with the same swizzle term
+    constexpr int NCH = D / 8, RPL = 64 / NCH;
+    unsigned voff0;
+    {
+        const int row = wave * RPL + lane / NCH;
+        const int pc = lane % NCH;
+        const int sw = (D == 128) ? (((row & 3) << 2) | ((row >> 2) & 3)) : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
+        voff0 = (unsigned)row * (unsigned)(Nkv * 2) + (unsigned)((pc ^ sw) << 4);
+    }
+    const unsigned wave_lds = __builtin_amdgcn_readfirstlane(lds0 + (unsigned)wave * 1024u);   // scalar: the wave's 1 KB slot
+    auto issue_kv = [&](int kt, int stage) __attribute__((always_inline)) {
+        const unsigned sk = wave_lds + stage * 2 * TILE;
+        const unsigned step = (unsigned)(4 * RPL) * (unsigned)(Nkv * 2);
         const unsigned base = (unsigned)(kt * 64) * (unsigned)(Nkv * 2);
-        const int valid = maxpos + 1 - kt * 64;
-        dma_tile<D>(sk, rsK, base, Nkv * 2, valid, wave, lane);
-        dma_tile<D>(sk + TILE, rsV, base, Nkv * 2, valid, wave, lane);
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) dma16(sk + 4 * i * 1024, rsK, voff0 + (base + i * step));
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) dma16(sk + TILE + 4 * i * 1024, rsV, voff0 + (base + i * step));
+    };
+    // One 64-key tile in the LDS stage at sk.  MASKED: some key of the tile lies after some query of the
+    // wave; the other tiles (most of them) spend no instruction on the mask.
+    // One 32-key half of the tile at a time keeps the score registers at 2 x 16.  The LDS fragments of an
+    // MFMA are read while the previous MFMAs run (one step ahead).  (Fragment addresses are rebuilt per
+    // read: with two waves per SIMD the register file has no room to keep them at d = 128.)
+    auto tile = [&](auto MASKED_, const int kt, const unsigned char* sk) __attribute__((always_inline)) {
+        constexpr bool masked = decltype(MASKED_)::value != 0;
+        const unsigned char* sv = sk + TILE;
+        bf16x8_t fa[2][2], fc[2];
+        auto load_a = [&](int mt, int ks, int buf) __attribute__((always_inline)) {
+            fa[buf][0] = frag_rows<D>(sk, mt * 32 + slot, ks, hh);
+            fa[buf][1] = frag_rows<D>(sv, mt * 32 + slot, ks, hh);
+        };
+        auto load_c = [&](int mt, int c, int buf) __attribute__((always_inline)) {
+            fc[buf] = frag_tokens<D>(sk, mt * 32 + 16 * (c / NT), c % NT, lane);
+        };
+        load_a(0, 0, 0);
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+            f32x16_t st, dpt;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) { st[v] = 0.f; dpt[v] = 0.f; }
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                if (ks + 1 < KS) load_a(mt, ks + 1, (ks + 1) & 1);
+                else load_c(mt, 0, 0);
+                CF_SCHED_FENCE();
+                st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][0], qf[ks], st, 0, 0, 0);
+                dpt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][1], dof[ks], dpt, 0, 0, 0);
+                CF_SCHED_FENCE();
+            }
+            // dS^T = P^T o (dP^T - D): lane = query, register = key
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                float pr = __builtin_amdgcn_exp2f(st[v] * scale2 - lse2);
+                if (masked) {
+                    const int key = kt * 64 + mt * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
+                    pr = key <= pos ? pr : 0.f;
+                }
+                st[v] = pr * (dpt[v] - Dq);
+            }
+            const bf16x8_t a0 = pack8(st, 0), a1 = pack8(st, 1);
+#pragma unroll
+            for (int c = 0; c < 2 * NT; ++c) {
+                if (c + 1 < 2 * NT) load_c(mt, c + 1, (c + 1) & 1);
+                else if (mt == 0) load_a(1, 0, 0);
+                CF_SCHED_FENCE();
+                acc[c % NT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c < NT ? a0 : a1, fc[c & 1], acc[c % NT], 0, 0, 0);
+                CF_SCHED_FENCE();
+            }
+        }
     };
 
     issue_kv(0, 0);
     wait_vmcnt<0>();
     lds_barrier();
     for (int kt = 0; kt < nkt; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < nkt) issue_kv(kt + 1, cur ^ 1);
+        if (kt + 1 < nkt) issue_kv(kt + 1, (kt + 1) & 1);
         if (kt * 64 <= wave_maxpos) {
-            const unsigned char* sk = smem + cur * 2 * TILE;
-            const unsigned char* sv = sk + TILE;
-            // One 32-key half of the tile at a time keeps the score registers at 2 x 16.  The LDS
-            // fragments of an MFMA are read while the previous MFMAs run (one step ahead).
-            bf16x8_t fa[2][2], fc[2];
-            auto load_a = [&](int mt, int ks, int buf) __attribute__((always_inline)) {
-                fa[buf][0] = frag_rows<D>(sk, mt * 32 + slot, ks, hh);
-                fa[buf][1] = frag_rows<D>(sv, mt * 32 + slot, ks, hh);
-            };
-            auto load_c = [&](int mt, int c, int buf) __attribute__((always_inline)) {
-                fc[buf] = frag_tokens<D>(sk, mt * 32 + 16 * (c / NT), c % NT, lane);
-            };
-            load_a(0, 0, 0);
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt) {
-                f32x16_t st, dpt;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) { st[v] = 0.f; dpt[v] = 0.f; }
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    if (ks + 1 < KS) load_a(mt, ks + 1, (ks + 1) & 1);
-                    else load_c(mt, 0, 0);
-                    CF_SCHED_FENCE();
-                    st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][0], qf[ks], st, 0, 0, 0);
-                    dpt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][1], dof[ks], dpt, 0, 0, 0);
-                    CF_SCHED_FENCE();
-                }
-                // dS^T = P^T o (dP^T - D): lane = query, register = key
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int key = kt * 64 + mt * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
-                    const float pr = key <= pos ? __builtin_amdgcn_exp2f(st[v] * scale2 - lse2) : 0.f;
-                    st[v] = pr * (dpt[v] - Dq);
-                }
-                const bf16x8_t a0 = pack8(st, 0), a1 = pack8(st, 1);
-#pragma unroll
-                for (int c = 0; c < 2 * NT; ++c) {
-                    if (c + 1 < 2 * NT) load_c(mt, c + 1, (c + 1) & 1);
-                    else if (mt == 0) load_a(1, 0, 0);
-                    CF_SCHED_FENCE();
-                    acc[c % NT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c < NT ? a0 : a1, fc[c & 1], acc[c % NT], 0, 0, 0);
-                    CF_SCHED_FENCE();
-                }
-            }
+            // a query that does not exist (a ragged last wave) has position -1 and is masked in every tile
+            const bool clear = kt * 64 + 63 <= wave_minpos && wave * 32 + 32 <= rows_in_tile;
+            const unsigned char* sk = smem + (kt & 1) * 2 * TILE;
+            if (clear) tile(ic<0>{}, kt, sk);
+            else tile(ic<1>{}, kt, sk);
         }
         wait_vmcnt<0>();
         lds_barrier();
@@ -283,6 +293,18 @@ __global__ __launch_bounds__(256, 2) void attn_dq_kernel(AttnParams p) {
 // ---------------------------------------------------------------------------
 // dK/dV kernel: one (key tile, query head) per block
 // ---------------------------------------------------------------------------
+// Slot order of an iteration of the kernel's pipeline (2*KS positions, KS "A" slots and KS "C" slots;
+// see the kernel): odd iterations alternate A, C; even iterations put all C slots into the first
+// 3*KS/2 positions, every third of which is an A slot, and the remaining A slots behind them.
+__host__ __device__ constexpr bool dkv_is_a(int KS, bool even, int p) {
+    return even ? (p < 3 * KS / 2 ? (p % 3 == 1) : true) : (p % 2 == 0);
+}
+__host__ __device__ constexpr int dkv_slot_index(int KS, bool even, int p) {
+    int n = 0;
+    for (int q = 0; q < p; ++q) n += (dkv_is_a(KS, even, q) == dkv_is_a(KS, even, p)) ? 1 : 0;
+    return n;
+}
+
 template <int D>
 __global__ __launch_bounds__(256, 1) void attn_dkv_kernel(AttnParams p) {
     constexpr int KS = D / 16, NT = D / 32;
@@ -290,7 +312,8 @@ __global__ __launch_bounds__(256, 1) void attn_dkv_kernel(AttnParams p) {
     constexpr int STAGE = 2 * TILE + 512;       // Q tile, dO tile, lse2[64], D[64]
     extern __shared__ __align__(16) unsigned char smem[];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // the wave number is the same in all lanes: saying so keeps everything derived from it in scalar registers
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int slot = lane & 31, hh = lane >> 5;
     const int G = p.Hq / p.Hkv;
     const int h = blockIdx.x % p.Hq, b = blockIdx.x / p.Hq, g = h / G;
@@ -349,175 +372,242 @@ __global__ __launch_bounds__(256, 1) void attn_dkv_kernel(AttnParams p) {
         ta[nt][0] = (unsigned)tile_off<D>(r, chunk) + (lane & 1) * 8;
         ta[nt][1] = (unsigned)tile_off<D>(r + 8, chunk) + (lane & 1) * 8;
     }
-    auto issue_q = [&](int step, int stage) {
+    // ---- global -> LDS.  Per-lane offsets of a tile's loads inside a 64-row step (row * stride +
+    // swizzled chunk) never change; the step's row offset is added per step.  Rows past the sequence
+    // end lie outside the descriptors' ranges and arrive as zeros (their statistics too), which is
+    // harmless: P = exp2(0 - 0) = 1 meets dO = 0, and dS = 1 * (0 - 0) = 0.
+    constexpr int NCH = D / 8, RPL = 64 / NCH, NLD = 64 / RPL / 4;
+    unsigned voff[NLD];
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+        const int row = (4 * i + wave) * RPL + lane / NCH;
+        const int pc = lane % NCH;
+        const int sw = (D == 128) ? (((row & 3) << 2) | ((row >> 2) & 3)) : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
+        voff[i] = (unsigned)row * (unsigned)(Nq * 2) + (unsigned)((pc ^ sw) << 4);
+    }
+    auto issue_q = [&](int step, int stage) __attribute__((always_inline)) {
         const unsigned sq = lds0 + stage * STAGE;
         const unsigned base = (unsigned)(step * 64) * (unsigned)(Nq * 2);
-        const int valid = seq_end - c0 - step * 64;
-        dma_tile<D>(sq, rsQ, base, Nq * 2, valid, wave, lane);
-        dma_tile<D>(sq + TILE, rsO, base, Nq * 2, valid, wave, lane);
-        {
-            // row statistics of the 64 queries (every wave issues the same two loads, which keeps the
-            // number of loads per wave and step equal); rows past the sequence end read zeros, which
-            // is harmless because their Q and dO rows are zero as well
-            const unsigned off = (unsigned)(step * 64 + lane) * 4u;
-            dma4(sq + 2 * TILE, rsL, off);
-            dma4(sq + 2 * TILE + 256, rsD, off);
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) dma16(__builtin_amdgcn_readfirstlane(sq + (4 * i + wave) * 1024), rsQ, base + voff[i]);
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) dma16(__builtin_amdgcn_readfirstlane(sq + TILE + (4 * i + wave) * 1024), rsO, base + voff[i]);
+        // row statistics of the 64 queries (every wave issues the same two loads, which keeps the
+        // number of loads per wave and step equal)
+        const unsigned off = (unsigned)(step * 64 + lane) * 4u;
+        dma4(sq + 2 * TILE, rsL, off);
+        dma4(sq + 2 * TILE + 256, rsD, off);
+    };
+    constexpr int LPS = 2 * NLD + 2;                // loads per wave and step
+
+    // ---- the pipeline.  The query rows go by in HALVES of 32 (two per 64-row step / LDS stage).  A
+    // half n needs three kinds of work: A(n) = S and dP (2*KS MFMAs against the wave's K and V
+    // fragments), B(n) = P and dS from them (vector ALU: exp2, mask, products, packing), C(n) = dV and
+    // dK (4*NT MFMAs).  A wave runs alone on its SIMD, so nothing overlaps unless the instruction
+    // stream interleaves it: ITERATION t issues A(t+1), B(t) and C(t-1) together, one softmax value
+    // (two at d = 64) and the LDS reads of a later slot between two MFMA pairs, so that in the steady
+    // state the matrix core runs back to back while the exponentials of the half before and the
+    // fragment reads of the slots ahead proceed under it.  Fragment reads go through a ring of four
+    // register pairs and are issued three slots ahead of their MFMAs, across iteration boundaries
+    // too (the LDS answers a read in a few hundred cycles when four waves keep it busy; a single slot
+    // of lookahead left every MFMA pair waiting for it).
+    // A slot = one MFMA pair: A slot ks = {S += Qfrag * K[ks], dP += dOfrag * V[ks]}; C slot c =
+    // {dK[nt] += dS[j] * Qtokens, dV[nt] += P[j] * dOtokens}, j = c / NT, nt = c % NT.
+    // Iterations come in pairs (even t = 2s, odd t = 2s+1) so that stage halves are compile-time.  In
+    // the even iteration all C slots come first (with a third of the A slots between them): after
+    // them no wave reads stage s-1 any more, so ONE barrier there both frees that stage for the loads
+    // of step s+3 and publishes step s+1 (awaited just before it), whose rows the odd iteration's A
+    // slots read.  Accumulation order of every output element is that of a plain loop over the rows.
+    constexpr int NP = 2 * KS;                      // slots per iteration (KS A slots, 2*NT = KS C slots)
+    constexpr int VPS = 16 / NP;                    // softmax values per slot
+    constexpr int LOOK = KS >= 8 ? 3 : 2, RING = 4;     // the reads issued for the next iteration must follow the barrier
+    static_assert(2 * NT == KS && NP % RING == 0 && (16 % NP) == 0 && NP - LOOK >= 3 * KS / 2, "slot layout");
+    typedef __attribute__((address_space(3))) unsigned char* lds_u8_ptr;
+    typedef const __attribute__((address_space(3))) u32x4_t* lds_u4_cptr;
+    typedef float f32x4v_t __attribute__((ext_vector_type(4)));
+    typedef const __attribute__((address_space(3))) f32x4v_t* lds_f4_cptr;
+    typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8_t;
+
+    f32x16_t st[2], dpt[2];                         // S / dP of the half being accumulated and of the one in B, by parity
+    bf16x8_t ap[2][2], ads[2][2];                   // packed P and dS, [half parity][16-query block]
+    bf16x8_t op[RING][2];                           // fragment pairs on their way to the MFMAs
+    f32x4v_t lqr[2], dqr[2];                        // log2(e)*LSE and D of four queries at a time, two groups in flight
+#pragma unroll
+    for (int h2 = 0; h2 < 2; ++h2)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { st[h2][v] = 0.f; dpt[h2][v] = 0.f; }
+
+    // is position p of an (even / odd) iteration an A slot, and which A or C slot is it
+    constexpr auto is_a = [](bool even, int p) constexpr { return dkv_is_a(KS, even, p); };
+    constexpr auto slot_index = [](bool even, int p) constexpr { return dkv_slot_index(KS, even, p); };
+    // reads of an A slot (row fragments of Q and dO, half hf of the stage at sb) or of a C slot (token
+    // fragments) into ring entry r
+    auto read_a = [&](unsigned sb, int hf, int ks, int r) __attribute__((always_inline)) {
+        const lds_u8_ptr q = reinterpret_cast<lds_u8_ptr>(sb + ra[ks]);
+        op[r][0] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<lds_u4_cptr>(q + hf * 32 * (D * 2)));
+        op[r][1] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<lds_u4_cptr>(q + (TILE + hf * 32 * (D * 2))));
+    };
+    auto read_c = [&](unsigned sb, int hf, int c, int r) __attribute__((always_inline)) {
+        const int j = c / NT, nt = c % NT;
+        const lds_u8_ptr lo = reinterpret_cast<lds_u8_ptr>(sb + ta[nt][0]);
+        const lds_u8_ptr hi = reinterpret_cast<lds_u8_ptr>(sb + ta[nt][1]);
+        const int off = (hf * 32 + 16 * j) * (D * 2);
+        const s16x4_t q0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lo + off));
+        const s16x4_t q1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(hi + off));
+        const s16x4_t o0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lo + (TILE + off)));
+        const s16x4_t o1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(hi + (TILE + off)));
+        op[r][0] = __builtin_bit_cast(bf16x8_t, (s16x8_t)__builtin_shufflevector(q0, q1, 0, 1, 2, 3, 4, 5, 6, 7));
+        op[r][1] = __builtin_bit_cast(bf16x8_t, (s16x8_t)__builtin_shufflevector(o0, o1, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    // statistics of queries [4*g4, 4*g4 + 4) (+ 4*hh per lane half) of half hf of the stage at sb
+    auto read_stats = [&](unsigned sb, int hf, int g4, int buf) __attribute__((always_inline)) {
+        const lds_u8_ptr ps = reinterpret_cast<lds_u8_ptr>(sb + 2 * TILE + 16 * hh);
+        lqr[buf] = *reinterpret_cast<lds_f4_cptr>(ps + (hf * 32 + 8 * g4) * 4);
+        dqr[buf] = *reinterpret_cast<lds_f4_cptr>(ps + (64 + hf * 32 + 8 * g4) * 4);
+    };
+    // P and dS of value v (query 8*(v/4) + 4*hh + v%4 of half t): lane = key, register = query
+    auto soft = [&](int par, int v, int qrow0, auto MASKED) __attribute__((always_inline)) {
+        constexpr bool masked = decltype(MASKED)::value != 0;
+        const int v4 = v >> 2, e = v & 3;
+        const float lv = lqr[v4 & 1][e], dd = dqr[v4 & 1][e];
+        float pr = __builtin_amdgcn_exp2f(st[par][v] * scale2 - lv);
+        if (masked) {
+            const bool ok = kvalid && (qrow0 + 8 * v4 + 4 * hh + e >= jk);
+            pr = ok ? pr : 0.f;
+        }
+        st[par][v] = pr;
+        dpt[par][v] = pr * (dpt[par][v] - dd);
+        if ((v & 7) == 7) {                          // a 16-query block (8 registers) is complete
+            ap[par][v >> 3] = pack8(st[par], v >> 3);
+            ads[par][v >> 3] = pack8(dpt[par], v >> 3);
         }
     };
+    // One iteration (see above).  KIND 0: steady state; 1: the very first iteration (no half before it:
+    // the C slots' MFMAs are left out, their reads are harmless); 2: the drain after the last half
+    // (only the C slots' MFMAs).
+    auto iteration = [&](auto EVEN_, auto MASKED, auto KIND_, const int s) __attribute__((always_inline)) {
+        constexpr bool EVEN = decltype(EVEN_)::value != 0;
+        constexpr int KIND = decltype(KIND_)::value;
+        constexpr int hfA = EVEN ? 1 : 0, hfB = EVEN ? 0 : 1, hfC = EVEN ? 1 : 0;
+        constexpr int parA = EVEN ? 1 : 0, parB = EVEN ? 0 : 1, parC = EVEN ? 1 : 0;    // parity of halves t+1, t, t-1
+        const unsigned sbA = lds0 + (unsigned)((EVEN ? s : s + 1) & 3) * STAGE;
+        const unsigned sbB = lds0 + (unsigned)(s & 3) * STAGE;
+        const unsigned sbC = lds0 + (unsigned)((EVEN ? s + 3 : s) & 3) * STAGE;
+        // the iteration after this one (the fragment reads of its first slots are issued here)
+        constexpr int hfA_n = EVEN ? 0 : 1, hfB_n = EVEN ? 1 : 0, hfC_n = EVEN ? 0 : 1;
+        const unsigned sbA_n = lds0 + (unsigned)((s + 1) & 3) * STAGE;
+        const unsigned sbB_n = lds0 + (unsigned)((EVEN ? s : s + 1) & 3) * STAGE;
+        const unsigned sbC_n = lds0 + (unsigned)(s & 3) * STAGE;
+        const int qrow0 = c0 + (2 * s + (EVEN ? 0 : 1)) * 32;       // compact row of the first query of half t
+        static_for<NP>([&](auto P) __attribute__((always_inline)) {
+            constexpr int pp = decltype(P)::value;
+            if constexpr (EVEN && pp == 3 * KS / 2 && KIND != 2) {
+                // every C slot of this iteration has its fragments: nobody reads stage s-1 any more
+                wait_vmcnt<LPS>();          // step s+1 has landed; step s+2 may be in flight
+                lds_barrier();
+                issue_q(s + 3, (s + 3) & 3);
+            }
+            // fragment reads of the slot LOOK positions ahead
+            {
+                constexpr int q = pp + LOOK;
+                if constexpr (q < NP) {
+                    if constexpr (is_a(EVEN, q)) read_a(sbA, hfA, slot_index(EVEN, q), q % RING);
+                    else read_c(sbC, hfC, slot_index(EVEN, q), q % RING);
+                } else if constexpr (KIND != 2) {
+                    constexpr int qn = q - NP;
+                    if constexpr (is_a(!EVEN, qn)) read_a(sbA_n, hfA_n, slot_index(!EVEN, qn), q % RING);
+                    else read_c(sbC_n, hfC_n, slot_index(!EVEN, qn), q % RING);
+                }
+            }
+            if constexpr (KIND != 2) {
+                // softmax values of half t, with the statistics of the next four queries fetched one group ahead
+#pragma unroll
+                for (int e = 0; e < VPS; ++e) {
+                    const int v = pp * VPS + e;
+                    if ((v & 3) == 0) {
+                        if (v < 12) read_stats(sbB, hfB, (v >> 2) + 1, ((v >> 2) + 1) & 1);
+                        else read_stats(sbB_n, hfB_n, 0, 0);
+                    }
+                    soft(parB, v, qrow0, MASKED);
+                }
+            }
+            CF_SCHED_FENCE();
+            if constexpr (is_a(EVEN, pp)) {
+                if constexpr (KIND != 2) {
+                    constexpr int ks = slot_index(EVEN, pp);
+                    if constexpr (ks == 0) {
+                        f32x16_t z;
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) z[v] = 0.f;
+                        st[parA] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[pp % RING][0], kf[ks], z, 0, 0, 0);
+                        dpt[parA] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[pp % RING][1], vf[ks], z, 0, 0, 0);
+                    } else {
+                        st[parA] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[pp % RING][0], kf[ks], st[parA], 0, 0, 0);
+                        dpt[parA] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[pp % RING][1], vf[ks], dpt[parA], 0, 0, 0);
+                    }
+                }
+            } else {
+                if constexpr (KIND != 1) {
+                    constexpr int c = slot_index(EVEN, pp), j = c / NT, nt = c % NT;
+                    dk[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ads[parC][j], op[pp % RING][0], dk[nt], 0, 0, 0);
+                    dv[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[parC][j], op[pp % RING][1], dv[nt], 0, 0, 0);
+                }
+            }
+            CF_SCHED_FENCE();
+        });
+    };
 
-    // Ring of four stages: the loads of step s+3 are issued at the top of step s, into the stage that
-    // step s-1 used.  Steps past the end are issued as well (every row out of range: zero fill), so
-    // the number of loads in flight is the same in every iteration.
-    constexpr int LPS = 2 * (D / 32) + 2;           // loads per wave and step
+    // Ring of four stages: the loads of step s+3 are issued in pair s, into the stage that step s-1
+    // used.  Steps past the end are issued as well (every row out of range: zero fill), so the number
+    // of loads in flight is the same in every pair.
     issue_q(0, 0);
     issue_q(1, 1);
     issue_q(2, 2);
-    wait_vmcnt<2 * LPS>();
-    lds_barrier();
-    // One step = 64 queries.  MASKED: the step may hold queries that lie before some of the tile's
-    // keys (the first two steps of a tile) or the tile has fewer than 128 keys; every later step of a
-    // full tile sees all of its keys and spends no instruction on the mask.
-    auto step_body = [&](const int step, auto MASKED) __attribute__((always_inline)) {
-        constexpr bool masked = decltype(MASKED)::value != 0;
-        const int cur = step & 3;
-        issue_q(step + 3, (step + 3) & 3);
-        const int qbase = c0 + step * 64;
-        // every wave works on every step: a wave whose keys all lie after the step's queries (first
-        // step of a tile) or past the sequence end multiplies zeros, which costs less than keeping
-        // the accumulators live across a branch
-        {
-            typedef __attribute__((address_space(3))) unsigned char* lds_u8_ptr;
-            typedef const __attribute__((address_space(3))) u32x4_t* lds_u4_cptr;
-            typedef float f32x4v_t __attribute__((ext_vector_type(4)));
-            typedef const __attribute__((address_space(3))) f32x4v_t* lds_f4_cptr;
-            const unsigned sq = lds0 + cur * STAGE;         // Q tile; the dO tile follows at + TILE, the statistics at + 2*TILE
-            lds_u8_ptr pra[KS], pta[NT][2];
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) pra[ks] = reinterpret_cast<lds_u8_ptr>(sq + ra[ks]);
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                pta[nt][0] = reinterpret_cast<lds_u8_ptr>(sq + ta[nt][0]);
-                pta[nt][1] = reinterpret_cast<lds_u8_ptr>(sq + ta[nt][1]);
-            }
-            const lds_u8_ptr psl = reinterpret_cast<lds_u8_ptr>(sq + 2 * TILE + 16 * hh);
-            // The tile is two halves of 32 queries (h = 0, 1).  Per half: A(h) = S and dP (2*KS MFMAs),
-            // B(h) = P and dS from them (vector ALU: exp2, masks, products), C(h) = dV and dK (4*NT
-            // MFMAs).  A wave runs alone on its SIMD, so the three kinds of work are software-pipelined
-            // by hand:   A(0) | A(1) + B(0) | C(0) + B(1) | C(1)
-            // with a few vector instructions and the LDS reads of the next MFMA pair placed between two
-            // MFMA pairs, which keeps the matrix core fed while the exponentials are computed.
-            constexpr int VPP = 16 / KS;                    // softmax values per MFMA pair
-            f32x16_t st[2], dpt[2];
-            bf16x8_t fa[2][2], fc[2][2];                    // [buffer][Q / dO]: row and token fragments
-            float4 lq[4], dq4[4];                           // log2(e)*LSE and D of the current half's queries, in groups of 4
-            bf16x8_t ap[2][2], ads[2][2];                   // packed P and dS, [half][16-query block]
-            // h, ks, c are compile-time after unrolling: every address is a register plus an immediate
-            auto load_a = [&](int h, int ks, int buf) __attribute__((always_inline)) {
-                fa[buf][0] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<lds_u4_cptr>(pra[ks] + h * 32 * (D * 2)));
-                fa[buf][1] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<lds_u4_cptr>(pra[ks] + (TILE + h * 32 * (D * 2))));
-                (void)buf;
-            };
-            auto tokens = [&](int nt, int off) __attribute__((always_inline)) {
-                typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8_t;
-                const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(pta[nt][0] + off));
-                const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(pta[nt][1] + off));
-                return __builtin_bit_cast(bf16x8_t, (s16x8_t)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-            };
-            auto load_c = [&](int h, int c, int buf) __attribute__((always_inline)) {
-                const int j = c / NT, nt = c % NT;
-                fc[buf][0] = tokens(nt, (h * 32 + 16 * j) * (D * 2));
-                fc[buf][1] = tokens(nt, TILE + (h * 32 + 16 * j) * (D * 2));
-            };
-            auto load_stats = [&](int h) __attribute__((always_inline)) {
-#pragma unroll
-                for (int v4 = 0; v4 < 4; ++v4) {
-                    const f32x4v_t a = *reinterpret_cast<lds_f4_cptr>(psl + (h * 32 + 8 * v4) * 4);
-                    const f32x4v_t c = *reinterpret_cast<lds_f4_cptr>(psl + (64 + h * 32 + 8 * v4) * 4);
-                    lq[v4] = make_float4(a.x, a.y, a.z, a.w);
-                    dq4[v4] = make_float4(c.x, c.y, c.z, c.w);
-                }
-            };
-            auto mma_a = [&](int h, int ks, int buf) __attribute__((always_inline)) {
-                st[h] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][0], kf[ks], st[h], 0, 0, 0);
-                dpt[h] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][1], vf[ks], dpt[h], 0, 0, 0);
-            };
-            auto mma_c = [&](int h, int c, int buf) __attribute__((always_inline)) {
-                const int j = c / NT, nt = c % NT;
-                dk[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ads[h][j], fc[buf][0], dk[nt], 0, 0, 0);
-                dv[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[h][j], fc[buf][1], dv[nt], 0, 0, 0);
-            };
-            // P and dS of value v (query 8*(v/4) + 4*hh + v%4 of the half): lane = key, register = query
-            auto soft = [&](int h, int v) __attribute__((always_inline)) {
-                const int v4 = v >> 2, e = v & 3;
-                const float lv = e == 0 ? lq[v4].x : (e == 1 ? lq[v4].y : (e == 2 ? lq[v4].z : lq[v4].w));
-                const float dd = e == 0 ? dq4[v4].x : (e == 1 ? dq4[v4].y : (e == 2 ? dq4[v4].z : dq4[v4].w));
-                float pr = __builtin_amdgcn_exp2f(st[h][v] * scale2 - lv);
-                if (masked) {
-                    const bool ok = kvalid && (qbase + h * 32 + 8 * v4 + 4 * hh + e >= jk);
-                    pr = ok ? pr : 0.f;
-                }
-                st[h][v] = pr;
-                dpt[h][v] = pr * (dpt[h][v] - dd);
-                if ((v & 7) == 7) {                          // a 16-query block (8 registers) is complete
-                    ap[h][v >> 3] = pack8(st[h], v >> 3);
-                    ads[h][v >> 3] = pack8(dpt[h], v >> 3);
-                }
-            };
-#pragma unroll
-            for (int h = 0; h < 2; ++h)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) { st[h][v] = 0.f; dpt[h][v] = 0.f; }
-            // ---- A(0)
-            load_a(0, 0, 0);
-            load_stats(0);
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                if (ks + 1 < KS) load_a(0, ks + 1, (ks + 1) & 1);
-                else load_a(1, 0, (ks + 1) & 1);
-                CF_SCHED_FENCE();
-                mma_a(0, ks, ks & 1);
-                CF_SCHED_FENCE();
-            }
-            // ---- A(1) + B(0)
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                if (ks + 1 < KS) load_a(1, ks + 1, (KS + ks + 1) & 1);
-                else load_c(0, 0, 0);
-#pragma unroll
-                for (int e = 0; e < VPP; ++e) soft(0, ks * VPP + e);
-                CF_SCHED_FENCE();
-                mma_a(1, ks, (KS + ks) & 1);
-                CF_SCHED_FENCE();
-            }
-            // ---- C(0) + B(1)
-            load_stats(1);
-#pragma unroll
-            for (int c = 0; c < 2 * NT; ++c) {
-                if (c + 1 < 2 * NT) load_c(0, c + 1, (c + 1) & 1);
-                else load_c(1, 0, (c + 1) & 1);
-#pragma unroll
-                for (int e = 0; e < VPP; ++e) soft(1, c * VPP + e);
-                CF_SCHED_FENCE();
-                mma_c(0, c, c & 1);
-                CF_SCHED_FENCE();
-            }
-            // ---- C(1)
-#pragma unroll
-            for (int c = 0; c < 2 * NT; ++c) {
-                if (c + 1 < 2 * NT) load_c(1, c + 1, (2 * NT + c + 1) & 1);
-                CF_SCHED_FENCE();
-                mma_c(1, c, (2 * NT + c) & 1);
-                CF_SCHED_FENCE();
-            }
-        }
-        wait_vmcnt<2 * LPS>();          // step + 1 has landed; steps + 2 and + 3 may be in flight
-        lds_barrier();
-    };
-    const int masked_steps = keys_in_tile < 128 ? steps : min(steps, 2);
-    int step = 0;
-    for (; step < masked_steps; ++step) step_body(step, ic<1>{});
-    for (; step < steps; ++step) step_body(step, ic<0>{});
+    // Everything is waited for here, not only stage 0: the K and V fragments above come from ordinary
+    // loads, and as long as the compiler cannot see them completed ahead of the loop it guards their
+    // first use inside the loop with a wait of its own, which the hardware applies to the loads just
+    // issued as well: every pair would then wait out a whole global-memory latency.
     wait_vmcnt<0>();
+    lds_barrier();
+    // head: A(0), then the statistics group and the fragment reads that the first iteration starts with
+    {
+        f32x16_t z;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) z[v] = 0.f;
+        st[0] = z;
+        dpt[0] = z;
+        static_for<KS>([&](auto K_) __attribute__((always_inline)) {
+            constexpr int ks = decltype(K_)::value;
+            read_a(lds0, 0, ks, ks % RING);
+            st[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[ks % RING][0], kf[ks], st[0], 0, 0, 0);
+            dpt[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[ks % RING][1], vf[ks], dpt[0], 0, 0, 0);
+        });
+        read_stats(lds0, 0, 0, 0);
+        static_for<LOOK>([&](auto Q_) __attribute__((always_inline)) {
+            constexpr int q = decltype(Q_)::value;
+            if constexpr (is_a(true, q)) read_a(lds0, 1, slot_index(true, q), q % RING);
+            else read_c(lds0 + 3 * STAGE, 1, slot_index(true, q), q % RING);      // a half that does not exist: never used
+        });
+        CF_SCHED_FENCE();
+    }
+    // MASKED: the pair may hold queries that lie before some of the tile's keys (the first two steps
+    // of a tile) or the tile has fewer than 128 keys; every later pair of a full tile sees all of its
+    // keys and spends no instruction on the mask.
+    const int masked_steps = keys_in_tile < 128 ? steps : min(steps, 2);
+    iteration(ic<1>{}, ic<1>{}, ic<1>{}, 0);
+    iteration(ic<0>{}, ic<1>{}, ic<0>{}, 0);
+    int s = 1;
+    for (; s < masked_steps; ++s) {
+        iteration(ic<1>{}, ic<1>{}, ic<0>{}, s);
+        iteration(ic<0>{}, ic<1>{}, ic<0>{}, s);
+    }
+    for (; s < steps; ++s) {
+        iteration(ic<1>{}, ic<0>{}, ic<0>{}, s);
+        iteration(ic<0>{}, ic<0>{}, ic<0>{}, s);
+    }
+    iteration(ic<1>{}, ic<0>{}, ic<2>{}, steps);     // drain: C of the last half
+    wait_vmcnt<0>();
+
 
     if (G == 1) {
 #pragma unroll

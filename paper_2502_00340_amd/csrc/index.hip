@@ -49,58 +49,18 @@ __device__ __forceinline__ int block_sum_256(int v, int* red) {
     return red[0] + red[1] + red[2] + red[3];
 }
 
-__global__ __launch_bounds__(IDX_THREADS) void mask_count_kernel(const uint8_t* __restrict__ mask,
-                                                                 int64_t T, int aligned,
-                                                                 int32_t* __restrict__ block_count) {
-    __shared__ int red[4];
-    unsigned w[4];
-    int64_t t0 = (int64_t)blockIdx.x * IDX_CHUNK + (int64_t)threadIdx.x * IDX_PER_THREAD;
-    load_flags(mask, t0, T, aligned != 0, w);
-    int total = block_sum_256(count_flags(w), red);
-    if (threadIdx.x == 0) block_count[blockIdx.x] = total;
-}
-
-// Exclusive prefix sum of the per-block counts, in place: one block, each thread owns a
-// contiguous run of the array.
-__global__ __launch_bounds__(1024) void block_scan_kernel(int32_t* __restrict__ block_count, int nblk) {
-    __shared__ int part[1024];
-    const int tid = threadIdx.x;
-    const int per = (nblk + 1023) / 1024;
-    const int lo = min(tid * per, nblk), hi = min(lo + per, nblk);
-    int s = 0;
-    for (int i = lo; i < hi; ++i) s += block_count[i];
-    part[tid] = s;
-    __syncthreads();
-    for (int o = 1; o < 1024; o <<= 1) {        // Hillis-Steele inclusive scan of the 1024 run totals
-        const int v = tid >= o ? part[tid - o] : 0;
-        __syncthreads();
-        part[tid] += v;
-        __syncthreads();
-    }
-    int run = part[tid] - s;                    // exclusive
-    for (int i = lo; i < hi; ++i) {
-        const int c = block_count[i];
-        block_count[i] = run;
-        run += c;
-    }
-}
-
-// block_count == nullptr: every block counts the mask bytes before its chunk itself
-// (only used for a handful of blocks); otherwise block_count[b] holds the number of kept
-// tokens before chunk b.
+// Masks of a handful of chunks (up to IDX_SELF_COUNT_MAX_BLOCKS, i.e. every layer-sized batch): one
+// launch, no scratch; every block counts the mask bytes before its chunk itself.
 __global__ __launch_bounds__(IDX_THREADS) void mask_scatter_kernel(
     const uint8_t* __restrict__ mask, int64_t T, int S, int B, int aligned,
-    const int32_t* __restrict__ block_count, int32_t* __restrict__ idx,
-    int32_t* __restrict__ cu_kept, int32_t* __restrict__ n_kept_dev) {
+    int32_t* __restrict__ idx, int32_t* __restrict__ cu_kept, int32_t* __restrict__ n_kept_dev) {
     __shared__ int red[4];
     __shared__ int wave_tot[4];
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
 
     int base;
-    if (block_count != nullptr) {
-        base = block_count[blockIdx.x];
-    } else {
+    {
         int before = 0;
         unsigned w[4];
         for (int c = 0; c < (int)blockIdx.x; ++c) {
@@ -147,10 +107,103 @@ __global__ __launch_bounds__(IDX_THREADS) void mask_scatter_kernel(
     }
 }
 
+// ---------------------------------------------------------------------------
+// Masks of more than a handful of chunks: two launches over SPANS of IDX_SPAN_CHUNKS chunks (8192
+// tokens), one block per span.  The first counts the kept tokens of every span; the second has every block add up the counts of the spans before its own
+// (two thousand numbers for 16 M tokens, read by all threads at once: no scan kernel, no waiting on
+// other blocks) and then compact its span chunk by chunk: flags -> wave / block scan -> the chunk's
+// kept positions gathered in LDS -> full 256-byte lines out.  The second pass over the mask finds it
+// in the memory-side cache.
+// (A single-pass chained scan with decoupled look-back was measured as well: one status word per chunk
+// has to cross from one XCD's L2 to another's through memory, about a microsecond per hop, and the chain
+// of hops made it slower than the two launches: 70 us against 45 us for 16 M tokens.)
+// ---------------------------------------------------------------------------
+static constexpr int IDX_SPAN_CHUNKS = 2;
+static constexpr int64_t IDX_SPAN = (int64_t)IDX_SPAN_CHUNKS * IDX_CHUNK;
+
+__global__ __launch_bounds__(IDX_THREADS) void mask_span_count_kernel(const uint8_t* __restrict__ mask, int64_t T,
+                                                                      int aligned, int32_t* __restrict__ span_count) {
+    __shared__ int red[4];
+    const int64_t s0 = (int64_t)blockIdx.x * IDX_SPAN + (int64_t)threadIdx.x * IDX_PER_THREAD;
+    unsigned w[IDX_SPAN_CHUNKS][4];
+#pragma unroll
+    for (int c = 0; c < IDX_SPAN_CHUNKS; ++c) load_flags(mask, s0 + (int64_t)c * IDX_CHUNK, T, aligned != 0, w[c]);
+    int n = 0;
+#pragma unroll
+    for (int c = 0; c < IDX_SPAN_CHUNKS; ++c) n += count_flags(w[c]);
+    const int total = block_sum_256(n, red);
+    if (threadIdx.x == 0) span_count[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(IDX_THREADS) void mask_span_scatter_kernel(
+    const uint8_t* __restrict__ mask, int64_t T, int S, int B, int aligned,
+    const int32_t* __restrict__ span_count, int32_t* __restrict__ idx, int32_t* __restrict__ cu_kept,
+    int32_t* __restrict__ n_kept_dev) {
+    __shared__ int red[4];
+    __shared__ int wave_tot[4];
+    __shared__ int32_t staged[IDX_CHUNK];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    // the span's mask bytes are requested first: they are on their way while the counts are added up
+    unsigned wall[IDX_SPAN_CHUNKS][4];
+#pragma unroll
+    for (int c = 0; c < IDX_SPAN_CHUNKS; ++c)
+        load_flags(mask, (int64_t)blockIdx.x * IDX_SPAN + (int64_t)c * IDX_CHUNK + (int64_t)tid * IDX_PER_THREAD, T,
+                   aligned != 0, wall[c]);
+    int before = 0;
+    for (int i = tid; i < (int)blockIdx.x; i += IDX_THREADS) before += span_count[i];
+    int base = block_sum_256(before, red);          // kept tokens in all spans before this one
+
+#pragma unroll
+    for (int c = 0; c < IDX_SPAN_CHUNKS; ++c) {
+        const int64_t t0 = (int64_t)blockIdx.x * IDX_SPAN + (int64_t)c * IDX_CHUNK + (int64_t)tid * IDX_PER_THREAD;
+        if ((int64_t)blockIdx.x * IDX_SPAN + (int64_t)c * IDX_CHUNK >= T) break;         // uniform: past the mask's end
+        const unsigned (&w)[4] = wall[c];
+        const int cnt = count_flags(w);
+        int incl = cnt;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int n = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += n;
+        }
+        __syncthreads();                            // the previous chunk's staged positions and totals have been read
+        if (lane == 63) wave_tot[wave] = incl;
+        __syncthreads();
+        int wave_base = 0;
+        for (int i = 0; i < wave; ++i) wave_base += wave_tot[i];
+        const int total = wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
+        int pos = wave_base + incl - cnt;           // kept tokens of this chunk before this thread's 16
+        if (t0 < T) {
+            // T <= 2^30: token numbers fit 32 bits.  Sequence starts inside these 16 tokens (none, as a rule:
+            // only then is the division's result used) get their prefix count; bytes past T were read as zero.
+            const unsigned u0 = (unsigned)t0;
+            unsigned b = (u0 + (unsigned)S - 1u) / (unsigned)S;          // first sequence that starts at or after u0
+            unsigned next_start = b * (unsigned)S;
+#pragma unroll
+            for (int e = 0; e < IDX_PER_THREAD; ++e) {
+                const unsigned t = u0 + e;
+                if (t == next_start && t < (unsigned)T) {
+                    cu_kept[b] = base + pos;
+                    ++b;
+                    next_start += (unsigned)S;
+                }
+                if ((w[e >> 2] >> (8 * (e & 3))) & 0xFFu) staged[pos++] = (int32_t)t;
+            }
+            if (t0 + IDX_PER_THREAD >= T) {         // this thread owns token T-1
+                cu_kept[B] = base + pos;
+                if (n_kept_dev != nullptr) *n_kept_dev = base + pos;
+            }
+        }
+        __syncthreads();
+        for (int i = tid; i < total; i += IDX_THREADS) idx[base + i] = staged[i];
+        base += total;
+    }
+}
+
 size_t index_ws_bytes(int64_t n_tokens) {
-    int64_t nblk = (n_tokens + IDX_CHUNK - 1) / IDX_CHUNK;
-    if (nblk < 1) nblk = 1;
-    return align_up((size_t)nblk * sizeof(int32_t), 256);
+    int64_t nspan = (n_tokens + IDX_SPAN - 1) / IDX_SPAN;
+    if (nspan < 1) nspan = 1;
+    return align_up((size_t)nspan * sizeof(int32_t), 256);      // one count per span
 }
 
 hipError_t launch_keep_index(const uint8_t* mask, int B, int S, int32_t* idx, int32_t* cu_kept,
@@ -159,14 +212,13 @@ hipError_t launch_keep_index(const uint8_t* mask, int B, int S, int32_t* idx, in
     const int nblk = ceil_div(T, IDX_CHUNK);
     const int aligned = ((uintptr_t)mask % 16 == 0) ? 1 : 0;
     if (nblk <= IDX_SELF_COUNT_MAX_BLOCKS) {
-        mask_scatter_kernel<<<nblk, IDX_THREADS, 0, st>>>(mask, T, S, B, aligned, nullptr, idx,
-                                                          cu_kept, n_kept_dev);
+        mask_scatter_kernel<<<nblk, IDX_THREADS, 0, st>>>(mask, T, S, B, aligned, idx, cu_kept, n_kept_dev);
     } else {
-        int32_t* block_count = static_cast<int32_t*>(ws);
-        mask_count_kernel<<<nblk, IDX_THREADS, 0, st>>>(mask, T, aligned, block_count);
-        block_scan_kernel<<<1, 1024, 0, st>>>(block_count, nblk);
-        mask_scatter_kernel<<<nblk, IDX_THREADS, 0, st>>>(mask, T, S, B, aligned, block_count, idx,
-                                                          cu_kept, n_kept_dev);
+        const int nspan = ceil_div(T, IDX_SPAN);
+        int32_t* span_count = static_cast<int32_t*>(ws);
+        mask_span_count_kernel<<<nspan, IDX_THREADS, 0, st>>>(mask, T, aligned, span_count);
+        mask_span_scatter_kernel<<<nspan, IDX_THREADS, 0, st>>>(mask, T, S, B, aligned, span_count, idx, cu_kept,
+                                                                n_kept_dev);
     }
     return hipGetLastError();
 }
@@ -176,10 +228,10 @@ hipError_t launch_keep_index(const uint8_t* mask, int B, int S, int32_t* idx, in
 // counts live in a file-scope device array.  Every GPU holds its own copy of the array at its own
 // address; host code never uses the array's name as a pointer but looks its address up once per
 // device (with that device current) and passes that pointer to the kernels.  The kernels write
-// every entry they later read (block b's count, b < number of blocks), so nothing has to be
-// cleared between calls; calls that overlap on one GPU share the array and race.
+// every entry they later read (span b's count, b < number of spans), so nothing has to be cleared
+// between calls; calls that overlap on one GPU share the array and race.
 // ---------------------------------------------------------------------------
-static __device__ __align__(256) int32_t scratch[IDX_STATIC_MAX_TOKENS / IDX_CHUNK];
+static __device__ __align__(256) int32_t scratch[IDX_STATIC_MAX_TOKENS / IDX_SPAN];
 
 hipError_t launch_keep_index_static(const uint8_t* mask, int B, int S, int32_t* idx, int32_t* cu_kept,
                                     int32_t* n_kept_dev, hipStream_t st) {
