@@ -328,30 +328,52 @@ def parts_leg(shape: WL.LayerShape, sv, W, dy, mask: np.ndarray, mask_dev, reps:
     return out
 
 
+def make_inputs_device(shape: WL.LayerShape, seed: int):
+    """The same distributions as make_inputs, drawn on the GPU (timing-only legs at long contexts, where the
+    host generator would take minutes): weights N(0, 0.02^2), gains 1 + N(0, 0.02^2), activations and
+    upstream gradient N(0, 1); attn_out and lse from the forward fixture."""
+    g = torch.Generator(device=DEV)
+    g.manual_seed(seed)
+    dt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+    rn = lambda *s: torch.randn(*s, device=DEV, generator=g, dtype=torch.float32)
+    H, F, Nq, Nkv, T = shape.H, shape.F, shape.Nq, shape.Nkv, shape.T
+    W = {"wq": rn(H, Nq) * 0.02, "wk": rn(H, Nkv) * 0.02, "wv": rn(H, Nkv) * 0.02, "wo": rn(Nq, H) * 0.02,
+         "wg": rn(H, F) * 0.02, "wu": rn(H, F) * 0.02, "wd": rn(F, H) * 0.02,
+         "g1": 1.0 + 0.02 * rn(H), "g2": 1.0 + 0.02 * rn(H)}
+    W = {k: v.to(dt) for k, v in W.items()}
+    sv = {"x": rn(T, H).to(dt), "r": rn(T, H).to(dt), "q": rn(T, Nq).to(dt), "k": rn(T, Nkv).to(dt),
+          "v": rn(T, Nkv).to(dt), "gate": rn(T, F).to(dt), "up": rn(T, F).to(dt)}
+    sv["attn_out"], sv["lse"] = forward_fixture(sv["q"], sv["k"], sv["v"], shape)
+    dy = rn(T, H).to(dt)
+    return W, sv, dy
+
+
 def context_sweep_leg(base: WL.LayerShape, steps: int, warmup: int):
-    """Filtered vs dense layer backward at a fixed token count T and keep ratio 0.5 for context
-    lengths from 1K to 8K (the paper's context-length experiment, Sec. 5.3, at layer level), and a
-    fine keep-ratio sweep at the base context length."""
+    """The layer-level form of the paper's context-length and filtering-ratio experiments (Sec. 5.3):
+    filtered vs dense layer backward at keep ratio 0.5 for context lengths 1K .. 32K (T = 8192 tokens up to
+    S = 8K, then one sequence of S tokens), and keep ratios 0.1 .. 1.0 at the shape's own context length."""
     import dataclasses
     out = {"by_context": {}, "by_ratio": {}}
-    T = base.T
-    for S in (1024, 2048, 4096, 8192):
+    for S in (1024, 2048, 4096, 8192, 16384, 32768):
+        T = max(8192, S)
         shape = dataclasses.replace(base, B=T // S, S=S, mask_kind="topk")
-        W, sv, dy, mask, rng = make_inputs(shape, 7)
-        md = torch.from_numpy(mask).to(DEV)
+        W, sv, dy = make_inputs_device(shape, 7 + S)
+        rng = np.random.default_rng(S)
+        md = torch.from_numpy(WL.mask_topk(rng, shape.B, shape.S, 0.5)).to(DEV)
         desc = Bn.make_desc(shape.B, shape.S, shape.H, shape.Hq, shape.Hkv, shape.d, shape.F, shape.dtype)
         plan = Bn.LayerBackward(desc, device=DEV)
-        t_f = time_steps(lambda: plan.filtered_async(sv, W, dy, md), steps, warmup)
-        t_d = time_steps(lambda: plan.dense(sv, W, dy), steps, warmup)
-        out["by_context"][str(S)] = {"B": shape.B, "filtered_ms": round(t_f * 1e3, 4), "dense_ms": round(t_d * 1e3, 4),
-                                     "speedup": round(t_d / t_f, 4)}
-        log("context %d: filtered %.3f ms dense %.3f ms speedup %.3f" % (S, t_f * 1e3, t_d * 1e3, t_d / t_f))
-        if S == base.S:
+        st = max(3, steps // 2) if S > 8192 else steps
+        t_f = time_steps(lambda: plan.filtered_async(sv, W, dy, md), st, warmup)
+        t_d = time_steps(lambda: plan.dense(sv, W, dy), st, warmup)
+        out["by_context"][str(S)] = {"B": shape.B, "tokens": T, "filtered_ms": round(t_f * 1e3, 4),
+                                     "dense_ms": round(t_d * 1e3, 4), "speedup": round(t_d / t_f, 4)}
+        log("%s context %d (T=%d): filtered %.3f ms dense %.3f ms speedup %.3f" % (base.name, S, T, t_f * 1e3, t_d * 1e3, t_d / t_f))
+        if S == base.S and T == base.T:
             for rho in (0.1, 0.2, 0.3, 0.4, 0.5, 0.6, 0.7, 0.8, 0.9, 1.0):
-                m = WL.mask_topk(rng, shape.B, shape.S, rho)
-                mdd = torch.from_numpy(m).to(DEV)
+                mdd = torch.from_numpy(WL.mask_topk(rng, shape.B, shape.S, rho)).to(DEV)
                 t = time_steps(lambda: plan.filtered_async(sv, W, dy, mdd), steps, warmup)
                 out["by_ratio"]["%.1f" % rho] = {"ms": round(t * 1e3, 4), "speedup": round(t_d / t, 4)}
+                log("%s keep ratio %.1f: %.3f ms speedup %.3f" % (base.name, rho, t * 1e3, t_d / t))
         del plan, W, sv, dy
         torch.cuda.empty_cache()
     return out
@@ -444,7 +466,9 @@ def main():
     ap.add_argument("--stack", type=int, default=0, metavar="L",
                     help="also time a stack of L layers chained through the compact entry point")
     ap.add_argument("--context-sweep", action="store_true",
-                    help="also time context lengths 1K..8K at fixed token count and keep ratios 0.1..1.0 (slow)")
+                    help="also time context lengths 1K..32K and keep ratios 0.1..1.0 on the bench config (slow)")
+    ap.add_argument("--sweep-configs", default="", metavar="I,J,..",
+                    help="run ONLY the context-length and keep-ratio sweeps, on these configs (e.g. 1,2,3,4), and print them")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU only (collectives and sharding are out of scope); "
@@ -456,6 +480,12 @@ def main():
     Bn.lib()        # fail loudly if the HIP library is missing
 
     shape = WL.CONFIGS[a.config]
+    if a.sweep_configs:
+        res = {}
+        for ci in [int(x) for x in a.sweep_configs.split(",")]:
+            res["config %d %s" % (ci, WL.CONFIGS[ci].name)] = context_sweep_leg(WL.CONFIGS[ci], a.steps, a.warmup)
+        print(json.dumps({"context_and_ratio_sweeps": res}), flush=True)
+        return
     if a.only_roofline:
         n_k = shape.B * WL.topk_count(shape.rho, shape.S)
         print(json.dumps({"roofline": roofline_leg(shape, n_k), "hbm_copy_ceiling": copy_ceiling_leg()}), flush=True)
