@@ -149,4 +149,5 @@ def check_layer(problem: Problem, got: dict, ref: dict, idx: np.ndarray | None, 
     tol_line = TOL_LINE[problem.dtype]
     bad = {k: v for k, v in lines.items() if not (v <= tol_line)}
     assert not bad, "worst row/column error above %g: %s (all: %s)" % (tol_line, bad, lines)
+    errs["worst_line"] = max(lines.values())
     return errs

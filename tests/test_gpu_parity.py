@@ -333,7 +333,7 @@ def test_layer_random_shapes(case):
     if n == 0:
         return
     errs = Hn.check_layer(p, got, p.oracle(), ridx, Hn.TOL[shape.dtype])
-    say("  n_kept=%d max rel err %.2e" % (n, max(errs.values())))
+    say("  n_kept=%d max rel err %.2e worst line %.2e" % (n, max(v for k, v in errs.items() if k != "worst_line"), errs["worst_line"]))
 
 
 def test_layer_with_a_count_known_beforehand_never_synchronises():
@@ -568,7 +568,7 @@ def test_layer_stack_of_eight_error_growth_over_depth():
         got = dict(plan.grads)
         got["dx"] = got["dx"][:n]
         errs = Hn.check_layer(probs[l], got, ref, ridx, Hn.TOL["bf16"])
-        worst.append(max(errs.values()))
+        worst.append(max(v for k, v in errs.items() if k != "worst_line"))
         say("  layer %d below the top: dx %.2e worst tensor %.2e" % (l, errs["dx"], worst[-1]))
         ref_dy = np.asarray(ref["dx"], dtype=np.float64)       # full length, zero on filtered rows
     assert max(worst) <= Hn.TOL["bf16"]
