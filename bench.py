@@ -162,8 +162,18 @@ def mfma_ceiling_leg(reps: int = 20):
         assert rc == 0, rc
 
     ms = back_to_back_ms(call, reps)
-    return {"TFLOPs": round(fl.value / ms / 1e9, 1), "avg_launch_ms": round(ms, 4), "blocks": n_cu, "iters": iters,
-            "kernel": "cf::mfma_probe_kernel (register-resident 16x16x32 bf16 MFMA loop, no LDS, no global traffic)"}
+    out = {"TFLOPs": round(fl.value / ms / 1e9, 1), "avg_launch_ms": round(ms, 4), "blocks": n_cu, "iters": iters,
+           "kernel": "cf::mfma_probe_kernel (register-resident 16x16x32 bf16 MFMA loop, no LDS, no global traffic)"}
+    # the same loop with the GEMM kernels' LDS fragment reads mixed in (nothing else of the GEMM)
+    with_reads = {}
+    for reads, name in ((0, "none"), (1, "nt_16_b128_per_64_mfma"), (2, "tn_32_tr_b64_per_64_mfma")):
+        def call_r(reads=reads):
+            rc = lib.cf_probe_mfma_lds_bf16(n_cu, iters, reads, _vp(sink), C.byref(fl), _st())
+            assert rc == 0, rc
+        ms_r = back_to_back_ms(call_r, reps)
+        with_reads[name] = round(fl.value / ms_r / 1e9, 1)
+    out["TFLOPs_with_lds_fragment_reads"] = with_reads
+    return out
 
 
 def copy_ceiling_leg(reps: int = 10):

@@ -274,11 +274,18 @@ cf_status cf_layer_bwd_lora(const cf_layer_desc* desc, const cf_saved* saved, co
  *   n_blocks*256 floats, overwritten (keeps the work alive).  *flops_out (host, nullable) receives
  *   the flop count of the launch.  Timing it gives the matrix cores' sustained rate on this chip
  *   under its power limit: the measured ceiling that the GEMM kernels are compared with.
+ * cf_probe_mfma_lds_bf16: the same loop with LDS fragment reads mixed in at the GEMM kernels' ratio
+ *   and nothing waiting for them inside the loop: reads = 0 none, 1 = 16 16-byte reads per 64 MFMAs
+ *   (the NT kernel's), 2 = 32 transposing 8-byte reads per 64 MFMAs (the TN kernel's).  Same arguments
+ *   and flop count as cf_probe_mfma_bf16; reads outside 0..2 -> CF_ERR_SHAPE.  Shows what the reads
+ *   alone cost next to the MFMAs (issue slots, power), apart from the operand stream that feeds them.
  * cf_probe_copy: dst[0..bytes) = src[0..bytes) (device pointers, 16-byte aligned, bytes % 16 == 0,
  *   no overlap): a plain streaming copy, the measured HBM ceiling (bytes read + bytes written per
  *   second) for the bandwidth-bound kernels, and the reference that scales profiler byte counters. */
 cf_status cf_probe_mfma_bf16(int32_t n_blocks, int32_t iters, float* sink, double* flops_out,
                              cf_stream stream);
+cf_status cf_probe_mfma_lds_bf16(int32_t n_blocks, int32_t iters, int32_t reads, float* sink,
+                                 double* flops_out, cf_stream stream);
 cf_status cf_probe_copy(const void* src, void* dst, size_t bytes, cf_stream stream);
 
 #ifdef __cplusplus

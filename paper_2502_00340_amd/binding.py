@@ -25,7 +25,8 @@ EXPORTS = (
     "cf_linear_bwd_reduced", "cf_attn_workspace_bytes", "cf_attn_bwd_filtered",
     "cf_layer_workspace_bytes", "cf_layer_bwd_filtered", "cf_layer_bwd_compact", "cf_layer_bwd_compact_dev",
     "cf_layer_bwd_dense",
-    "cf_lora_workspace_bytes", "cf_layer_bwd_lora", "cf_probe_mfma_bf16", "cf_probe_copy",
+    "cf_lora_workspace_bytes", "cf_layer_bwd_lora", "cf_probe_mfma_bf16", "cf_probe_mfma_lds_bf16",
+    "cf_probe_copy",
 )
 
 
@@ -120,6 +121,8 @@ def lib() -> C.CDLL:
                                     vp, C.POINTER(LoraGrads), vp, vp, C.POINTER(i32), vp, sz, vp]
     L.cf_probe_mfma_bf16.restype = C.c_int
     L.cf_probe_mfma_bf16.argtypes = [i32, i32, vp, C.POINTER(C.c_double), vp]
+    L.cf_probe_mfma_lds_bf16.restype = C.c_int
+    L.cf_probe_mfma_lds_bf16.argtypes = [i32, i32, i32, vp, C.POINTER(C.c_double), vp]
     L.cf_probe_copy.restype = C.c_int
     L.cf_probe_copy.argtypes = [vp, vp, sz, vp]
     _lib = L

@@ -49,7 +49,8 @@ struct AttnParams {
     const float* stat;             // [2][Hq][n_kept]: log2(e)*LSE and D = rowsum(dO*O) of every kept row and head
     const int32_t *idx, *cu_kept;
     bf16_t *dq_kept, *dk_kept, *dv_kept;
-    float *dk_part, *dv_part;      // [G][n_kept][Hkv*d] fp32 per-query-head partials (G > 1 only)
+    float *dk_part, *dv_part;      // [G/hp][n_kept][Hkv*d] fp32 partials, one per block of hp query heads (G > hp only)
+    int hp;                        // dK/dV kernel: query heads of one KV group that a block walks through (divides G)
     int B, S, Hq, Hkv;
     int n_kept;                    // rows that the compact buffers are laid out for (the stride of stat and of the partials)
     const int32_t* n_dev;          // nullable: the live row count on the device, at most n_kept
@@ -315,8 +316,9 @@ __global__ __launch_bounds__(256, 1) void attn_dkv_kernel(AttnParams p) {
     // the wave number is the same in all lanes: saying so keeps everything derived from it in scalar registers
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int slot = lane & 31, hh = lane >> 5;
-    const int G = p.Hq / p.Hkv;
-    const int h = blockIdx.x % p.Hq, b = blockIdx.x / p.Hq, g = h / G;
+    const int G = p.Hq / p.Hkv, HP = p.hp;
+    const int nhb = p.Hq / HP;                      // head blocks per sequence
+    const int h0 = (blockIdx.x % nhb) * HP, b = blockIdx.x / nhb, g = h0 / G;
     const int Nq = p.Hq * D, Nkv = p.Hkv * D;
     int seq_begin, seq_end;
     seq_range(p, b, seq_begin, seq_end);
@@ -352,11 +354,14 @@ __global__ __launch_bounds__(256, 1) void attn_dkv_kernel(AttnParams p) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) { dk[nt][v] = 0.f; dv[nt][v] = 0.f; }
 
-    // Q and dO rows of this sequence from its first key on, this head's columns
-    const i32x4_t rsQ = make_rsrc(p.q_kept + (int64_t)c0 * Nq + h * D, ((int64_t)(seq_end - c0) * Nq - h * D) * 2);
-    const i32x4_t rsO = make_rsrc(p.do_kept + (int64_t)c0 * Nq + h * D, ((int64_t)(seq_end - c0) * Nq - h * D) * 2);
-    const i32x4_t rsL = make_rsrc(p.stat + (int64_t)h * p.n_kept + c0, (int64_t)(seq_end - c0) * 4);
-    const i32x4_t rsD = make_rsrc(p.stat + (int64_t)(p.Hq + h) * p.n_kept + c0, (int64_t)(seq_end - c0) * 4);
+    // Q and dO rows of this sequence from its first key on, the current head's columns (set per head below)
+    i32x4_t rsQ, rsO, rsL, rsD;
+    auto open_head = [&](int h) __attribute__((always_inline)) {
+        rsQ = make_rsrc(p.q_kept + (int64_t)c0 * Nq + h * D, ((int64_t)(seq_end - c0) * Nq - h * D) * 2);
+        rsO = make_rsrc(p.do_kept + (int64_t)c0 * Nq + h * D, ((int64_t)(seq_end - c0) * Nq - h * D) * 2);
+        rsL = make_rsrc(p.stat + (int64_t)h * p.n_kept + c0, (int64_t)(seq_end - c0) * 4);
+        rsD = make_rsrc(p.stat + (int64_t)(p.Hq + h) * p.n_kept + c0, (int64_t)(seq_end - c0) * 4);
+    };
     const unsigned lds0 = __builtin_amdgcn_readfirstlane(lds_addr_of(smem));
     // Per-lane byte offsets of the fragment reads inside a 64-row tile, fixed for the whole kernel:
     // row fragments (this lane's row of a 32-row half, d chunk ks) and token fragments (d block nt,
@@ -520,6 +525,11 @@ __global__ __launch_bounds__(256, 1) void attn_dkv_kernel(AttnParams p) {
                 }
             }
             if constexpr (KIND != 2) {
+                // The A-slot MFMAs are inline assembly (see below), so the compiler does not know that the S and dP
+                // values which the previous iteration's last A slot produced may still be on their way when this
+                // iteration's first softmax value reads them: eight wait states here, on top of the reads above,
+                // cover the eleven that an 8-pass MFMA needs ahead of a vector ALU read of its destination.
+                if constexpr (pp == 0) asm volatile("s_nop 7");
                 // softmax values of half t, with the statistics of the next four queries fetched one group ahead
 #pragma unroll
                 for (int e = 0; e < VPS; ++e) {
@@ -535,15 +545,16 @@ __global__ __launch_bounds__(256, 1) void attn_dkv_kernel(AttnParams p) {
             if constexpr (is_a(EVEN, pp)) {
                 if constexpr (KIND != 2) {
                     constexpr int ks = slot_index(EVEN, pp);
+                    // Inline assembly keeps S and dP in the VGPR file, where the softmax arithmetic reads them:
+                    // with the builtin the register allocator accumulates them in AGPRs and copies all 32
+                    // registers of a half out again, one v_accvgpr_read each.  The price is that the compiler
+                    // no longer sees these MFMAs' latency (see the wait states at the head of an iteration).
                     if constexpr (ks == 0) {
-                        f32x16_t z;
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) z[v] = 0.f;
-                        st[parA] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[pp % RING][0], kf[ks], z, 0, 0, 0);
-                        dpt[parA] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[pp % RING][1], vf[ks], z, 0, 0, 0);
+                        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(st[parA]) : "v"(op[pp % RING][0]), "v"(kf[ks]));
+                        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(dpt[parA]) : "v"(op[pp % RING][1]), "v"(vf[ks]));
                     } else {
-                        st[parA] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[pp % RING][0], kf[ks], st[parA], 0, 0, 0);
-                        dpt[parA] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op[pp % RING][1], vf[ks], dpt[parA], 0, 0, 0);
+                        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(st[parA]) : "v"(op[pp % RING][0]), "v"(kf[ks]));
+                        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(dpt[parA]) : "v"(op[pp % RING][1]), "v"(vf[ks]));
                     }
                 }
             } else {
@@ -557,6 +568,13 @@ __global__ __launch_bounds__(256, 1) void attn_dkv_kernel(AttnParams p) {
         });
     };
 
+    // The block walks through HP query heads of its KV group one after the other: the K and V fragments
+    // and the dK / dV accumulators stay in registers, only the Q / dO / statistics stream changes, so
+    // the group's sum over these heads costs no partial buffer and a tile's fixed costs (fragment fetch,
+    // write-out) are paid once per HP heads.
+    for (int hi = 0; hi < HP; ++hi) {
+    open_head(h0 + hi);
+    if (hi > 0) lds_barrier();                      // every wave is done with the previous head's stages
     // Ring of four stages: the loads of step s+3 are issued in pair s, into the stage that step s-1
     // used.  Steps past the end are issued as well (every row out of range: zero fill), so the number
     // of loads in flight is the same in every pair.
@@ -606,10 +624,10 @@ __global__ __launch_bounds__(256, 1) void attn_dkv_kernel(AttnParams p) {
         iteration(ic<0>{}, ic<0>{}, ic<0>{}, s);
     }
     iteration(ic<1>{}, ic<0>{}, ic<2>{}, steps);     // drain: C of the last half
-    wait_vmcnt<0>();
+    wait_vmcnt<0>();                                // the zero-fill loads of the steps past the end
+    }
 
-
-    if (G == 1) {
+    if (G == HP) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
 #pragma unroll
@@ -623,7 +641,7 @@ __global__ __launch_bounds__(256, 1) void attn_dkv_kernel(AttnParams p) {
             }
         }
     } else {
-        const int64_t part = (int64_t)(h - g * G) * p.n_kept * Nkv;
+        const int64_t part = (int64_t)((h0 - g * G) / HP) * p.n_kept * Nkv;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
 #pragma unroll
@@ -749,10 +767,22 @@ static hipError_t launch_t(const AttnParams& p, const bf16_t* o_rows, const floa
     const int max_per_seq = n_kept < p.S ? n_kept : p.S;
     const int tiles = ceil_div(max_per_seq, 128);
     attn_dq_kernel<D><<<dim3(p.Hq * p.B, tiles), 256, smem_dq, st>>>(p);
-    attn_dkv_kernel<D><<<dim3(p.Hq * p.B, tiles), 256, smem_dkv, st>>>(p);
-    if (p.Hq != p.Hkv) {
+    // Query heads per dK/dV block: the largest divisor of the group size that still leaves about two
+    // blocks per CU (a block costs between one and `tiles` steps, handed out heaviest first, so two per
+    // CU already balance); every head more in a block saves that block's fixed cost once.
+    AttnParams pk = p;
+    const int G = p.Hq / p.Hkv;
+    const int64_t tile_rows = ceil_div(n_kept, 128);           // key tiles over all sequences, roughly
+    pk.hp = 1;
+    for (int c = G; c > 1; --c)
+        if (G % c == 0 && tile_rows * (p.Hq / c) >= 2 * (int64_t)compute_units()) {
+            pk.hp = c;
+            break;
+        }
+    attn_dkv_kernel<D><<<dim3((p.Hq / pk.hp) * p.B, tiles), 256, smem_dkv, st>>>(pk);
+    if (G != pk.hp) {
         const int64_t n_elems = (int64_t)n_kept * p.Hkv * D;
-        attn_dkv_reduce_kernel<<<ceil_div(n_elems / 8, 256), 256, 0, st>>>(p.dk_part, p.dv_part, p.Hq / p.Hkv,
+        attn_dkv_reduce_kernel<<<ceil_div(n_elems / 8, 256), 256, 0, st>>>(p.dk_part, p.dv_part, G / pk.hp,
                                                                           n_kept, p.n_dev, p.Hkv * D, p.scale,
                                                                           p.dk_kept, p.dv_kept);
     }
@@ -774,6 +804,7 @@ hipError_t launch_attn_bwd_mfma(const cf_layer_desc& L, float scale, const void*
     p.cu_kept = cu_kept; p.dq_kept = (bf16_t*)dq_kept; p.dk_kept = (bf16_t*)dk_kept;
     p.dv_kept = (bf16_t*)dv_kept; p.B = L.B; p.S = L.S; p.Hq = L.Hq; p.Hkv = L.Hkv; p.scale = scale;
     p.n_kept = n_kept;
+    p.hp = 1;
     p.n_dev = rows.dev;
     p.dk_part = partials;
     p.dv_part = partials ? partials + (size_t)n_kept * L.Hq * L.d : nullptr;

@@ -186,4 +186,19 @@ hipError_t launch_gemm_tn_groups(const void* A, int K, int M, int ngroups, const
                                  void* const* Cg, const int* Ng, hipStream_t st, float beta = 0.f,
                                  bool c_f32 = false, const int32_t* n_dev = nullptr);
 
+// CUs of the current device (cached per device ordinal; 256 if the query fails)
+inline int compute_units() {
+    static std::atomic<int> cache[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    std::atomic<int>& c = cache[dev & 63];
+    int n = c.load(std::memory_order_relaxed);
+    if (n == 0) {
+        int v = 0;
+        n = (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) ? v : 256;
+        c.store(n, std::memory_order_relaxed);
+    }
+    return n;
+}
+
 }  // namespace cf

@@ -959,21 +959,6 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g) {
 }
 
 
-// CUs of the current device (cached per device ordinal; 256 if the query fails)
-static int compute_units() {
-    static std::atomic<int> cache[64];
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 256;
-    std::atomic<int>& c = cache[dev & 63];
-    int n = c.load(std::memory_order_relaxed);
-    if (n == 0) {
-        int v = 0;
-        n = (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) ? v : 256;
-        c.store(n, std::memory_order_relaxed);
-    }
-    return n;
-}
-
 // Number of K parts for a split-K launch (0: use the ordinary kernel) and the K range of a part.
 // Splitting pays when the 128x128 tiles cover at most half of the CUs and K is long enough that
 // every part still runs several K-steps.

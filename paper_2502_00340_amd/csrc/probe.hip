@@ -63,6 +63,63 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float* __restrict__ sin
     sink[tid] = s;
 }
 
+// The same MFMA loop with the GEMM's LDS fragment reads mixed in at the GEMM's ratio: READS 1 = 16
+// ds_read_b128 per 64 MFMAs (mode NT), READS 2 = 32 ds_read_b64_tr_b16 per 64 MFMAs (mode TN), every read
+// behind an MFMA, nothing waiting for them inside the loop (their results are folded into the sink after
+// it).  The LDS holds pseudo-random bf16 values; reads are conflict-free (16 bytes per lane, consecutive).
+template <int READS>
+__global__ __launch_bounds__(256) void mfma_lds_probe_kernel(float* __restrict__ sink, int iters) {
+    __shared__ __align__(16) unsigned lds[16384];
+    const unsigned tid = blockIdx.x * 256u + threadIdx.x;
+    for (int i = threadIdx.x; i < 16384; i += 256) {
+        const unsigned h = probe_hash(i * 2654435761u + blockIdx.x);
+        lds[i] = (h & 0x807F807Fu) | 0x3F003F00u;                   // two bf16 values in +-[0.5, 1)
+    }
+    __syncthreads();
+    bf16x8_t a[8], b[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        a[i] = probe_fragment(tid * 16u + i);
+        b[i] = probe_fragment(tid * 16u + 8u + i);
+    }
+    f32x4_t acc[8][8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.f;
+    u32x4_t r[4];
+    u32x2_t r2[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { r[i] = u32x4_t{0, 0, 0, 0}; r2[i] = u32x2_t{0, 0}; }
+    // wave w reads bytes [1024 w + 16 lane + 4096 k, +16), k < 8: inside the 64 KB array
+    const unsigned addr = lds_addr_of(lds) + (threadIdx.x & 63) * 16 + (threadIdx.x >> 6) * 1024;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int m = i * 8 + j;
+                asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(b[j]), "v"(a[i]));
+                if (READS == 1 && (m & 3) == 1)
+                    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r[(m >> 2) & 3]) : "v"(addr), "n"(((m >> 2) & 7) * 4096));
+                if (READS == 2 && (m & 1) == 1)
+                    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r2[(m >> 1) & 3]) : "v"(addr), "n"(((m >> 1) & 7) * 4096));
+            }
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) s += acc[i][j][0] + acc[i][j][3];
+    unsigned x = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) x ^= r[i][0] ^ r[i][3] ^ r2[i][0] ^ r2[i][1];
+    sink[tid] = s + (float)(x & 0xFF);
+}
+
 // block b copies words [b*1024, (b+1)*1024): four loads per lane in flight, then four stores, both with
 // the non-temporal hint (the data is touched once).  Of the variants measured on this chip (grid-stride
 // loops of 1, 4 or 8 words per lane, with and without the hint, 2 K to 64 K blocks; one, two, four or
@@ -93,6 +150,20 @@ cf_status cf_probe_mfma_bf16(int32_t n_blocks, int32_t iters, float* sink, doubl
     mfma_probe_kernel<<<n_blocks, 256, 0, reinterpret_cast<hipStream_t>(stream)>>>(sink, iters);
     if (hipGetLastError() != hipSuccess) return CF_ERR_HIP;
     // 4 waves x 64 MFMAs of 16x16x32 (2*16*16*32 flop) per iteration and block
+    if (flops_out) *flops_out = (double)n_blocks * 4.0 * 64.0 * 16384.0 * (double)iters;
+    return CF_OK;
+}
+
+cf_status cf_probe_mfma_lds_bf16(int32_t n_blocks, int32_t iters, int32_t reads, float* sink, double* flops_out,
+                                 cf_stream stream) {
+    if (!sink) return CF_ERR_NULL;
+    if (n_blocks <= 0 || n_blocks > 65536 || iters <= 0 || reads < 0 || reads > 2 || ((uintptr_t)sink % 4) != 0)
+        return CF_ERR_SHAPE;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (reads == 0) mfma_lds_probe_kernel<0><<<n_blocks, 256, 0, st>>>(sink, iters);
+    else if (reads == 1) mfma_lds_probe_kernel<1><<<n_blocks, 256, 0, st>>>(sink, iters);
+    else mfma_lds_probe_kernel<2><<<n_blocks, 256, 0, st>>>(sink, iters);
+    if (hipGetLastError() != hipSuccess) return CF_ERR_HIP;
     if (flops_out) *flops_out = (double)n_blocks * 4.0 * 64.0 * 16384.0 * (double)iters;
     return CF_OK;
 }

@@ -239,6 +239,21 @@ def test_attn_bwd_filtered_long_context(S, Hq, Hkv, d, kind):
     _attn_case("bf16", 1, S, Hq, Hkv, d, mask, seed=S + 7 * d, f8=np.float32 if S > 4096 else np.float64)
 
 
+@pytest.mark.parametrize("B,S,Hq,Hkv,d,kind,rho", [
+    # enough key tiles that a dK/dV block takes several query heads of its KV group in a row
+    # (the launcher wants about two blocks per CU of a 256-CU chip):
+    (4, 2048, 16, 4, 64, "topk", 1.0),      # 64 key tiles x 16 heads: two heads per block, two partials per group
+    (8, 2048, 8, 4, 128, "spans", 1.0),     # 128 x 8: the whole group of two in one block, no partials
+    (12, 2048, 16, 2, 64, "ragged", 0.8),   # about 154 x 16, ragged sequences: four heads of a group of eight per block
+])
+def test_attn_bwd_filtered_heads_sharing_a_block(B, S, Hq, Hkv, d, kind, rho):
+    say("attn bf16 heads per block B=%d S=%d Hq=%d Hkv=%d d=%d %s rho=%.1f" % (B, S, Hq, Hkv, d, kind, rho))
+    rng = np.random.default_rng(B * S + Hq)
+    shape = WL.LayerShape("attn_hp", B=B, S=S, H=8, Hq=Hq, Hkv=Hkv, d=d, F=8, dtype="bf16", rho=rho, mask_kind=kind)
+    mask = np.ones((B, S), np.uint8) if rho >= 1.0 else WL.make_mask(shape, rng)
+    _attn_case("bf16", B, S, Hq, Hkv, d, mask, seed=S + Hq + d, f8=np.float32)
+
+
 def test_attn_fp32_small_head_dims():
     for d in (8, 32):
         say("attn f32 d=%d" % d)
