@@ -138,11 +138,13 @@ hipError_t launch_rmsnorm_fwd(int dtype, const void* x, const void* g, const int
                               RowCount rows, int H, float eps, void* h, hipStream_t st);
 // dx_out = res + rmsnorm_bwd(dh; x, g); dg_partial is [rmsnorm_bwd_blocks(n_rows), H] fp32 scratch.
 // dg_acc_f32: dg_out is fp32 [H] and the gain gradient is added to it instead of written.
+// h_out (nullable, [n_rows, H]): also receives the normalised rows rmsnorm(x)*g, as launch_rmsnorm_fwd
+// would write them.
 int rmsnorm_bwd_blocks(int n_rows);
 hipError_t launch_rmsnorm_bwd(int dtype, const void* dh, const void* x, const void* g,
                               const int32_t* idx, const void* res, RowCount rows, int H, float eps,
                               void* dx_out, float* dg_partial, void* dg_out, hipStream_t st,
-                              bool dg_acc_f32 = false);
+                              bool dg_acc_f32 = false, void* h_out = nullptr);
 // g[j, h*d + i] (in place, [n_rows, heads*d]): transposed rotary rotation at position idx[j] % S
 // (idx null: j % S); cos, sin are [S, d/2] fp32
 hipError_t launch_rope_bwd(int dtype, void* g, const int32_t* idx, RowCount rows, int heads, int d, int S,

@@ -115,6 +115,9 @@ __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const T* __restrict__ 
 
 // dx_out[j,:] = res[j,:] + rstd*(u - n*mean(u*n)),  n = x*rstd, u = dh*g
 // dg_partial[block,:] = sum over the block's rows of dh*n
+// h_out (nullable): h_out[j,:] = n*g, the normalised row itself (what rmsnorm_fwd_kernel computes, with
+// the same arithmetic): the parameter-gradient GEMMs of the linears behind this norm need it as an
+// operand, and the row and its rstd are in registers here anyway.
 // A block owns one row at a time, NV 16-byte vectors per thread, and works on two rows per
 // iteration so that the loads of the second row overlap the reduction of the first; every
 // load of an iteration (x, dh, res of both rows) is issued before the first reduction.
@@ -134,7 +137,7 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ 
                                                           const T* __restrict__ res, int n_max,
                                                           const int32_t* __restrict__ n_dev,
                                                           int H, float eps, T* __restrict__ dx_out,
-                                                          float* __restrict__ dg_partial) {
+                                                          float* __restrict__ dg_partial, T* __restrict__ h_out) {
     constexpr int VN = Vec<T>::N;
     __shared__ float red[16];
     const int n_rows = live_rows(n_max, n_dev);
@@ -207,6 +210,11 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const T* __restrict__ 
                         dgacc[i][e] += dv[r][i][e] * n;
                     }
                     Vec<T>::store(dx_out + (int64_t)j * H + v * VN, o);
+                    if (h_out != nullptr) {
+#pragma unroll
+                        for (int e = 0; e < VN; ++e) o[e] = xv[r][i][e] * rstd * gv[i][e];
+                        Vec<T>::store(h_out + (int64_t)j * H + v * VN, o);
+                    }
                 }
             }
         }
@@ -370,10 +378,10 @@ int rmsnorm_bwd_blocks(int n_rows) {
 template <typename T>
 static void rmsnorm_bwd_dispatch(int nv, int nblk, hipStream_t st, const void* dh, const void* x, const void* g,
                                  const int32_t* idx, const void* res, RowCount rows, int H, float eps,
-                                 void* dx_out, float* dg_partial) {
+                                 void* dx_out, float* dg_partial, void* h_out) {
 #define CF_RMS_BWD(NV)                                                                               \
     rmsnorm_bwd_kernel<T, NV><<<nblk, 256, 0, st>>>((const T*)dh, (const T*)x, (const T*)g, idx,      \
-                                                    (const T*)res, rows.n, rows.dev, H, eps, (T*)dx_out, dg_partial)
+                                                    (const T*)res, rows.n, rows.dev, H, eps, (T*)dx_out, dg_partial, (T*)h_out)
     if (nv <= 1) CF_RMS_BWD(1);
     else if (nv <= 2) CF_RMS_BWD(2);
     else if (nv <= 4) CF_RMS_BWD(4);
@@ -383,7 +391,8 @@ static void rmsnorm_bwd_dispatch(int nv, int nblk, hipStream_t st, const void* d
 
 hipError_t launch_rmsnorm_bwd(int dtype, const void* dh, const void* x, const void* g,
                               const int32_t* idx, const void* res, RowCount rows, int H, float eps,
-                              void* dx_out, float* dg_partial, void* dg_out, hipStream_t st, bool dg_acc_f32) {
+                              void* dx_out, float* dg_partial, void* dg_out, hipStream_t st, bool dg_acc_f32,
+                              void* h_out) {
     const int n_rows = rows.n;
     const int nblk = rmsnorm_bwd_blocks(n_rows);
     if (n_rows <= 0) return dg_acc_f32 ? hipSuccess : launch_fill_zero(dg_out, (size_t)H * dtype_size(dtype), st);
@@ -391,11 +400,11 @@ hipError_t launch_rmsnorm_bwd(int dtype, const void* dh, const void* x, const vo
     const int nv = ceil_div(H / vn, 256);           // 16-byte vectors per thread (<= RMS_MAX_VEC, checked by the API)
     const int fin = ceil_div(H, 32);
     if (dtype == CF_F32) {
-        rmsnorm_bwd_dispatch<float>(nv, nblk, st, dh, x, g, idx, res, rows, H, eps, dx_out, dg_partial);
+        rmsnorm_bwd_dispatch<float>(nv, nblk, st, dh, x, g, idx, res, rows, H, eps, dx_out, dg_partial, h_out);
         if (dg_acc_f32) colsum_finish_kernel<float, true><<<fin, 256, 0, st>>>(dg_partial, n_rows, rows.dev, H, (float*)dg_out);
         else colsum_finish_kernel<float><<<fin, 256, 0, st>>>(dg_partial, n_rows, rows.dev, H, (float*)dg_out);
     } else {
-        rmsnorm_bwd_dispatch<bf16_t>(nv, nblk, st, dh, x, g, idx, res, rows, H, eps, dx_out, dg_partial);
+        rmsnorm_bwd_dispatch<bf16_t>(nv, nblk, st, dh, x, g, idx, res, rows, H, eps, dx_out, dg_partial, h_out);
         if (dg_acc_f32) colsum_finish_kernel<float, true><<<fin, 256, 0, st>>>(dg_partial, n_rows, rows.dev, H, (float*)dg_out);
         else colsum_finish_kernel<bf16_t><<<fin, 256, 0, st>>>(dg_partial, n_rows, rows.dev, H, (bf16_t*)dg_out);
     }
