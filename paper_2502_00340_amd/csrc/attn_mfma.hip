@@ -50,12 +50,24 @@ struct AttnParams {
     const int32_t *idx, *cu_kept;
     bf16_t *dq_kept, *dk_kept, *dv_kept;
     float *dk_part, *dv_part;      // [G/hp][n_kept][Hkv*d] fp32 partials, one per block of hp query heads (G > hp only)
-    int hp;                        // dK/dV kernel: query heads of one KV group that a block walks through (divides G)
+    int n_cu;                      // compute units of the device (the dK/dV kernel sizes its blocks' work by it)
     int B, S, Hq, Hkv;
     int n_kept;                    // rows that the compact buffers are laid out for (the stride of stat and of the partials)
     const int32_t* n_dev;          // nullable: the live row count on the device, at most n_kept
     float scale;
 };
+
+// Query heads of one KV group that a dK/dV block walks through: the largest divisor of the group size G
+// that still leaves about two blocks per CU (a block costs between one and `tiles` steps and blocks are
+// handed out heaviest first, so two per CU already balance); every head more in a block saves that
+// block's fixed cost once and one fp32 partial.  A function of the LIVE row count, which only the
+// device may know: the dK/dV blocks and the reduction evaluate it themselves and agree.
+__host__ __device__ inline int attn_heads_per_block(int n_rows, int Hq, int G, int n_cu) {
+    const int64_t tile_rows = (n_rows + 127) / 128;             // key tiles over all sequences, roughly
+    for (int c = G; c > 1; --c)
+        if (G % c == 0 && tile_rows * (Hq / c) >= 2 * (int64_t)n_cu) return c;
+    return 1;
+}
 
 // Compact rows [begin, end) of sequence b.  The prefix counts are clamped to the live row count, so a
 // mask that keeps more tokens than the buffers were sized for cannot send a block past their end.
@@ -140,8 +152,11 @@ __global__ __launch_bounds__(256, 2) void attn_dq_kernel(AttnParams p) {
     int seq_begin, seq_end;
     seq_range(p, b, seq_begin, seq_end);
     const int cnt = seq_end - seq_begin;
-    const int qt = gridDim.y - 1 - blockIdx.y;        // heaviest (latest) query tiles first
-    if (qt * 128 >= cnt) return;
+    // heaviest (latest) query tiles of the sequence first; the grid is sized for an upper bound of the
+    // row count, and the blocks past this sequence's tiles come last in the launch order
+    const int seq_tiles = (cnt + 127) / 128;
+    if ((int)blockIdx.y >= seq_tiles) return;
+    const int qt = seq_tiles - 1 - blockIdx.y;
     const int j0 = seq_begin + qt * 128;
     const int rows_in_tile = min(128, cnt - qt * 128);
 
@@ -316,15 +331,22 @@ __global__ __launch_bounds__(256, 1) void attn_dkv_kernel(AttnParams p) {
     // the wave number is the same in all lanes: saying so keeps everything derived from it in scalar registers
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int slot = lane & 31, hh = lane >> 5;
-    const int G = p.Hq / p.Hkv, HP = p.hp;
+    const int G = p.Hq / p.Hkv;
+    const int HP = attn_heads_per_block(live_rows(p.n_kept, p.n_dev), p.Hq, G, p.n_cu);
+    // The grid is one-dimensional and has a block per (key tile, sequence, query head).  Only nhb * B blocks
+    // per key tile are needed; they are numbered first, key tile by key tile (heaviest first), so the blocks
+    // without work all come at the end of the launch order instead of between the working ones (a block
+    // needs a whole CU's LDS even to find out that it has nothing to do).
     const int nhb = p.Hq / HP;                      // head blocks per sequence
-    const int h0 = (blockIdx.x % nhb) * HP, b = blockIdx.x / nhb, g = h0 / G;
+    const int per_tile = nhb * p.B;
+    const int kt = blockIdx.x / per_tile, bx = blockIdx.x % per_tile;
+    if (kt >= (int)gridDim.x / (p.Hq * p.B)) return;
+    const int h0 = (bx % nhb) * HP, b = bx / nhb, g = h0 / G;
     const int Nq = p.Hq * D, Nkv = p.Hkv * D;
     int seq_begin, seq_end;
     seq_range(p, b, seq_begin, seq_end);
     const int cnt = seq_end - seq_begin;
-    const int kt = blockIdx.y;                      // early key tiles see the most queries: heaviest first
-    if (kt * 128 >= cnt) return;
+    if (kt * 128 >= cnt) return;                    // early key tiles see the most queries: heaviest first
     const int c0 = seq_begin + kt * 128;            // compact row of the tile's first key
     const int keys_in_tile = min(128, cnt - kt * 128);
 
@@ -659,13 +681,17 @@ __global__ __launch_bounds__(256, 1) void attn_dkv_kernel(AttnParams p) {
 
 // dk = scale * sum_g dk_part[g], dv = sum_g dv_part[g]   (fixed order: deterministic)
 __global__ __launch_bounds__(256) void attn_dkv_reduce_kernel(const float* __restrict__ dk_part,
-                                                              const float* __restrict__ dv_part, int G,
-                                                              int n_max, const int32_t* __restrict__ n_dev, int Nkv,
-                                                              float scale,
+                                                              const float* __restrict__ dv_part, int Hq, int Hkv,
+                                                              int n_cu, int n_max, const int32_t* __restrict__ n_dev,
+                                                              int Nkv, float scale,
                                                               bf16_t* __restrict__ dk, bf16_t* __restrict__ dv) {
-    const int64_t n_elems = (int64_t)n_max * Nkv;                       // stride between two heads' partials
+    const int n_live = live_rows(n_max, n_dev);
+    const int hp = attn_heads_per_block(n_live, Hq, Hq / Hkv, n_cu);
+    const int G = Hq / Hkv / hp;                                        // partials per KV group
+    if (G == 1) return;                                                 // the dK/dV blocks wrote the results themselves
+    const int64_t n_elems = (int64_t)n_max * Nkv;                       // stride between two partials
     const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
-    if (i >= (int64_t)live_rows(n_max, n_dev) * Nkv) return;
+    if (i >= (int64_t)n_live * Nkv) return;
     float sk[8], sv[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) { sk[e] = 0.f; sv[e] = 0.f; }
@@ -767,22 +793,10 @@ static hipError_t launch_t(const AttnParams& p, const bf16_t* o_rows, const floa
     const int max_per_seq = n_kept < p.S ? n_kept : p.S;
     const int tiles = ceil_div(max_per_seq, 128);
     attn_dq_kernel<D><<<dim3(p.Hq * p.B, tiles), 256, smem_dq, st>>>(p);
-    // Query heads per dK/dV block: the largest divisor of the group size that still leaves about two
-    // blocks per CU (a block costs between one and `tiles` steps, handed out heaviest first, so two per
-    // CU already balance); every head more in a block saves that block's fixed cost once.
-    AttnParams pk = p;
-    const int G = p.Hq / p.Hkv;
-    const int64_t tile_rows = ceil_div(n_kept, 128);           // key tiles over all sequences, roughly
-    pk.hp = 1;
-    for (int c = G; c > 1; --c)
-        if (G % c == 0 && tile_rows * (p.Hq / c) >= 2 * (int64_t)compute_units()) {
-            pk.hp = c;
-            break;
-        }
-    attn_dkv_kernel<D><<<dim3((p.Hq / pk.hp) * p.B, tiles), 256, smem_dkv, st>>>(pk);
-    if (G != pk.hp) {
+    attn_dkv_kernel<D><<<dim3(p.Hq * p.B * tiles), 256, smem_dkv, st>>>(p);
+    if (p.Hq != p.Hkv) {
         const int64_t n_elems = (int64_t)n_kept * p.Hkv * D;
-        attn_dkv_reduce_kernel<<<ceil_div(n_elems / 8, 256), 256, 0, st>>>(p.dk_part, p.dv_part, G / pk.hp,
+        attn_dkv_reduce_kernel<<<ceil_div(n_elems / 8, 256), 256, 0, st>>>(p.dk_part, p.dv_part, p.Hq, p.Hkv, p.n_cu,
                                                                           n_kept, p.n_dev, p.Hkv * D, p.scale,
                                                                           p.dk_kept, p.dv_kept);
     }
@@ -804,7 +818,7 @@ hipError_t launch_attn_bwd_mfma(const cf_layer_desc& L, float scale, const void*
     p.cu_kept = cu_kept; p.dq_kept = (bf16_t*)dq_kept; p.dk_kept = (bf16_t*)dk_kept;
     p.dv_kept = (bf16_t*)dv_kept; p.B = L.B; p.S = L.S; p.Hq = L.Hq; p.Hkv = L.Hkv; p.scale = scale;
     p.n_kept = n_kept;
-    p.hp = 1;
+    p.n_cu = compute_units();
     p.n_dev = rows.dev;
     p.dk_part = partials;
     p.dv_part = partials ? partials + (size_t)n_kept * L.Hq * L.d : nullptr;
