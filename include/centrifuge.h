@@ -194,7 +194,8 @@ cf_status cf_attn_bwd_filtered(const cf_layer_desc* desc, const void* q_kept, co
  * ignored).  Outputs: grads->dx compact [N_k,H] (the row-sparse gradient for the layer below), all
  * parameter gradients; idx_out [T] / cu_kept_out [B+1] / n_kept_dev_out [1] (device, each nullable)
  * receive the keep index and N_k; n_kept_host (HOST, nullable; page-locked memory keeps the copy
- * asynchronous) receives N_k once the stream has reached that point: read it after synchronising.
+ * asynchronous) receives N_k through a copy queued behind the call's kernels: read it after
+ * synchronising with the stream.
  * The call itself never synchronises: every kernel reads N_k on the device.
  *   max_kept: upper bound of N_k that the workspace and grads->dx are sized for; 0 or a value above
  *   T means T, which is always sufficient.  A caller that knows its keep ratio saves workspace.  If

@@ -601,9 +601,13 @@ cf_status cf_layer_bwd_filtered(const cf_layer_desc* desc, const cf_saved* saved
     int32_t* n_dev = n_kept_dev_out ? n_kept_dev_out : wk.n_kept_dev;
     CF_HIP(launch_keep_index(mask, desc->B, desc->S, idx, cu, n_dev, wk.index_ws, st));
     // the count stays on the device: every later kernel reads it there, nothing waits for the host
+    s = layer_core(*desc, *saved, *w, dy_full, true, idx, cu, RowCount{max_kept, n_dev}, *grads, wk, st);
+    if (s != CF_OK) return s;
+    // The host's copy of the count is queued behind the layer's kernels: the caller can read it only
+    // after synchronising with the stream anyway, and ahead of them the copy would sit in their way.
     if (n_kept_host)
         CF_HIP(hipMemcpyAsync(n_kept_host, n_dev, sizeof(int32_t), hipMemcpyDeviceToHost, st));
-    return layer_core(*desc, *saved, *w, dy_full, true, idx, cu, RowCount{max_kept, n_dev}, *grads, wk, st);
+    return CF_OK;
 }
 
 cf_status cf_layer_bwd_compact(const cf_layer_desc* desc, const cf_saved* saved, const cf_weights* w,
