@@ -396,8 +396,8 @@ def lora_leg(shape: WL.LayerShape, sv, W, dy, mask_dev, rng, steps: int, warmup:
           for k, v in WL.make_lora(shape, rng, rank=rank, alpha=2.0 * rank).items()}
     desc = Bn.make_desc(shape.B, shape.S, shape.H, shape.Hq, shape.Hkv, shape.d, shape.F, shape.dtype)
     plan = Bn.LoraBackward(desc, rank, device=DEV)
-    t_f = time_steps(lambda: plan.run(sv, W, lo, dy, mask_dev), steps, warmup)
-    t_d = time_steps(lambda: plan.run(sv, W, lo, dy, None), steps, warmup)
+    t_f = time_steps(lambda: plan.run_async(sv, W, lo, dy, mask_dev), steps, warmup)
+    t_d = time_steps(lambda: plan.run_async(sv, W, lo, dy, None), steps, warmup)
     return {"rank": rank, "filtered_ms": round(t_f * 1e3, 4), "dense_ms": round(t_d * 1e3, 4),
             "speedup": round(t_d / t_f, 4)}
 

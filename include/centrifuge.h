@@ -28,8 +28,8 @@
  *     8 and d must be 64 or 128 (another multiple of 8 returns CF_ERR_UNSUPPORTED);
  *     in CF_F32 mode they must be multiples of 4 and d <= 256.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *     Calls enqueue work and return without synchronising; the two exceptions
- *     (cf_build_keep_index with a host pointer, cf_layer_bwd_lora with a mask) say so.
+ *     Calls enqueue work and return without synchronising; the one exception
+ *     (cf_build_keep_index with a host pointer) says so.
  *   - The number of kept tokens N_k is a DEVICE value after the index build.  Calls
  *     that take `n_kept_dev` + `max_kept` read it there: max_kept is the upper bound
  *     that buffers and launches are sized for, the kernels work on min(N_k, max_kept)
@@ -255,17 +255,18 @@ typedef struct {
 } cf_lora_grads;
 
 /* cf_layer_bwd_lora: the filtered layer backward of a LoRA-adapted layer.  Arguments as for
- * cf_layer_bwd_filtered (without max_kept), but with a mask this call does synchronise the stream
- * once, right after the index build, to read N_k into *n_kept_host (required then) and size its
- * launches (the split-K launches of the rank-r products are planned on the host).  mask == NULL means
- * "every token kept" (no index, no gather, no host synchronisation: the dense LoRA backward of the
- * same library, and n_kept_host may be NULL).
- * ws must hold cf_lora_workspace_bytes(desc, rank, max_kept) bytes. */
+ * cf_layer_bwd_filtered (max_kept, idx_out, cu_kept_out, n_kept_dev_out, n_kept_host included): the kept
+ * count stays on the device, every kernel reads it there, and the call never synchronises (the split-K
+ * launches of the rank-r products are planned for max_kept; a part of the contraction that lies past the
+ * live count contributes zeros).  mask == NULL means "every token kept" (no index, no gather: the dense
+ * LoRA backward of the same library; *n_kept_host, when given, is set to T at once).
+ * ws must hold cf_lora_workspace_bytes(desc, rank, max_kept) bytes (max_kept 0 or above T means T). */
 size_t cf_lora_workspace_bytes(const cf_layer_desc* desc, int32_t rank, int32_t max_kept);
 cf_status cf_layer_bwd_lora(const cf_layer_desc* desc, const cf_saved* saved, const cf_weights* w,
-                            const cf_lora* lora, const void* dy_full, const uint8_t* mask,
+                            const cf_lora* lora, const void* dy_full, const uint8_t* mask, int32_t max_kept,
                             cf_lora_grads* grads, int32_t* idx_out, int32_t* cu_kept_out,
-                            int32_t* n_kept_host, void* ws, size_t ws_bytes, cf_stream stream);
+                            int32_t* n_kept_dev_out, int32_t* n_kept_host, void* ws, size_t ws_bytes,
+                            cf_stream stream);
 
 /* ---- measurement probes (for the rooflines of Sec. 3.2's GEMMs and of the gather / row-local
  * kernels; not part of the method) ------------------------------------------------------------

@@ -118,7 +118,7 @@ def lib() -> C.CDLL:
     L.cf_lora_workspace_bytes.argtypes = [C.POINTER(LayerDesc), i32, i32]
     L.cf_layer_bwd_lora.restype = C.c_int
     L.cf_layer_bwd_lora.argtypes = [C.POINTER(LayerDesc), C.POINTER(Saved), C.POINTER(Weights), C.POINTER(Lora), vp,
-                                    vp, C.POINTER(LoraGrads), vp, vp, C.POINTER(i32), vp, sz, vp]
+                                    vp, i32, C.POINTER(LoraGrads), vp, vp, vp, C.POINTER(i32), vp, sz, vp]
     L.cf_probe_mfma_bf16.restype = C.c_int
     L.cf_probe_mfma_bf16.argtypes = [i32, i32, vp, C.POINTER(C.c_double), vp]
     L.cf_probe_mfma_lds_bf16.restype = C.c_int
@@ -391,16 +391,25 @@ class LoraBackward(LayerBackward):
             raise CfError(2, "cf_lora_workspace_bytes")
         self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=self.device)
         self._g = LoraGrads(*[self.grads[n].data_ptr() for n, _ in LoraGrads._fields_])
+        self.max_kept = T
+        self.n_kept_dev = torch.zeros(1, dtype=torch.int32, device=self.device)
         self._n_host = torch.empty(1, dtype=torch.int32).pin_memory()
 
-    def run(self, saved: dict, weights: dict, lora: dict, dy: torch.Tensor, mask: torch.Tensor | None) -> int:
-        """mask None: every token kept (the dense LoRA backward).  Returns N_k."""
+    def run_async(self, saved: dict, weights: dict, lora: dict, dy: torch.Tensor, mask: torch.Tensor | None) -> None:
+        """mask None: every token kept (the dense LoRA backward).  Nothing synchronises: the kept count is
+        in self.n_kept_dev, and n_kept() reads the page-locked copy after waiting for the stream."""
         sv, w = self._pack(saved, weights)
         lo = Lora(*([lora[n].data_ptr() for n in _LORA_T] + [self.rank, float(lora["scale"])]))
         self._n_host[0] = -1
         _check(lib().cf_layer_bwd_lora(C.byref(self.desc), C.byref(sv), C.byref(w), C.byref(lo), _ptr(dy),
-                                       _ptr(mask), C.byref(self._g), _ptr(self.idx), _ptr(self.cu_kept),
+                                       _ptr(mask), self.max_kept, C.byref(self._g), _ptr(self.idx),
+                                       _ptr(self.cu_kept), _ptr(self.n_kept_dev),
                                        C.cast(self._n_host.data_ptr(), C.POINTER(C.c_int32)), _ptr(self.ws),
                                        self.ws_bytes, _stream()),
                "cf_layer_bwd_lora")
+
+    def run(self, saved: dict, weights: dict, lora: dict, dy: torch.Tensor, mask: torch.Tensor | None) -> int:
+        """run_async, then waits for the stream and returns N_k."""
+        self.run_async(saved, weights, lora, dy, mask)
+        torch.cuda.current_stream().synchronize()
         return int(self._n_host[0])

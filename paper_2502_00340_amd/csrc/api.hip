@@ -322,38 +322,41 @@ LoraWs carve_lora(const cf_layer_desc& L, int rank, int max_kept, void* ws) {
 
 // One adapted projection with input rows x [N,in] and output gradient dy [N,out]:
 // t = scale*dy*b^T (kept for the caller's dX GEMM), db = (scale*x*a)^T*dy, da = x^T*t.
-cf_status lora_proj(int dt, const void* x, const void* dy, const void* a, const void* b, int N, int in,
+cf_status lora_proj(int dt, const void* x, const void* dy, const void* a, const void* b, RowCount rows, int in,
                     int out, int rank, float scale, void* t, void* da, void* db, const LoraWs& w,
                     hipStream_t st) {
+    const int N = rows.n;
+    const int32_t* nd = rows.dev;
     {   // t [N,rank] = scale * dy [N,out] * b [rank,out]^T
         GemmSeg s{dy, b, out};
-        CF_HIP(launch_gemm(dt, 0, &s, 1, t, N, rank, 0.f, st, scale, w.splitk, kSplitKBytes));
+        CF_HIP(launch_gemm(dt, 0, &s, 1, t, N, rank, 0.f, st, scale, w.splitk, kSplitKBytes, false, nd));
     }
     CF_HIP(launch_transpose(dt, a, in, rank, w.a_t, st));
     {   // u [N,rank] = scale * x [N,in] * a_t [rank,in]^T
         GemmSeg s{x, w.a_t, in};
-        CF_HIP(launch_gemm(dt, 0, &s, 1, w.u, N, rank, 0.f, st, scale, w.splitk, kSplitKBytes));
+        CF_HIP(launch_gemm(dt, 0, &s, 1, w.u, N, rank, 0.f, st, scale, w.splitk, kSplitKBytes, false, nd));
     }
     {   // db [rank,out] = u^T * dy
         GemmSeg s{w.u, dy, N};
-        CF_HIP(launch_gemm(dt, 1, &s, 1, db, rank, out, 0.f, st, 1.f, w.splitk, kSplitKBytes));
+        CF_HIP(launch_gemm(dt, 1, &s, 1, db, rank, out, 0.f, st, 1.f, w.splitk, kSplitKBytes, false, nd));
     }
     {   // da [in,rank] = x^T * t
         GemmSeg s{x, t, N};
-        CF_HIP(launch_gemm(dt, 1, &s, 1, da, in, rank, 0.f, st, 1.f, w.splitk, kSplitKBytes));
+        CF_HIP(launch_gemm(dt, 1, &s, 1, da, in, rank, 0.f, st, 1.f, w.splitk, kSplitKBytes, false, nd));
     }
     return CF_OK;
 }
 
 cf_status layer_core_lora(const cf_layer_desc& L, const cf_saved& sv, const cf_weights& W,
                           const cf_lora& A, const void* dy_rows, const int32_t* idx,
-                          const int32_t* cu_kept, int N, cf_lora_grads& G, const LoraWs& lw,
+                          const int32_t* cu_kept, RowCount rows, cf_lora_grads& G, const LoraWs& lw,
                           hipStream_t st) {
     const LayerWs& w = lw.base;
     const int dt = L.dtype;
     const size_t e = dtype_size(dt);
     const int H = L.H, F = L.F, Nq = L.Hq * L.d, Nkv = L.Hkv * L.d, R = A.rank;
-    const RowCount rows{N, nullptr};        // this entry point reads the count back before it launches
+    const int N = rows.n;                   // the live rows, or their upper bound when the count is on the device
+    const int32_t* nd = rows.dev;
     if (N == 0) {
         void* outs[8] = {G.daq, G.dbq, G.dak, G.dbk, G.dav, G.dbv, G.dao, G.dbo};
         size_t sz[8] = {(size_t)H * R, (size_t)R * Nq, (size_t)H * R, (size_t)R * Nkv,
@@ -373,7 +376,7 @@ cf_status layer_core_lora(const cf_layer_desc& L, const cf_saved& sv, const cf_w
     void* d_act = w.bufF1;
     {
         GemmSeg s{dy_rows, W.wd, H};
-        CF_HIP(launch_gemm(dt, 0, &s, 1, d_act, N, F, 0.f, st));
+        CF_HIP(launch_gemm(dt, 0, &s, 1, d_act, N, F, 0.f, st, 1.f, nullptr, 0, false, nd));
     }
     void* d_gate = w.bufF1;
     void* d_up = w.bufF0;
@@ -381,16 +384,16 @@ cf_status layer_core_lora(const cf_layer_desc& L, const cf_saved& sv, const cf_w
     void* dh2 = w.bufHb;
     {
         GemmSeg s[2] = {{d_gate, W.wg, F}, {d_up, W.wu, F}};
-        CF_HIP(launch_gemm(dt, 0, s, 2, dh2, N, H, 0.f, st));
+        CF_HIP(launch_gemm(dt, 0, s, 2, dh2, N, H, 0.f, st, 1.f, nullptr, 0, false, nd));
     }
     CF_HIP(launch_rmsnorm_bwd(dt, dh2, sv.r, W.g2, idx, dy_rows, rows, H, L.rms_eps, w.dr, w.dg_partial,
                               lw.dg_scratch, st));
     // ---- adapted O projection: input a [N,Nq], output gradient dr [N,H]
-    cf_status ps = lora_proj(dt, a_rows, w.dr, A.ao, A.bo, N, Nq, H, R, A.scale, lw.to, G.dao, G.dbo, lw, st);
+    cf_status ps = lora_proj(dt, a_rows, w.dr, A.ao, A.bo, rows, Nq, H, R, A.scale, lw.to, G.dao, G.dbo, lw, st);
     if (ps != CF_OK) return ps;
     {   // da = dr*Wo^T + t_o*a_o^T
         GemmSeg s[2] = {{w.dr, W.wo, H}, {lw.to, A.ao, R}};
-        CF_HIP(launch_gemm(dt, 0, s, 2, w.da, N, Nq, 0.f, st));
+        CF_HIP(launch_gemm(dt, 0, s, 2, w.da, N, Nq, 0.f, st, 1.f, nullptr, 0, false, nd));
     }
     cf_status as = attn_dispatch(L, q_rows, sv.k, sv.v, a_rows, sv.lse, w.da, idx, cu_kept, rows, w.dq,
                                  w.dk, w.dv, w.attn_ws, st);
@@ -402,18 +405,18 @@ cf_status layer_core_lora(const cf_layer_desc& L, const cf_saved& sv, const cf_w
     // ---- adapted Q, K, V projections: input h1 [N,H]
     void* h1 = w.bufHa;
     CF_HIP(launch_rmsnorm_fwd(dt, sv.x, W.g1, idx, rows, H, L.rms_eps, h1, st));
-    ps = lora_proj(dt, h1, w.dq, A.aq, A.bq, N, H, Nq, R, A.scale, lw.tq, G.daq, G.dbq, lw, st);
+    ps = lora_proj(dt, h1, w.dq, A.aq, A.bq, rows, H, Nq, R, A.scale, lw.tq, G.daq, G.dbq, lw, st);
     if (ps != CF_OK) return ps;
-    ps = lora_proj(dt, h1, w.dk, A.ak, A.bk, N, H, Nkv, R, A.scale, lw.tk, G.dak, G.dbk, lw, st);
+    ps = lora_proj(dt, h1, w.dk, A.ak, A.bk, rows, H, Nkv, R, A.scale, lw.tk, G.dak, G.dbk, lw, st);
     if (ps != CF_OK) return ps;
-    ps = lora_proj(dt, h1, w.dv, A.av, A.bv, N, H, Nkv, R, A.scale, lw.tv, G.dav, G.dbv, lw, st);
+    ps = lora_proj(dt, h1, w.dv, A.av, A.bv, rows, H, Nkv, R, A.scale, lw.tv, G.dav, G.dbv, lw, st);
     if (ps != CF_OK) return ps;
     void* dh1 = w.bufHb;
     {   // dh1 = dq*Wq^T + dk*Wk^T + dv*Wv^T, then += t_q*a_q^T + t_k*a_k^T + t_v*a_v^T
         GemmSeg s[3] = {{w.dq, W.wq, Nq}, {w.dk, W.wk, Nkv}, {w.dv, W.wv, Nkv}};
-        CF_HIP(launch_gemm(dt, 0, s, 3, dh1, N, H, 0.f, st));
+        CF_HIP(launch_gemm(dt, 0, s, 3, dh1, N, H, 0.f, st, 1.f, nullptr, 0, false, nd));
         GemmSeg s2[3] = {{lw.tq, A.aq, R}, {lw.tk, A.ak, R}, {lw.tv, A.av, R}};
-        CF_HIP(launch_gemm(dt, 0, s2, 3, dh1, N, H, 1.f, st));
+        CF_HIP(launch_gemm(dt, 0, s2, 3, dh1, N, H, 1.f, st, 1.f, nullptr, 0, false, nd));
     }
     CF_HIP(launch_rmsnorm_bwd(dt, dh1, sv.x, W.g1, idx, w.dr, rows, H, L.rms_eps, G.dx, w.dg_partial,
                               lw.dg_scratch, st));
@@ -676,9 +679,10 @@ size_t cf_lora_workspace_bytes(const cf_layer_desc* desc, int32_t rank, int32_t 
 }
 
 cf_status cf_layer_bwd_lora(const cf_layer_desc* desc, const cf_saved* saved, const cf_weights* w,
-                            const cf_lora* lora, const void* dy_full, const uint8_t* mask,
+                            const cf_lora* lora, const void* dy_full, const uint8_t* mask, int32_t max_kept,
                             cf_lora_grads* grads, int32_t* idx_out, int32_t* cu_kept_out,
-                            int32_t* n_kept_host, void* ws, size_t ws_bytes, cf_stream stream) {
+                            int32_t* n_kept_dev_out, int32_t* n_kept_host, void* ws, size_t ws_bytes,
+                            cf_stream stream) {
     cf_status s = check_layer_desc(desc);
     if (s != CF_OK) return s;
     if (!saved || !w || !lora || !dy_full || !grads) return CF_ERR_NULL;
@@ -699,32 +703,35 @@ cf_status cf_layer_bwd_lora(const cf_layer_desc* desc, const cf_saved* saved, co
     const int mult = desc->dtype == CF_BF16 ? 8 : 4;
     if (lora->rank <= 0 || lora->rank % mult || lora->rank > 1024) return CF_ERR_SHAPE;
     if (!(lora->scale == lora->scale)) return CF_ERR_SHAPE;
-    if (mask && !n_kept_host) return CF_ERR_NULL;
-    if ((idx_out && misaligned(idx_out, 4)) || (cu_kept_out && misaligned(cu_kept_out, 4))) return CF_ERR_SHAPE;
+    if ((idx_out && misaligned(idx_out, 4)) || (cu_kept_out && misaligned(cu_kept_out, 4)) ||
+        (n_kept_dev_out && misaligned(n_kept_dev_out, 4)))
+        return CF_ERR_SHAPE;
     if (!ws || misaligned(ws, 256)) return CF_ERR_WORKSPACE;
     const int T = desc->B * desc->S;
+    if (max_kept < 0) return CF_ERR_SHAPE;
+    if (max_kept == 0 || max_kept > T) max_kept = T;
     hipStream_t st = as_stream(stream);
     if (!mask) {
         LoraWs lw = carve_lora(*desc, lora->rank, T, ws);
         if (ws_bytes < lw.total) return CF_ERR_WORKSPACE;
         if (n_kept_host) *n_kept_host = T;
-        return layer_core_lora(*desc, *saved, *w, *lora, dy_full, nullptr, nullptr, T, *grads, lw, st);
+        return layer_core_lora(*desc, *saved, *w, *lora, dy_full, nullptr, nullptr, RowCount{T, nullptr}, *grads,
+                               lw, st);
     }
-    LoraWs w0 = carve_lora(*desc, lora->rank, 0, ws);
-    if (ws_bytes < w0.total) return CF_ERR_WORKSPACE;
-    int32_t* idx = idx_out ? idx_out : w0.base.idx;
-    int32_t* cu = cu_kept_out ? cu_kept_out : w0.base.cu_kept;
-    CF_HIP(launch_keep_index(mask, desc->B, desc->S, idx, cu, w0.base.n_kept_dev, w0.base.index_ws, st));
-    CF_HIP(hipMemcpyAsync(n_kept_host, w0.base.n_kept_dev, sizeof(int32_t), hipMemcpyDeviceToHost, st));
-    CF_HIP(hipStreamSynchronize(st));
-    const int N = *n_kept_host;
-    if (N < 0 || N > T) return CF_ERR_HIP;
-    LoraWs lw = carve_lora(*desc, lora->rank, N, ws);
+    LoraWs lw = carve_lora(*desc, lora->rank, max_kept, ws);
     if (ws_bytes < lw.total) return CF_ERR_WORKSPACE;
-    if (N > 0)
-        CF_HIP(launch_gather(dy_full, (int64_t)desc->H * dtype_size(desc->dtype), idx, RowCount{N, nullptr},
-                             lw.base.dy_k, st));
-    return layer_core_lora(*desc, *saved, *w, *lora, lw.base.dy_k, idx, cu, N, *grads, lw, st);
+    int32_t* idx = idx_out ? idx_out : lw.base.idx;
+    int32_t* cu = cu_kept_out ? cu_kept_out : lw.base.cu_kept;
+    int32_t* n_dev = n_kept_dev_out ? n_kept_dev_out : lw.base.n_kept_dev;
+    CF_HIP(launch_keep_index(mask, desc->B, desc->S, idx, cu, n_dev, lw.base.index_ws, st));
+    // the count stays on the device, as in cf_layer_bwd_filtered: nothing here waits for the host
+    const RowCount rows{max_kept, n_dev};
+    CF_HIP(launch_gather(dy_full, (int64_t)desc->H * dtype_size(desc->dtype), idx, rows, lw.base.dy_k, st));
+    s = layer_core_lora(*desc, *saved, *w, *lora, lw.base.dy_k, idx, cu, rows, *grads, lw, st);
+    if (s != CF_OK) return s;
+    if (n_kept_host)
+        CF_HIP(hipMemcpyAsync(n_kept_host, n_dev, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    return CF_OK;
 }
 
 }  // extern "C"

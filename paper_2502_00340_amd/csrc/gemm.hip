@@ -857,18 +857,32 @@ __global__ __launch_bounds__(256) void gemm_bf16_splitk_kernel(GemmArgs g, float
     extern __shared__ __align__(16) unsigned char smem[];
     const int tiles_m = (g.M + 127) / 128;
     const int m0 = ((int)blockIdx.x % tiles_m) * 128, n0 = ((int)blockIdx.x / tiles_m) * 128;
+    // a device-side kept-token count bounds M (mode NT) or K (mode TN); the launch was planned for the
+    // host's upper bound, so a block may find its rows or its K range empty: it then stores nothing
+    // (NT; the reduction skips those rows too) or a tile of zeros (TN)
+    int Mx = g.M, Kx = g.K[0];
+    if (g.n_dev != nullptr) {
+        const int n = max(*g.n_dev, 0);
+        if (MODE == 0) Mx = min(Mx, n);
+        else Kx = min(Kx, n);
+    }
     const int kbeg = (int)blockIdx.y * kchunk;
-    const int kend = min(g.K[0], kbeg + kchunk);
+    const int kend = max(kbeg, min(Kx, kbeg + kchunk));
+    if (MODE == 0 && m0 >= Mx) return;
     const TileRef t{m0, n0, g.N, g.B[0], g.C};
-    gemm_tiles<MODE, 2, 2, true, false>(g, g.M, g.K[0], t, [](TileRef&) { return false; }, smem, kbeg, kend,
+    gemm_tiles<MODE, 2, 2, true, false>(g, Mx, Kx, t, [](TileRef&) { return false; }, smem, kbeg, kend,
                                         partial + (int64_t)blockIdx.y * g.M * g.N);
 }
 
 // C[m, n..n+7] = alpha * sum_p partial[p][m, n..n+7] + beta * C
+// rows_dev (nullable): the live number of rows of C on the device (mode NT with a device-side count);
+// rows past it have no partials and are left alone.
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, bf16_t* __restrict__ C,
-                                                            int64_t mn, int parts, float alpha, float beta) {
+                                                            int64_t mn, int parts, float alpha, float beta,
+                                                            const int32_t* __restrict__ rows_dev, int ncols) {
     const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
     if (e >= mn) return;
+    if (rows_dev != nullptr && e >= (int64_t)max(*rows_dev, 0) * ncols) return;
     float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     for (int p = 0; p < parts; ++p) {
         const float4 a = *reinterpret_cast<const float4*>(partial + p * mn + e);
@@ -986,7 +1000,7 @@ static hipError_t launch_bf16_splitk(GemmArgs& g, int parts, int kchunk, float* 
     if (e != hipSuccess) return e;
     const int64_t mn = (int64_t)g.M * g.N;
     splitk_reduce_kernel<<<(unsigned)ceil_div(mn / 8, (int64_t)256), 256, 0, st>>>(
-        partial, static_cast<bf16_t*>(g.C), mn, parts, g.alpha, g.beta);
+        partial, static_cast<bf16_t*>(g.C), mn, parts, g.alpha, g.beta, MODE == 0 ? g.n_dev : nullptr, g.N);
     return hipGetLastError();
 }
 
@@ -1047,7 +1061,7 @@ hipError_t launch_gemm(int dtype, int mode, const GemmSeg* segs, int nseg, void*
         else gemm_f32_kernel<1><<<grid, 256, 0, st>>>(g);
         return hipGetLastError();
     }
-    if (splitk_ws != nullptr && n_dev == nullptr && a_idx == nullptr) {
+    if (splitk_ws != nullptr && a_idx == nullptr) {
         int kchunk = 0;
         const int parts = plan_splitk(g, compute_units(), splitk_bytes, kchunk);
         if (parts >= 2)

@@ -175,14 +175,16 @@ def test_lora_argument_errors(L):
     assert ok_ws > L.cf_layer_workspace_bytes(C.byref(d), 256)
     assert L.cf_lora_workspace_bytes(C.byref(d), 0, 256) == 0
     lo = Bn.Lora(*([0x10000] * 8 + [8, 2.0]))
-    assert f(C.byref(d), C.byref(sv), C.byref(w), None, FAKE, FAKE, C.byref(g), None, None, C.byref(n), FAKE, ok_ws, None) == 1
-    assert f(C.byref(d), C.byref(sv), C.byref(w), C.byref(lo), FAKE, FAKE, C.byref(g), None, None, None, FAKE, ok_ws, None) == 1
+    assert f(C.byref(d), C.byref(sv), C.byref(w), None, FAKE, FAKE, 0, C.byref(g), None, None, None, C.byref(n), FAKE, ok_ws, None) == 1
     lo_bad = Bn.Lora(*([0x10000] * 7 + [0, 8, 2.0]))
-    assert f(C.byref(d), C.byref(sv), C.byref(w), C.byref(lo_bad), FAKE, FAKE, C.byref(g), None, None, C.byref(n), FAKE, ok_ws, None) == 1
+    assert f(C.byref(d), C.byref(sv), C.byref(w), C.byref(lo_bad), FAKE, FAKE, 0, C.byref(g), None, None, None, C.byref(n), FAKE, ok_ws, None) == 1
     lo_rank = Bn.Lora(*([0x10000] * 8 + [6, 2.0]))
-    assert f(C.byref(d), C.byref(sv), C.byref(w), C.byref(lo_rank), FAKE, FAKE, C.byref(g), None, None, C.byref(n), FAKE, ok_ws, None) == 2
-    assert f(C.byref(d), C.byref(sv), C.byref(w), C.byref(lo), FAKE, FAKE, C.byref(g), None, None, C.byref(n), FAKE, 256, None) == 4
-    assert f(C.byref(d), C.byref(sv), C.byref(w), C.byref(lo), FAKE, None, C.byref(g), None, None, None, FAKE, 256, None) == 4
+    assert f(C.byref(d), C.byref(sv), C.byref(w), C.byref(lo_rank), FAKE, FAKE, 0, C.byref(g), None, None, None, C.byref(n), FAKE, ok_ws, None) == 2
+    # a negative bound, a misaligned device count pointer, a workspace that is too small (sized for T when max_kept is 0)
+    assert f(C.byref(d), C.byref(sv), C.byref(w), C.byref(lo), FAKE, FAKE, -1, C.byref(g), None, None, None, C.byref(n), FAKE, ok_ws, None) == 2
+    assert f(C.byref(d), C.byref(sv), C.byref(w), C.byref(lo), FAKE, FAKE, 0, C.byref(g), None, None, C.c_void_p(0x10002), C.byref(n), FAKE, ok_ws, None) == 2
+    assert f(C.byref(d), C.byref(sv), C.byref(w), C.byref(lo), FAKE, FAKE, 256, C.byref(g), None, None, None, C.byref(n), FAKE, 256, None) == 4
+    assert f(C.byref(d), C.byref(sv), C.byref(w), C.byref(lo), FAKE, None, 0, C.byref(g), None, None, None, None, FAKE, 256, None) == 4
 
 
 def test_product_path_does_not_import_the_oracle():

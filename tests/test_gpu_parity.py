@@ -697,3 +697,29 @@ def test_layer_lora(dtype, mode, rank, which):
         say("  " + " ".join("%s=%.1e" % kv for kv in errs.items()))
         bad = {k: v for k, v in errs.items() if not (v <= Hn.TOL[dtype])}
         assert not bad, bad
+        if mask_on:
+            # the same call with the tightest bound (max_kept = N_k): launches and split-K plans are sized
+            # for it instead of for T, the result must meet the same tolerance
+            sv_d, W_d, dy_d, mask_d = p.device_tensors(DEV)
+            lo_d = {k: (Hn.to_dev(v, p.dtype, DEV) if isinstance(v, np.ndarray) else v) for k, v in lora_np.items()}
+            plan.max_kept = n
+            assert plan.run(sv_d, W_d, lo_d, dy_d, mask_d) == n
+            errs = {k: Hn.rel_fro(Hn.to_np(plan.grads[k]), ref[k]) for k in LORA_NAMES}
+            errs["dx"] = Hn.rel_fro(Hn.to_np(plan.grads["dx"][:n]), ref["dx"][ridx])
+            bad = {k: v for k, v in errs.items() if not (v <= Hn.TOL[dtype])}
+            assert not bad, ("tight bound", bad)
+
+
+def test_layer_lora_nothing_kept():
+    """A mask that keeps no token: the count is only known on the device, every adapter gradient must
+    come out zero (the kernels run on empty row and contraction ranges)."""
+    shape = WL.LayerShape("lora0", dtype="bf16", **LORA_SHAPES["splitk"])
+    say("layer lora, empty mask")
+    rng = np.random.default_rng(53)
+    lora_np = {k: (Hn.quantize(v, "bf16") if isinstance(v, np.ndarray) else v)
+               for k, v in WL.make_lora(shape, rng, rank=64, alpha=128.0).items()}
+    p = Hn.Problem(shape, 54, "independent", mask=np.zeros((shape.B, shape.S), np.uint8))
+    plan, n = _run_lora(p, lora_np, 64, True)
+    assert n == 0
+    for k in LORA_NAMES:
+        assert not bool(plan.grads[k].float().abs().max() > 0), k
