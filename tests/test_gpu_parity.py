@@ -371,6 +371,41 @@ def test_layer_with_a_count_known_beforehand_never_synchronises():
     assert torch.equal(plan.grads["dx"][:n], ref.grads["dx"][:n])
 
 
+def test_layer_filtered_call_replays_from_a_captured_graph_with_other_masks():
+    """The filtered call allocates nothing, never synchronises and sizes nothing on the host by the kept
+    count, so it can be captured once into a HIP graph and replayed for ANY mask: every replay (with
+    eager work and synchronisations between them, a different mask, kept count and upstream gradient
+    each time) must give bit for bit what the eager call gives for the same inputs."""
+    shape = SMALL_BF16_GROUPED
+    say("layer graph capture %s" % shape.name)
+    p = Hn.Problem(shape, 71, "independent", rho=0.5)
+    sv, W, dy, mask = p.device_tensors(DEV)
+    ref = Bn.LayerBackward(p.desc(), device=DEV)
+    plan = Bn.LayerBackward(p.desc(), device=DEV)
+    plan.filtered_async(sv, W, dy, mask)        # outside the capture: one-time function attributes
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        plan.filtered_async(sv, W, dy, mask)
+    rng = np.random.default_rng(72)
+    for rep, rho in enumerate((0.5, 0.2, 0.9, 0.0)):
+        new_mask = (rng.random((shape.B, shape.S)) < rho).astype(np.uint8)
+        mask.copy_(torch.from_numpy(new_mask).to(DEV))
+        dy.copy_(Hn.to_dev(Hn.quantize(rng.standard_normal((shape.T, shape.H)), "bf16"), "bf16", DEV))
+        n = ref.filtered(sv, W, dy, mask)       # eager, synchronises
+        assert n == int(new_mask.sum())
+        for t in list(plan.grads.values()) + [plan.idx, plan.cu_kept, plan.n_kept_dev]:
+            t.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        say("  replay %d: n_kept %d" % (rep, n))
+        assert int(plan.n_kept_dev.item()) == n and int(plan._n_host[0]) == n
+        assert torch.equal(plan.idx[:n], ref.idx[:n]) and torch.equal(plan.cu_kept, ref.cu_kept)
+        for name in Hn.GRADS:
+            assert torch.equal(plan.grads[name], ref.grads[name]), (rep, name)
+        assert torch.equal(plan.grads["dx"][:n], ref.grads["dx"][:n]), rep
+
+
 def test_layer_device_side_count_with_a_tight_bound_and_a_stack_without_any_host_read():
     """The filtered call reads N_k on the device.  (1) A workspace and launch bound of exactly N_k
     (max_kept = N_k, the smallest legal one) gives bit for bit what the default bound T gives.
