@@ -244,6 +244,7 @@ def test_attn_bwd_filtered_long_context(S, Hq, Hkv, d, kind):
     # (the launcher wants about two blocks per CU of a 256-CU chip):
     (4, 2048, 16, 4, 64, "topk", 1.0),      # 64 key tiles x 16 heads: two heads per block, two partials per group
     (8, 2048, 8, 4, 128, "spans", 1.0),     # 128 x 8: the whole group of two in one block, no partials
+    (8, 2048, 8, 4, 64, "topk", 1.0),       # the same at d = 64
     (12, 2048, 16, 2, 64, "ragged", 0.8),   # about 154 x 16, ragged sequences: four heads of a group of eight per block
 ])
 def test_attn_bwd_filtered_heads_sharing_a_block(B, S, Hq, Hkv, d, kind, rho):
